@@ -1,0 +1,175 @@
+/*
+ * mace.h - C ABI of the MI355X hybrid-iteration library.
+ *
+ * One hybrid iteration of a pre-norm decoder layer over a mixed token batch: prefill rows,
+ * decode rows (one per request, attending to a paged KV cache) and fine-tune rows (the two
+ * sequences prompt+chosen / prompt+rejected of each preference pair) are processed by the same
+ * launch sequence, followed by the DPO head and the backward pass of the fine-tune rows.  This
+ * is what the executor of the paper's serving loop runs on the GPU for one scheduled bin
+ * (Fig. 1, Section 4, Section 5); the scheduler that forms the bin is not part of this library.
+ *
+ * Conventions
+ *  - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
+ *    host memory.  The library never frees or keeps a caller pointer after a call returns.
+ *  - All device work is enqueued on the `stream` argument (a hipStream_t passed as void*, NULL =
+ *    the default stream).  Calls do not synchronise with the host; outputs are valid once the
+ *    caller has synchronised the stream.
+ *  - Every entry point returns MACE_OK (0) or a negative mace_status_t.  Arguments are validated
+ *    on the host before anything is launched; mace_last_error() returns a message for the last
+ *    failure on the calling thread.  No C++ exception crosses this boundary.
+ *  - Matrices are row-major [out, in].  io_dtype selects the element type of x, the weights, the
+ *    gains and the KV cache: MACE_BF16 (2-byte bfloat16) or MACE_F32.  Internal accumulation is
+ *    fp32; y, all gradients, losses and log-probabilities are fp32.
+ *  - Rows of the token batch are ordered prefill | decode | fine-tune.  Fine-tune sequence 2i is
+ *    prompt+chosen of pair i, 2i+1 is prompt+rejected.
+ */
+#ifndef MACE_H
+#define MACE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MACE_OK = 0,
+  MACE_INVALID_ARG = -1,        /* null pointer, negative count, inconsistent offsets */
+  MACE_BAD_SHAPE = -2,          /* model dimensions the kernels do not support */
+  MACE_WORKSPACE_TOO_SMALL = -3,
+  MACE_HIP_ERROR = -4           /* a HIP runtime call or launch failed */
+} mace_status_t;
+
+enum { MACE_F32 = 0, MACE_BF16 = 1 };
+
+typedef struct mace_ctx *mace_handle_t;
+
+/* Model dimensions.  Constraints (else MACE_BAD_SHAPE): head_dim is 64 or 128; n_q_heads is a
+ * multiple of n_kv_heads; d_model, n_q_heads*head_dim and d_ff are multiples of 64; vocab is a
+ * multiple of 32. */
+typedef struct {
+  int32_t d_model, n_q_heads, n_kv_heads, head_dim, d_ff, vocab;
+  float rms_eps;       /* RMSNorm epsilon */
+  float rope_theta;    /* rotary base; pair (i, i+head_dim/2) rotates by pos * theta^(-2i/head_dim) */
+  int32_t io_dtype;    /* MACE_F32 or MACE_BF16 */
+} mace_model_t;
+
+/* Layer weights, device, io_dtype.  g_attn/g_mlp: RMSNorm gains [d_model].  wq [Hq*hd, d], wk and
+ * wv [Hkv*hd, d], wo [d, Hq*hd], w_gate and w_up [d_ff, d], w_down [d, d_ff]. */
+typedef struct {
+  const void *g_attn, *wq, *wk, *wv, *wo, *g_mlp, *w_gate, *w_up, *w_down;
+} mace_layer_w_t;
+
+/* Gradients of the same tensors, device, fp32, same shapes.  Any pointer may be NULL (skipped). */
+typedef struct {
+  float *g_attn, *wq, *wk, *wv, *wo, *g_mlp, *w_gate, *w_up, *w_down;
+} mace_layer_grads_t;
+
+/* Paged KV cache (the PagedAttention-style cache of Section 5): K and V separately, each
+ * [num_blocks, n_kv_heads, block_size, head_dim] in io_dtype, device.  K rows are stored after
+ * the rotary embedding.  block_size is a power of two (1..256). */
+typedef struct {
+  void *k, *v;
+  int64_t num_blocks;
+  int32_t block_size;
+} mace_kv_cache_t;
+
+/* Batch descriptor of one iteration.  n_tokens = T_p + T_d + T_f with T_d = n_decode. */
+typedef struct {
+  int32_t n_prefill, n_decode, n_ft_seq, n_tokens;
+  const int32_t *seg_offsets_host; /* host   [n_prefill+n_decode+n_ft_seq+1] first row of every request, last = n_tokens */
+  const int32_t *seg_offsets;      /* device copy of the same array */
+  const int32_t *positions;        /* device [n_tokens] rotary position of every row */
+  const int32_t *slot_mapping;     /* device [T_p+T_d] cache slot of every inference row, -1 = do not store */
+  const int32_t *block_tables;     /* device [n_decode, max_blocks_per_req] block ids of the decode requests */
+  const int32_t *context_lens_host;/* host   [n_decode] tokens already cached (the new token is not counted) */
+  const int32_t *context_lens;     /* device copy of the same array */
+  int32_t max_blocks_per_req;
+} mace_batch_t;
+
+/* Create / destroy a handle.  The handle owns a few KB of device tables (rotary frequencies). */
+int mace_create(mace_handle_t *out, const mace_model_t *model);
+void mace_destroy(mace_handle_t h);
+
+/* Message for the last error on this thread ("" if none). */
+const char *mace_last_error(void);
+
+/* Bytes of the buffer that carries fine-tune activations from the forward to the backward pass. */
+size_t mace_fwd_saved_bytes(mace_handle_t h, int32_t n_ft_tokens);
+/* Bytes of scratch the forward, backward and DPO calls need for a batch of these sizes
+ * (n_tokens total rows, n_ft_tokens fine-tune rows, n_decode requests with at most
+ * max_context cached tokens, n_loss_rows response tokens).  One workspace of this size serves
+ * all three calls of an iteration; its contents need not survive between calls. */
+size_t mace_workspace_bytes(mace_handle_t h, int32_t n_tokens, int32_t n_ft_tokens, int32_t n_decode,
+                            int32_t max_context, int32_t n_loss_rows);
+
+/* Host, pure integer: cache slots of positions start_pos .. start_pos+n-1 of one request,
+ * slot(p) = block_table[p / B] * B + p % B (paged cache of Section 5).  table_len entries are
+ * readable; MACE_INVALID_ARG if a position falls outside the table or an entry is negative. */
+int mace_kv_slot_mapping(const int32_t *block_table, int32_t table_len, int32_t block_size,
+                         int32_t start_pos, int32_t n, int32_t *slots_out);
+
+/* Scatter n new rows k_new, v_new [n, Hkv, hd] (device, io_dtype) into the cache at
+ * slot_mapping[n] (device; -1 or out-of-range slots are skipped).  "Only one token is appended
+ * per iteration" per decode request (Section 3.2); prefill appends the whole prompt. */
+int mace_kv_cache_append(mace_handle_t h, mace_kv_cache_t *cache, const void *k_new, const void *v_new,
+                         const int32_t *slot_mapping, int32_t n, void *stream);
+
+/* Gather the rows of positions 0..ctx_len-1 of one request, in order, into k_out, v_out
+ * [ctx_len, Hkv, hd] (device, io_dtype; bit-exact copies).  block_table: device
+ * [ceil(ctx_len/B)].  slots_out: optional device int64 [ctx_len], the slot of every row. */
+int mace_kv_cache_gather(mace_handle_t h, const mace_kv_cache_t *cache, const int32_t *block_table,
+                         int32_t ctx_len, void *k_out, void *v_out, int64_t *slots_out, void *stream);
+
+/* Forward of all rows of the iteration (Fig. 1: prefill, decode and fine-tune work colocated in
+ * one iteration; every row sees the same weights).
+ *   x  device [n_tokens, d_model] io_dtype;  y  device [n_tokens, d_model] fp32.
+ * Prefill and decode rows write their post-rotary K and V to `cache` at slot_mapping; decode
+ * rows attend to context_lens[r] cached tokens plus their own.  Fine-tune rows cache nothing;
+ * their activations go to `saved` (mace_fwd_saved_bytes) for mace_hybrid_layer_bwd.
+ * Fine-tune rows are computed with two-term bf16 operands (about 16 significand bits) so that
+ * the DPO loss meets its 1e-3 tolerance; inference rows use plain bf16 operands. */
+int mace_hybrid_layer_fwd(mace_handle_t h, const mace_layer_w_t *w, const mace_batch_t *batch,
+                          mace_kv_cache_t *cache, const void *x, float *y, void *saved,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/* Backward of the fine-tune rows.  dy_ft device fp32 [T_f, d_model] (dL/dy of the fine-tune rows,
+ * e.g. dh_ft of mace_dpo_logprob_loss); x the same x as in the forward; dx_ft device fp32
+ * [T_f, d_model].  grads: fp32 weight gradients, summed over all fine-tune rows; overwritten, or
+ * added to when accumulate != 0. */
+int mace_hybrid_layer_bwd(mace_handle_t h, const mace_layer_w_t *w, const mace_batch_t *batch,
+                          const void *x, const float *dy_ft, const void *saved, float *dx_ft,
+                          const mace_layer_grads_t *grads, int accumulate,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/* DPO head over the fine-tune rows (Section 3.1).  For sequence s with prompt length P_s and
+ * length L_s, rows t = P_s-1 .. L_s-2 predict token t+1 through a final RMSNorm (gain g_final)
+ * and the tied head w_lm [vocab, d_model]; log pi(y|x) is the sum of those log-probabilities.
+ * Pair i: z = beta * ((logp[2i] - ref_logp[2i]) - (logp[2i+1] - ref_logp[2i+1])),
+ * loss_per_pair[i] = -log sigmoid(z), loss_mean = mean over pairs.
+ *   h_ft            device fp32 [T_f, d_model]  (rows of y of the fine-tune sequences)
+ *   g_final, w_lm   device io_dtype
+ *   token_ids       device int32 [T_f]
+ *   ft_seq_offsets  device and host int32 [n_seq+1], relative to the first fine-tune row
+ *   prompt_lens     device and host int32 [n_seq]; 1 <= P_s <= L_s
+ *   ref_logp        device fp32 [n_seq] (log pi_ref of each sequence, pre-computed)
+ * Outputs (device fp32): logp_out [n_seq]; loss_per_pair [n_pairs]; loss_mean [1];
+ *   clpd_out [n_pairs] = logp[2i]-logp[2i+1] (optional); win_out int32 [n_pairs] = clpd > 0 (optional).
+ * Gradients of loss_mean (all optional, NULL = skipped; if all three are NULL no backward work is
+ * done): dh_ft fp32 [T_f, d_model] (zero on rows that carry no loss), dw_lm fp32 [vocab, d_model]
+ * (head contribution only), dg_final fp32 [d_model]; overwritten, or added to when accumulate != 0
+ * (dh_ft is always overwritten). */
+int mace_dpo_logprob_loss(mace_handle_t h, const float *h_ft, const void *g_final, const void *w_lm,
+                          const int32_t *token_ids, const int32_t *ft_seq_offsets,
+                          const int32_t *ft_seq_offsets_host, const int32_t *prompt_lens,
+                          const int32_t *prompt_lens_host, int32_t n_pairs, const float *ref_logp,
+                          float beta, float *logp_out, float *loss_per_pair, float *loss_mean,
+                          float *clpd_out, int32_t *win_out, float *dh_ft, float *dw_lm,
+                          float *dg_final, int accumulate, void *workspace, size_t workspace_bytes,
+                          void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MACE_H */

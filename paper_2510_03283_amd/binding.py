@@ -1,0 +1,200 @@
+"""ctypes binding of libmace_hip.so: the same entry points as include/mace.h, argument
+marshalling only.  Device buffers are torch tensors (torch is used for memory and streams);
+every step of the path runs inside the library's HIP kernels.  There is no fallback: if the
+library is missing or a call fails, an exception is raised."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmace_hip.so")
+_lib = None
+
+MACE_F32, MACE_BF16 = 0, 1
+
+EXPORTS = [
+    "mace_create", "mace_destroy", "mace_last_error", "mace_fwd_saved_bytes", "mace_workspace_bytes",
+    "mace_kv_slot_mapping", "mace_kv_cache_append", "mace_kv_cache_gather", "mace_hybrid_layer_fwd",
+    "mace_hybrid_layer_bwd", "mace_dpo_logprob_loss",
+]
+
+
+class MaceError(RuntimeError):
+    pass
+
+
+class ModelT(C.Structure):
+    _fields_ = [("d_model", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("d_ff", C.c_int32), ("vocab", C.c_int32), ("rms_eps", C.c_float), ("rope_theta", C.c_float),
+                ("io_dtype", C.c_int32)]
+
+
+class LayerWT(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("g_attn", "wq", "wk", "wv", "wo", "g_mlp", "w_gate", "w_up", "w_down")]
+
+
+class LayerGradsT(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("g_attn", "wq", "wk", "wv", "wo", "g_mlp", "w_gate", "w_up", "w_down")]
+
+
+class KvCacheT(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("num_blocks", C.c_int64), ("block_size", C.c_int32)]
+
+
+class BatchT(C.Structure):
+    _fields_ = [("n_prefill", C.c_int32), ("n_decode", C.c_int32), ("n_ft_seq", C.c_int32), ("n_tokens", C.c_int32),
+                ("seg_offsets_host", C.c_void_p), ("seg_offsets", C.c_void_p), ("positions", C.c_void_p),
+                ("slot_mapping", C.c_void_p), ("block_tables", C.c_void_p), ("context_lens_host", C.c_void_p),
+                ("context_lens", C.c_void_p), ("max_blocks_per_req", C.c_int32)]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load():
+    """Load the HIP library (built in-tree by paper_2510_03283_amd.build); fail loudly if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise MaceError(f"{_LIB_PATH} is missing: build it with `python -m paper_2510_03283_amd.build`")
+    lib = C.CDLL(_LIB_PATH)
+    vp, i32, i64, sz, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t, C.c_float
+    lib.mace_create.argtypes = [C.POINTER(vp), C.POINTER(ModelT)]
+    lib.mace_create.restype = C.c_int
+    lib.mace_destroy.argtypes = [vp]
+    lib.mace_destroy.restype = None
+    lib.mace_last_error.argtypes = []
+    lib.mace_last_error.restype = C.c_char_p
+    lib.mace_fwd_saved_bytes.argtypes = [vp, i32]
+    lib.mace_fwd_saved_bytes.restype = sz
+    lib.mace_workspace_bytes.argtypes = [vp, i32, i32, i32, i32, i32]
+    lib.mace_workspace_bytes.restype = sz
+    lib.mace_kv_slot_mapping.argtypes = [vp, i32, i32, i32, i32, vp]
+    lib.mace_kv_slot_mapping.restype = C.c_int
+    lib.mace_kv_cache_append.argtypes = [vp, C.POINTER(KvCacheT), vp, vp, vp, i32, vp]
+    lib.mace_kv_cache_append.restype = C.c_int
+    lib.mace_kv_cache_gather.argtypes = [vp, C.POINTER(KvCacheT), vp, i32, vp, vp, vp, vp]
+    lib.mace_kv_cache_gather.restype = C.c_int
+    lib.mace_hybrid_layer_fwd.argtypes = [vp, C.POINTER(LayerWT), C.POINTER(BatchT), C.POINTER(KvCacheT), vp, vp, vp, vp, sz, vp]
+    lib.mace_hybrid_layer_fwd.restype = C.c_int
+    lib.mace_hybrid_layer_bwd.argtypes = [vp, C.POINTER(LayerWT), C.POINTER(BatchT), vp, vp, vp, vp, C.POINTER(LayerGradsT), C.c_int, vp, sz, vp]
+    lib.mace_hybrid_layer_bwd.restype = C.c_int
+    lib.mace_dpo_logprob_loss.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, f32, vp, vp, vp, vp, vp, vp, vp, vp, C.c_int, vp, sz, vp]
+    lib.mace_dpo_logprob_loss.restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise MaceError(f"{what} failed ({rc}): {load().mace_last_error().decode()}")
+
+
+def _dev(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device tensors must be contiguous GPU tensors"
+    return C.c_void_p(t.data_ptr())
+
+
+def _host_i32(t):
+    """Host int32 array -> (keep-alive numpy array, pointer)."""
+    import numpy as np
+    a = np.ascontiguousarray(t, dtype=np.int32)
+    return a, C.c_void_p(a.ctypes.data)
+
+
+def _stream(stream=None):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+def mace_create(d_model, n_q_heads, n_kv_heads, head_dim, d_ff, vocab, rms_eps, rope_theta, io_dtype):
+    h = C.c_void_p()
+    m = ModelT(d_model, n_q_heads, n_kv_heads, head_dim, d_ff, vocab, rms_eps, rope_theta, io_dtype)
+    _check(load().mace_create(C.byref(h), C.byref(m)), "mace_create")
+    return h
+
+
+def mace_destroy(h):
+    load().mace_destroy(h)
+
+
+def mace_fwd_saved_bytes(h, n_ft_tokens: int) -> int:
+    return int(load().mace_fwd_saved_bytes(h, n_ft_tokens))
+
+
+def mace_workspace_bytes(h, n_tokens, n_ft_tokens, n_decode, max_context, n_loss_rows) -> int:
+    return int(load().mace_workspace_bytes(h, n_tokens, n_ft_tokens, n_decode, max_context, n_loss_rows))
+
+
+def mace_kv_slot_mapping(block_table, block_size: int, start_pos: int, n: int):
+    """Host-side slot computation; returns a numpy int32 array."""
+    import numpy as np
+    bt, btp = _host_i32(block_table)
+    out = np.empty(n, dtype=np.int32)
+    _check(load().mace_kv_slot_mapping(btp, len(bt), block_size, start_pos, n, C.c_void_p(out.ctypes.data)), "mace_kv_slot_mapping")
+    return out
+
+
+def kv_cache_struct(k: torch.Tensor, v: torch.Tensor, num_blocks: int, block_size: int) -> KvCacheT:
+    return KvCacheT(k.data_ptr(), v.data_ptr(), num_blocks, block_size)
+
+
+def mace_kv_cache_append(h, cache: KvCacheT, k_new, v_new, slot_mapping, n: int, stream=None):
+    _check(load().mace_kv_cache_append(h, C.byref(cache), _dev(k_new), _dev(v_new), _dev(slot_mapping), n, _stream(stream)), "mace_kv_cache_append")
+
+
+def mace_kv_cache_gather(h, cache: KvCacheT, block_table, ctx_len: int, k_out, v_out, slots_out=None, stream=None):
+    _check(load().mace_kv_cache_gather(h, C.byref(cache), _dev(block_table), ctx_len, _dev(k_out), _dev(v_out), _dev(slots_out), _stream(stream)), "mace_kv_cache_gather")
+
+
+def layer_weights_struct(w: dict) -> LayerWT:
+    """w: dict of device tensors keyed g1, wq, wk, wv, wo, g2, wg, wu, wd."""
+    return LayerWT(*[w[k].data_ptr() for k in ("g1", "wq", "wk", "wv", "wo", "g2", "wg", "wu", "wd")])
+
+
+def layer_grads_struct(g: dict) -> LayerGradsT:
+    return LayerGradsT(*[(g[k].data_ptr() if g.get(k) is not None else None) for k in ("g1", "wq", "wk", "wv", "wo", "g2", "wg", "wu", "wd")])
+
+
+class BatchDesc:
+    """Owns the host arrays a mace_batch_t points to, next to the struct itself."""
+
+    def __init__(self, n_prefill, n_decode, n_ft_seq, n_tokens, seg_offsets_host, seg_offsets, positions,
+                 slot_mapping, block_tables, context_lens_host, context_lens, max_blocks_per_req):
+        self._seg, segp = _host_i32(seg_offsets_host)
+        self._ctx, ctxp = _host_i32(context_lens_host)
+        self._keep = (seg_offsets, positions, slot_mapping, block_tables, context_lens)
+        self.struct = BatchT(n_prefill, n_decode, n_ft_seq, n_tokens, segp, _dev(seg_offsets), _dev(positions),
+                             _dev(slot_mapping), _dev(block_tables), ctxp if n_decode else None,
+                             _dev(context_lens), max_blocks_per_req)
+
+
+def mace_hybrid_layer_fwd(h, w: LayerWT, batch: BatchDesc, cache: Optional[KvCacheT], x, y, saved, workspace, stream=None):
+    _check(load().mace_hybrid_layer_fwd(h, C.byref(w), C.byref(batch.struct), C.byref(cache) if cache is not None else None,
+                                        _dev(x), _dev(y), _dev(saved), _dev(workspace), workspace.numel() * workspace.element_size(),
+                                        _stream(stream)), "mace_hybrid_layer_fwd")
+
+
+def mace_hybrid_layer_bwd(h, w: LayerWT, batch: BatchDesc, x, dy_ft, saved, dx_ft, grads: LayerGradsT, accumulate, workspace, stream=None):
+    _check(load().mace_hybrid_layer_bwd(h, C.byref(w), C.byref(batch.struct), _dev(x), _dev(dy_ft), _dev(saved), _dev(dx_ft),
+                                        C.byref(grads), int(accumulate), _dev(workspace), workspace.numel() * workspace.element_size(),
+                                        _stream(stream)), "mace_hybrid_layer_bwd")
+
+
+def mace_dpo_logprob_loss(h, h_ft, g_final, w_lm, token_ids, ft_seq_offsets, ft_seq_offsets_host, prompt_lens, prompt_lens_host,
+                          n_pairs, ref_logp, beta, logp_out, loss_per_pair, loss_mean, clpd_out, win_out, dh_ft, dw_lm, dg_final,
+                          accumulate, workspace, stream=None):
+    so, sop = _host_i32(ft_seq_offsets_host)
+    pl, plp = _host_i32(prompt_lens_host)
+    _check(load().mace_dpo_logprob_loss(h, _dev(h_ft), _dev(g_final), _dev(w_lm), _dev(token_ids), _dev(ft_seq_offsets), sop,
+                                        _dev(prompt_lens), plp, n_pairs, _dev(ref_logp), float(beta), _dev(logp_out),
+                                        _dev(loss_per_pair), _dev(loss_mean), _dev(clpd_out), _dev(win_out), _dev(dh_ft),
+                                        _dev(dw_lm), _dev(dg_final), int(accumulate), _dev(workspace),
+                                        workspace.numel() * workspace.element_size(), _stream(stream)), "mace_dpo_logprob_loss")

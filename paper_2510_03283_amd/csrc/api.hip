@@ -1,0 +1,672 @@
+// C ABI of the hybrid-iteration library: argument validation, workspace layout, launch sequences.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/mace.h"
+#include "gemm.h"
+#include "kernels.h"
+
+struct mace_ctx {
+  mace_model_t m;
+  double *inv_freq;   // device [head_dim/2]
+};
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const std::string &msg) {
+  g_err = msg;
+  return code;
+}
+int hip_fail(hipError_t e, const char *where) {
+  return fail(MACE_HIP_ERROR, std::string(where) + ": " + hipGetErrorString(e));
+}
+#define HIP_TRY(expr, where)                         \
+  do {                                               \
+    hipError_t e__ = (expr);                         \
+    if (e__ != hipSuccess) return hip_fail(e__, where); \
+  } while (0)
+
+// Bump allocator over a caller buffer; with base == nullptr it only measures.
+struct Bump {
+  char *base;
+  size_t off = 0;
+  explicit Bump(void *b) : base((char *)b) {}
+  template <typename T>
+  T *take(size_t n) {
+    off = align_up(off, 256);
+    T *p = base ? (T *)(base + off) : nullptr;
+    off += n * sizeof(T);
+    return p;
+  }
+};
+
+struct Dims {
+  int d, Hq, Hkv, hd, F, V, qd, kd, nqkv;
+  bool bf;
+  explicit Dims(const mace_model_t &m)
+      : d(m.d_model), Hq(m.n_q_heads), Hkv(m.n_kv_heads), hd(m.head_dim), F(m.d_ff), V(m.vocab),
+        qd(m.n_q_heads * m.head_dim), kd(m.n_kv_heads * m.head_dim), nqkv((m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim),
+        bf(m.io_dtype == MACE_BF16) {}
+};
+
+constexpr int DG_PARTS = 512;   // blocks (and partial rows) of the RMSNorm backward
+
+// bf16 (hi, lo) views of the seven weight matrices; for bf16 models hi aliases the caller's weights.
+struct WSplit {
+  const bf16_t *hi[7];
+  bf16_t *lo[7];
+};
+enum { W_Q, W_K, W_V, W_O, W_G, W_U, W_D };
+
+size_t weight_elems(const Dims &D, int i) {
+  switch (i) {
+    case W_Q: return (size_t)D.qd * D.d;
+    case W_K: case W_V: return (size_t)D.kd * D.d;
+    case W_O: return (size_t)D.d * D.qd;
+    default: return (size_t)D.F * D.d;
+  }
+}
+
+// Reserve (and for fp32 models fill) the split weights.  need_lo: the forward uses the lo term.
+int prepare_weights(const Dims &D, const mace_layer_w_t *w, Bump &ws, bool need_lo, bool run, hipStream_t st, WSplit &out) {
+  const void *src[7] = {w ? w->wq : nullptr, w ? w->wk : nullptr, w ? w->wv : nullptr, w ? w->wo : nullptr,
+                        w ? w->w_gate : nullptr, w ? w->w_up : nullptr, w ? w->w_down : nullptr};
+  for (int i = 0; i < 7; ++i) {
+    if (D.bf) {
+      out.hi[i] = (const bf16_t *)src[i];
+      out.lo[i] = nullptr;
+    } else {
+      bf16_t *hi = ws.take<bf16_t>(weight_elems(D, i));
+      bf16_t *lo = need_lo ? ws.take<bf16_t>(weight_elems(D, i)) : nullptr;
+      out.hi[i] = hi;
+      out.lo[i] = lo;
+      if (run) HIP_TRY(launch_split_f32((const float *)src[i], weight_elems(D, i), hi, lo, st), "split weights");
+    }
+  }
+  return MACE_OK;
+}
+
+// ---------------------------------------------------------------- saved activations (ft rows)
+struct Saved {
+  float *rstd1, *rstd2, *lse, *x1, *gu;
+  bf16_t *a, *q, *k, *v, *o, *b;
+};
+Saved plan_saved(const Dims &D, size_t Tf, Bump &s) {
+  Saved S;
+  S.rstd1 = s.take<float>(Tf);
+  S.rstd2 = s.take<float>(Tf);
+  S.lse = s.take<float>(Tf * D.Hq);
+  S.x1 = s.take<float>(Tf * D.d);
+  S.gu = s.take<float>(Tf * 2 * D.F);
+  S.a = s.take<bf16_t>(Tf * D.d);
+  S.q = s.take<bf16_t>(Tf * D.qd);
+  S.k = s.take<bf16_t>(Tf * D.kd);
+  S.v = s.take<bf16_t>(Tf * D.kd);
+  S.o = s.take<bf16_t>(Tf * D.qd);
+  S.b = s.take<bf16_t>(Tf * D.d);
+  return S;
+}
+
+// ---------------------------------------------------------------- forward scratch
+struct FwdWs {
+  // inference rows
+  bf16_t *a_i, *q_i, *k_i, *v_i, *o_i, *b_i, *hm_i;
+  float *qkv_i, *x1_i, *gu_i, *dec_partial;
+  // fine-tune rows
+  float *qkv_f;
+  bf16_t *a_lo, *q_lo, *k_lo, *v_lo, *o_lo, *b_lo, *hm_hi, *hm_lo;
+};
+FwdWs plan_fwd(const Dims &D, size_t Ti, size_t Tf, int n_decode, int max_ctx, Bump &w) {
+  FwdWs F;
+  F.a_i = w.take<bf16_t>(Ti * D.d);
+  F.qkv_i = w.take<float>(Ti * D.nqkv);
+  F.q_i = w.take<bf16_t>(Ti * D.qd);
+  F.k_i = w.take<bf16_t>(Ti * D.kd);
+  F.v_i = w.take<bf16_t>(Ti * D.kd);
+  F.o_i = w.take<bf16_t>(Ti * D.qd);
+  F.x1_i = w.take<float>(Ti * D.d);
+  F.b_i = w.take<bf16_t>(Ti * D.d);
+  F.gu_i = w.take<float>(Ti * 2 * D.F);
+  F.hm_i = w.take<bf16_t>(Ti * D.F);
+  F.dec_partial = w.take<float>(decode_partial_floats(n_decode, D.Hq, D.hd, max_ctx));
+  F.qkv_f = w.take<float>(Tf * D.nqkv);
+  F.a_lo = w.take<bf16_t>(Tf * D.d);
+  F.q_lo = w.take<bf16_t>(Tf * D.qd);
+  F.k_lo = w.take<bf16_t>(Tf * D.kd);
+  F.v_lo = w.take<bf16_t>(Tf * D.kd);
+  F.o_lo = w.take<bf16_t>(Tf * D.qd);
+  F.b_lo = w.take<bf16_t>(Tf * D.d);
+  F.hm_hi = w.take<bf16_t>(Tf * D.F);
+  F.hm_lo = w.take<bf16_t>(Tf * D.F);
+  return F;
+}
+
+// ---------------------------------------------------------------- backward scratch
+struct BwdWs {
+  bf16_t *dy_bf, *dhm, *dgu, *hm, *dx1_bf, *dattn, *dqkv;
+  float *db, *dx1, *dvec, *dq, *dk, *dv, *da, *dg_part;
+};
+BwdWs plan_bwd(const Dims &D, size_t Tf, Bump &w) {
+  BwdWs B;
+  B.dy_bf = w.take<bf16_t>(Tf * D.d);
+  B.dhm = w.take<bf16_t>(Tf * D.F);
+  B.dgu = w.take<bf16_t>(Tf * 2 * D.F);
+  B.hm = w.take<bf16_t>(Tf * D.F);
+  B.db = w.take<float>(Tf * D.d);
+  B.dx1 = w.take<float>(Tf * D.d);
+  B.dx1_bf = w.take<bf16_t>(Tf * D.d);
+  B.dattn = w.take<bf16_t>(Tf * D.qd);
+  B.dvec = w.take<float>(Tf * D.Hq);
+  B.dq = w.take<float>(Tf * D.qd);
+  B.dk = w.take<float>(Tf * D.kd);
+  B.dv = w.take<float>(Tf * D.kd);
+  B.dqkv = w.take<bf16_t>(Tf * D.nqkv);
+  B.da = w.take<float>(Tf * D.d);
+  B.dg_part = w.take<float>((size_t)DG_PARTS * D.d);
+  return B;
+}
+
+// ---------------------------------------------------------------- DPO head scratch
+struct DpoWs {
+  int32_t *row_idx, *label, *seq_id;
+  bf16_t *n_hi, *n_lo, *dl, *e_hi, *e_lo;
+  float *rstd, *logits, *logp_t, *lse, *dlogp, *dn, *dg_part;
+};
+DpoWs plan_dpo(const Dims &D, size_t R, size_t n_seq, Bump &w) {
+  DpoWs P;
+  P.row_idx = w.take<int32_t>(R);
+  P.label = w.take<int32_t>(R);
+  P.seq_id = w.take<int32_t>(R);
+  P.n_hi = w.take<bf16_t>(R * D.d);
+  P.n_lo = w.take<bf16_t>(R * D.d);
+  P.rstd = w.take<float>(R);
+  P.logits = w.take<float>(R * D.V);
+  P.logp_t = w.take<float>(R);
+  P.lse = w.take<float>(R);
+  P.dlogp = w.take<float>(n_seq);
+  P.dl = w.take<bf16_t>(R * D.V);
+  P.dn = w.take<float>(R * D.d);
+  P.dg_part = w.take<float>((size_t)DG_PARTS * D.d);
+  if (!D.bf) {
+    P.e_hi = w.take<bf16_t>((size_t)D.V * D.d);
+    P.e_lo = w.take<bf16_t>((size_t)D.V * D.d);
+  } else {
+    P.e_hi = P.e_lo = nullptr;
+  }
+  return P;
+}
+
+int run_gemm(int LA, int LB, GemmParams &p, hipStream_t st, const char *where) {
+  const char *why = nullptr;
+  hipError_t e = gemm_launch(LA, LB, p, st, &why);
+  if (e != hipSuccess) return fail(why ? MACE_BAD_SHAPE : MACE_HIP_ERROR, std::string(where) + ": " + (why ? why : hipGetErrorString(e)));
+  return MACE_OK;
+}
+#define TRY(expr)                 \
+  do {                            \
+    int rc__ = (expr);            \
+    if (rc__ != MACE_OK) return rc__; \
+  } while (0)
+
+GemmParams gp_init(int K, long long lda, long long ldb, long long ldc) {
+  GemmParams p;
+  memset(&p, 0, sizeof(p));
+  p.K = K; p.lda = lda; p.ldb = ldb; p.ldc = ldc; p.ldr = ldc;
+  return p;
+}
+void gp_group(GemmParams &p, const bf16_t *a_hi, const bf16_t *a_lo, void *c, const void *resid, int M, int npass) {
+  if (M <= 0) return;
+  GemmMGroup &g = p.mg[p.n_mg++];
+  g.a[0] = a_hi; g.a[1] = a_lo; g.c = c; g.resid = resid; g.M = M; g.npass = npass;
+}
+void gp_seg(GemmParams &p, const bf16_t *b_hi, const bf16_t *b_lo, int N, int c_col) {
+  GemmNSeg &s = p.ns[p.n_ns++];
+  s.b[0] = b_hi; s.b[1] = b_lo; s.N = N; s.c_col = c_col;
+}
+
+struct BatchInfo {
+  int Tp, Td, Tf, Ti, T, n_seq_all, max_prefill, max_ft, max_ctx;
+};
+
+int check_batch(const mace_batch_t *b, BatchInfo &I) {
+  if (!b) return fail(MACE_INVALID_ARG, "batch is null");
+  if (b->n_prefill < 0 || b->n_decode < 0 || b->n_ft_seq < 0 || b->n_tokens < 0) return fail(MACE_INVALID_ARG, "negative count in batch");
+  const int ns = b->n_prefill + b->n_decode + b->n_ft_seq;
+  if (!b->seg_offsets_host) return fail(MACE_INVALID_ARG, "seg_offsets_host is null");
+  const int32_t *so = b->seg_offsets_host;
+  if (so[0] != 0 || so[ns] != b->n_tokens) return fail(MACE_INVALID_ARG, "seg_offsets must start at 0 and end at n_tokens");
+  I.max_prefill = I.max_ft = I.max_ctx = 0;
+  for (int i = 0; i < ns; ++i) {
+    const int L = so[i + 1] - so[i];
+    if (L < 0) return fail(MACE_INVALID_ARG, "seg_offsets not non-decreasing");
+    if (i < b->n_prefill) I.max_prefill = L > I.max_prefill ? L : I.max_prefill;
+    else if (i < b->n_prefill + b->n_decode) { if (L != 1) return fail(MACE_INVALID_ARG, "a decode request must have exactly one row"); }
+    else I.max_ft = L > I.max_ft ? L : I.max_ft;
+  }
+  I.Tp = so[b->n_prefill];
+  I.Td = b->n_decode;
+  I.Ti = I.Tp + I.Td;
+  I.T = b->n_tokens;
+  I.Tf = I.T - I.Ti;
+  I.n_seq_all = ns;
+  if (b->n_tokens > 0 && (!b->seg_offsets || !b->positions)) return fail(MACE_INVALID_ARG, "seg_offsets/positions device pointer is null");
+  if (b->n_decode > 0) {
+    if (!b->context_lens_host || !b->context_lens || !b->block_tables) return fail(MACE_INVALID_ARG, "decode descriptors are null");
+    for (int i = 0; i < b->n_decode; ++i) {
+      const int n = b->context_lens_host[i];
+      if (n < 0) return fail(MACE_INVALID_ARG, "negative context length");
+      I.max_ctx = n > I.max_ctx ? n : I.max_ctx;
+    }
+  }
+  return MACE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *mace_last_error(void) { return g_err.c_str(); }
+
+int mace_create(mace_handle_t *out, const mace_model_t *model) {
+  if (!out || !model) return fail(MACE_INVALID_ARG, "mace_create: null argument");
+  const mace_model_t &m = *model;
+  if (m.d_model <= 0 || m.n_q_heads <= 0 || m.n_kv_heads <= 0 || m.d_ff <= 0 || m.vocab <= 0) return fail(MACE_BAD_SHAPE, "non-positive dimension");
+  if (m.head_dim != 64 && m.head_dim != 128) return fail(MACE_BAD_SHAPE, "head_dim must be 64 or 128");
+  if (m.n_q_heads % m.n_kv_heads) return fail(MACE_BAD_SHAPE, "n_q_heads must be a multiple of n_kv_heads");
+  const int grp = m.n_q_heads / m.n_kv_heads;
+  if (grp != 1 && grp != 2 && grp != 4 && grp != 8) return fail(MACE_BAD_SHAPE, "n_q_heads / n_kv_heads must be 1, 2, 4 or 8");
+  if (m.d_model % 64 || m.d_ff % 64 || m.vocab % 64) return fail(MACE_BAD_SHAPE, "d_model, d_ff and vocab must be multiples of 64");
+  if (m.d_model > 8192) return fail(MACE_BAD_SHAPE, "d_model must not exceed 8192");
+  if (m.io_dtype != MACE_F32 && m.io_dtype != MACE_BF16) return fail(MACE_INVALID_ARG, "io_dtype");
+  if (!(m.rms_eps >= 0.f) || !(m.rope_theta > 0.f)) return fail(MACE_INVALID_ARG, "rms_eps / rope_theta");
+  mace_ctx *c = new (std::nothrow) mace_ctx;
+  if (!c) return fail(MACE_HIP_ERROR, "out of host memory");
+  c->m = m;
+  c->inv_freq = nullptr;
+  const int half = m.head_dim / 2;
+  std::vector<double> f(half);
+  for (int i = 0; i < half; ++i) f[i] = std::pow((double)m.rope_theta, -2.0 * i / m.head_dim);
+  hipError_t e = hipMalloc((void **)&c->inv_freq, half * sizeof(double));
+  if (e == hipSuccess) e = hipMemcpy(c->inv_freq, f.data(), half * sizeof(double), hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    if (c->inv_freq) (void)hipFree(c->inv_freq);
+    delete c;
+    return hip_fail(e, "mace_create");
+  }
+  *out = c;
+  return MACE_OK;
+}
+
+void mace_destroy(mace_handle_t h) {
+  if (!h) return;
+  if (h->inv_freq) (void)hipFree(h->inv_freq);
+  delete h;
+}
+
+size_t mace_fwd_saved_bytes(mace_handle_t h, int32_t n_ft_tokens) {
+  if (!h || n_ft_tokens < 0) return 0;
+  Bump b(nullptr);
+  plan_saved(Dims(h->m), (size_t)n_ft_tokens, b);
+  return align_up(b.off, 256);
+}
+
+size_t mace_workspace_bytes(mace_handle_t h, int32_t n_tokens, int32_t n_ft_tokens, int32_t n_decode,
+                            int32_t max_context, int32_t n_loss_rows) {
+  if (!h || n_tokens < 0 || n_ft_tokens < 0 || n_ft_tokens > n_tokens || n_decode < 0 || max_context < 0 || n_loss_rows < 0) return 0;
+  const Dims D(h->m);
+  WSplit ws;
+  Bump f(nullptr), b(nullptr), p(nullptr);
+  prepare_weights(D, nullptr, f, true, false, nullptr, ws);
+  plan_fwd(D, (size_t)(n_tokens - n_ft_tokens), (size_t)n_ft_tokens, n_decode, max_context, f);
+  prepare_weights(D, nullptr, b, false, false, nullptr, ws);
+  plan_bwd(D, (size_t)n_ft_tokens, b);
+  plan_dpo(D, (size_t)n_loss_rows, 1u << 16, p);
+  size_t m = f.off > b.off ? f.off : b.off;
+  m = m > p.off ? m : p.off;
+  return align_up(m, 256) + 256;
+}
+
+int mace_kv_slot_mapping(const int32_t *block_table, int32_t table_len, int32_t block_size, int32_t start_pos, int32_t n,
+                         int32_t *slots_out) {
+  if (!block_table || !slots_out || table_len < 0 || start_pos < 0 || n < 0) return fail(MACE_INVALID_ARG, "mace_kv_slot_mapping: bad argument");
+  if (block_size <= 0 || (block_size & (block_size - 1))) return fail(MACE_INVALID_ARG, "block_size must be a power of two");
+  for (int32_t i = 0; i < n; ++i) {
+    const int64_t p = (int64_t)start_pos + i;
+    const int64_t bi = p / block_size;
+    if (bi >= table_len) return fail(MACE_INVALID_ARG, "position beyond the block table");
+    const int64_t blk = block_table[bi];
+    if (blk < 0) return fail(MACE_INVALID_ARG, "negative block id");
+    const int64_t slot = blk * block_size + p % block_size;
+    if (slot > INT32_MAX) return fail(MACE_INVALID_ARG, "slot does not fit int32");
+    slots_out[i] = (int32_t)slot;
+  }
+  return MACE_OK;
+}
+
+static int check_cache(const mace_kv_cache_t *c) {
+  if (!c || !c->k || !c->v) return fail(MACE_INVALID_ARG, "kv cache is null");
+  if (c->num_blocks <= 0) return fail(MACE_INVALID_ARG, "kv cache has no blocks");
+  if (c->block_size <= 0 || c->block_size > 256 || (c->block_size & (c->block_size - 1))) return fail(MACE_INVALID_ARG, "block_size must be a power of two in 1..256");
+  return MACE_OK;
+}
+
+int mace_kv_cache_append(mace_handle_t h, mace_kv_cache_t *cache, const void *k_new, const void *v_new,
+                         const int32_t *slot_mapping, int32_t n, void *stream) {
+  if (!h) return fail(MACE_INVALID_ARG, "handle is null");
+  TRY(check_cache(cache));
+  if (n < 0 || (n > 0 && (!k_new || !v_new || !slot_mapping))) return fail(MACE_INVALID_ARG, "mace_kv_cache_append: bad argument");
+  const Dims D(h->m);
+  HIP_TRY(launch_kv_append(cache->k, cache->v, D.bf, cache->num_blocks * cache->block_size, cache->block_size, D.Hkv, D.hd, k_new, v_new, slot_mapping, n, (hipStream_t)stream), "kv append");
+  return MACE_OK;
+}
+
+int mace_kv_cache_gather(mace_handle_t h, const mace_kv_cache_t *cache, const int32_t *block_table, int32_t ctx_len,
+                         void *k_out, void *v_out, int64_t *slots_out, void *stream) {
+  if (!h) return fail(MACE_INVALID_ARG, "handle is null");
+  TRY(check_cache(cache));
+  if (ctx_len < 0 || (ctx_len > 0 && (!block_table || !k_out || !v_out))) return fail(MACE_INVALID_ARG, "mace_kv_cache_gather: bad argument");
+  const Dims D(h->m);
+  HIP_TRY(launch_kv_gather(cache->k, cache->v, D.bf, cache->num_blocks, cache->block_size, D.Hkv, D.hd, block_table, ctx_len, k_out, v_out, (long long *)slots_out, (hipStream_t)stream), "kv gather");
+  return MACE_OK;
+}
+
+int mace_hybrid_layer_fwd(mace_handle_t h, const mace_layer_w_t *w, const mace_batch_t *batch, mace_kv_cache_t *cache,
+                          const void *x, float *y, void *saved, void *workspace, size_t workspace_bytes, void *stream) {
+  if (!h || !w || !x || !y) return fail(MACE_INVALID_ARG, "mace_hybrid_layer_fwd: null argument");
+  if (!w->g_attn || !w->wq || !w->wk || !w->wv || !w->wo || !w->g_mlp || !w->w_gate || !w->w_up || !w->w_down) return fail(MACE_INVALID_ARG, "null weight pointer");
+  BatchInfo I;
+  TRY(check_batch(batch, I));
+  const Dims D(h->m);
+  hipStream_t st = (hipStream_t)stream;
+  if (I.T == 0) return MACE_OK;
+  if (I.Ti > 0) {
+    TRY(check_cache(cache));
+    if (!batch->slot_mapping) return fail(MACE_INVALID_ARG, "slot_mapping is null");
+    if (I.Td > 0) {
+      if (batch->max_blocks_per_req <= 0) return fail(MACE_INVALID_ARG, "max_blocks_per_req");
+      if ((long long)I.max_ctx + 1 > (long long)batch->max_blocks_per_req * cache->block_size) return fail(MACE_INVALID_ARG, "context longer than the block table");
+    }
+  }
+  if (I.Tf > 0 && !saved) return fail(MACE_INVALID_ARG, "saved is null");
+  if (!workspace) return fail(MACE_INVALID_ARG, "workspace is null");
+  if (((uintptr_t)workspace & 255) || ((uintptr_t)saved & 255)) return fail(MACE_INVALID_ARG, "workspace/saved must be 256-byte aligned");
+
+  // layout (measure first, then bind)
+  WSplit W;
+  {
+    Bump m(nullptr);
+    WSplit tmp;
+    prepare_weights(D, w, m, true, false, st, tmp);
+    plan_fwd(D, I.Ti, I.Tf, I.Td, I.max_ctx, m);
+    if (m.off > workspace_bytes) return fail(MACE_WORKSPACE_TOO_SMALL, "forward workspace too small");
+  }
+  Bump wsb(workspace), svb(saved);
+  TRY(prepare_weights(D, w, wsb, true, true, st, W));
+  FwdWs F = plan_fwd(D, I.Ti, I.Tf, I.Td, I.max_ctx, wsb);
+  Saved S = plan_saved(D, I.Tf, svb);
+  const int np_ft = D.bf ? 2 : 3;
+  const size_t es = D.bf ? 2 : 4;
+  const char *xb = (const char *)x;
+  const int resid_x = D.bf ? 2 : 1;
+
+  // 1. RMSNorm (attention)
+  HIP_TRY(launch_rmsnorm_fwd(x, D.bf, nullptr, w->g_attn, D.bf, I.Ti, D.d, h->m.rms_eps, F.a_i, nullptr, nullptr, st), "rmsnorm1");
+  HIP_TRY(launch_rmsnorm_fwd(xb + (size_t)I.Ti * D.d * es, D.bf, nullptr, w->g_attn, D.bf, I.Tf, D.d, h->m.rms_eps, S.a, F.a_lo, S.rstd1, st), "rmsnorm1 ft");
+  // 2. QKV projection, all rows in one launch
+  {
+    GemmParams p = gp_init(D.d, D.d, D.d, D.nqkv);
+    gp_group(p, S.a, F.a_lo, F.qkv_f, nullptr, I.Tf, np_ft);
+    gp_group(p, F.a_i, nullptr, F.qkv_i, nullptr, I.Ti, 1);
+    gp_seg(p, W.hi[W_Q], W.lo[W_Q], D.qd, 0);
+    gp_seg(p, W.hi[W_K], W.lo[W_K], D.kd, D.qd);
+    gp_seg(p, W.hi[W_V], W.lo[W_V], D.kd, D.qd + D.kd);
+    TRY(run_gemm(0, 0, p, st, "qkv gemm"));
+  }
+  // 3. RoPE, operand split, KV append of the inference rows
+  if (I.Ti > 0)
+    HIP_TRY(launch_rope_split(F.qkv_i, batch->positions, h->inv_freq, I.Ti, D.Hq, D.Hkv, D.hd, F.q_i, F.k_i, F.v_i, nullptr, nullptr, nullptr,
+                              batch->slot_mapping, cache->k, cache->v, D.bf, cache->num_blocks * cache->block_size, cache->block_size, st), "rope");
+  HIP_TRY(launch_rope_split(F.qkv_f, batch->positions + I.Ti, h->inv_freq, I.Tf, D.Hq, D.Hkv, D.hd, S.q, S.k, S.v, F.q_lo, F.k_lo, F.v_lo,
+                            nullptr, nullptr, nullptr, D.bf, 0, 1, st), "rope ft");
+  // 4. attention: prefill (causal), decode (paged), fine-tune (causal, split operands, LSE kept)
+  HIP_TRY(launch_attn_fwd(F.q_i, F.k_i, F.v_i, nullptr, nullptr, nullptr, batch->seg_offsets, 0, batch->n_prefill, I.max_prefill, D.Hq, D.Hkv, D.hd, F.o_i, nullptr, nullptr, st), "prefill attention");
+  if (I.Td > 0)
+    HIP_TRY(launch_attn_decode(F.q_i + (size_t)I.Tp * D.qd, cache->k, cache->v, D.bf, cache->num_blocks, cache->block_size, batch->block_tables, batch->max_blocks_per_req,
+                               batch->context_lens, I.Td, I.max_ctx, D.Hq, D.Hkv, D.hd, F.dec_partial, F.o_i + (size_t)I.Tp * D.qd, st), "decode attention");
+  HIP_TRY(launch_attn_fwd(S.q, S.k, S.v, F.q_lo, F.k_lo, F.v_lo, batch->seg_offsets + batch->n_prefill + batch->n_decode, I.Ti, batch->n_ft_seq, I.max_ft, D.Hq, D.Hkv, D.hd, S.o, F.o_lo, S.lse, st), "ft attention");
+  // 5. output projection + residual
+  {
+    GemmParams p = gp_init(D.qd, D.qd, D.qd, D.d);
+    p.resid_kind = resid_x; p.ldr = D.d;
+    gp_group(p, S.o, F.o_lo, S.x1, xb + (size_t)I.Ti * D.d * es, I.Tf, np_ft);
+    gp_group(p, F.o_i, nullptr, F.x1_i, x, I.Ti, 1);
+    gp_seg(p, W.hi[W_O], W.lo[W_O], D.d, 0);
+    TRY(run_gemm(0, 0, p, st, "o gemm"));
+  }
+  // 6. RMSNorm (MLP), gate/up projection, SwiGLU, down projection + residual
+  HIP_TRY(launch_rmsnorm_fwd(F.x1_i, false, nullptr, w->g_mlp, D.bf, I.Ti, D.d, h->m.rms_eps, F.b_i, nullptr, nullptr, st), "rmsnorm2");
+  HIP_TRY(launch_rmsnorm_fwd(S.x1, false, nullptr, w->g_mlp, D.bf, I.Tf, D.d, h->m.rms_eps, S.b, F.b_lo, S.rstd2, st), "rmsnorm2 ft");
+  {
+    GemmParams p = gp_init(D.d, D.d, D.d, 2 * D.F);
+    gp_group(p, S.b, F.b_lo, S.gu, nullptr, I.Tf, np_ft);
+    gp_group(p, F.b_i, nullptr, F.gu_i, nullptr, I.Ti, 1);
+    gp_seg(p, W.hi[W_G], W.lo[W_G], D.F, 0);
+    gp_seg(p, W.hi[W_U], W.lo[W_U], D.F, D.F);
+    TRY(run_gemm(0, 0, p, st, "gate/up gemm"));
+  }
+  HIP_TRY(launch_swiglu_fwd(F.gu_i, I.Ti, D.F, F.hm_i, nullptr, st), "swiglu");
+  HIP_TRY(launch_swiglu_fwd(S.gu, I.Tf, D.F, F.hm_hi, F.hm_lo, st), "swiglu ft");
+  {
+    GemmParams p = gp_init(D.F, D.F, D.F, D.d);
+    p.resid_kind = 1; p.ldr = D.d;
+    gp_group(p, F.hm_hi, F.hm_lo, y + (size_t)I.Ti * D.d, S.x1, I.Tf, np_ft);
+    gp_group(p, F.hm_i, nullptr, y, F.x1_i, I.Ti, 1);
+    gp_seg(p, W.hi[W_D], W.lo[W_D], D.d, 0);
+    TRY(run_gemm(0, 0, p, st, "down gemm"));
+  }
+  return MACE_OK;
+}
+
+int mace_hybrid_layer_bwd(mace_handle_t h, const mace_layer_w_t *w, const mace_batch_t *batch, const void *x,
+                          const float *dy_ft, const void *saved, float *dx_ft, const mace_layer_grads_t *grads,
+                          int accumulate, void *workspace, size_t workspace_bytes, void *stream) {
+  if (!h || !w || !x || !dy_ft || !saved || !dx_ft || !grads) return fail(MACE_INVALID_ARG, "mace_hybrid_layer_bwd: null argument");
+  if (!w->g_attn || !w->wq || !w->wk || !w->wv || !w->wo || !w->g_mlp || !w->w_gate || !w->w_up || !w->w_down) return fail(MACE_INVALID_ARG, "null weight pointer");
+  BatchInfo I;
+  TRY(check_batch(batch, I));
+  const Dims D(h->m);
+  hipStream_t st = (hipStream_t)stream;
+  if (I.Tf == 0) return MACE_OK;
+  if (!workspace) return fail(MACE_INVALID_ARG, "workspace is null");
+  if (((uintptr_t)workspace & 255) || ((uintptr_t)saved & 255)) return fail(MACE_INVALID_ARG, "workspace/saved must be 256-byte aligned");
+  {
+    Bump m(nullptr);
+    WSplit tmp;
+    prepare_weights(D, w, m, false, false, st, tmp);
+    plan_bwd(D, I.Tf, m);
+    if (m.off > workspace_bytes) return fail(MACE_WORKSPACE_TOO_SMALL, "backward workspace too small");
+  }
+  Bump wsb(workspace), svb((void *)saved);
+  WSplit W;
+  TRY(prepare_weights(D, w, wsb, false, true, st, W));
+  BwdWs B = plan_bwd(D, I.Tf, wsb);
+  const Saved S = plan_saved(D, I.Tf, svb);
+  const int Tf = I.Tf;
+  const size_t es = D.bf ? 2 : 4;
+  const int acc = accumulate ? 1 : 0;
+  const int n_part = Tf < DG_PARTS ? Tf : DG_PARTS;
+
+  HIP_TRY(launch_split_f32(dy_ft, (size_t)Tf * D.d, B.dy_bf, nullptr, st), "cast dy");
+  // MLP: dHm = dY Wd ; SwiGLU backward ; dWd = dY^T Hm
+  {
+    GemmParams p = gp_init(D.d, D.d, D.F, D.F);
+    p.out_bf16 = 1;
+    gp_group(p, B.dy_bf, nullptr, B.dhm, nullptr, Tf, 1);
+    gp_seg(p, W.hi[W_D], nullptr, D.F, 0);
+    TRY(run_gemm(0, 1, p, st, "dhm gemm"));
+  }
+  HIP_TRY(launch_swiglu_bwd(B.dhm, S.gu, Tf, D.F, B.dgu, B.hm, st), "swiglu bwd");
+  if (grads->w_down) {
+    GemmParams p = gp_init(Tf, D.d, D.F, D.F);
+    p.resid_kind = acc;
+    gp_group(p, B.dy_bf, nullptr, grads->w_down, grads->w_down, D.d, 1);
+    gp_seg(p, B.hm, nullptr, D.F, 0);
+    TRY(run_gemm(1, 1, p, st, "dWd gemm"));
+  }
+  // db = dG Wg + dU Wu ; dWg = dG^T b ; dWu = dU^T b
+  {
+    GemmParams p = gp_init(D.F, 2 * D.F, D.d, D.d);
+    gp_group(p, B.dgu, nullptr, B.db, nullptr, Tf, 1);
+    gp_seg(p, W.hi[W_G], nullptr, D.d, 0);
+    TRY(run_gemm(0, 1, p, st, "db gemm (gate)"));
+    GemmParams p2 = gp_init(D.F, 2 * D.F, D.d, D.d);
+    p2.resid_kind = 1;
+    gp_group(p2, B.dgu + D.F, nullptr, B.db, B.db, Tf, 1);
+    gp_seg(p2, W.hi[W_U], nullptr, D.d, 0);
+    TRY(run_gemm(0, 1, p2, st, "db gemm (up)"));
+  }
+  if (grads->w_gate || grads->w_up) {
+    GemmParams p = gp_init(Tf, 2 * D.F, D.d, D.d);
+    p.resid_kind = acc;
+    if (grads->w_gate) gp_group(p, B.dgu, nullptr, grads->w_gate, grads->w_gate, D.F, 1);
+    if (grads->w_up) gp_group(p, B.dgu + D.F, nullptr, grads->w_up, grads->w_up, D.F, 1);
+    gp_seg(p, S.b, nullptr, D.d, 0);
+    TRY(run_gemm(1, 1, p, st, "dWg/dWu gemm"));
+  }
+  // RMSNorm (MLP) backward: dx1 = dy + ...
+  HIP_TRY(launch_rmsnorm_bwd(B.db, S.x1, false, nullptr, w->g_mlp, D.bf, S.rstd2, dy_ft, Tf, D.d, B.dx1, B.dx1_bf, B.dg_part, n_part, st), "rmsnorm2 bwd");
+  if (grads->g_mlp) HIP_TRY(launch_colsum(B.dg_part, n_part, D.d, grads->g_mlp, acc, st), "dg2");
+  // attention output projection
+  {
+    GemmParams p = gp_init(D.d, D.d, D.qd, D.qd);
+    p.out_bf16 = 1;
+    gp_group(p, B.dx1_bf, nullptr, B.dattn, nullptr, Tf, 1);
+    gp_seg(p, W.hi[W_O], nullptr, D.qd, 0);
+    TRY(run_gemm(0, 1, p, st, "dattn gemm"));
+  }
+  if (grads->wo) {
+    GemmParams p = gp_init(Tf, D.d, D.qd, D.qd);
+    p.resid_kind = acc;
+    gp_group(p, B.dx1_bf, nullptr, grads->wo, grads->wo, D.d, 1);
+    gp_seg(p, S.o, nullptr, D.qd, 0);
+    TRY(run_gemm(1, 1, p, st, "dWo gemm"));
+  }
+  // attention backward, RoPE backward
+  HIP_TRY(launch_attn_bwd(S.q, S.k, S.v, S.o, B.dattn, S.lse, batch->seg_offsets + batch->n_prefill + batch->n_decode, I.Ti, batch->n_ft_seq, I.max_ft, Tf,
+                          D.Hq, D.Hkv, D.hd, B.dvec, B.dq, B.dk, B.dv, st), "attention bwd");
+  HIP_TRY(launch_rope_bwd(B.dq, B.dk, B.dv, batch->positions + I.Ti, h->inv_freq, Tf, D.Hq, D.Hkv, D.hd, B.dqkv, st), "rope bwd");
+  // da = dq Wq + dk Wk + dv Wv ; dWq, dWk, dWv
+  {
+    const bf16_t *as[3] = {B.dqkv, B.dqkv + D.qd, B.dqkv + D.qd + D.kd};
+    const int ks[3] = {D.qd, D.kd, D.kd};
+    const int wi[3] = {W_Q, W_K, W_V};
+    for (int i = 0; i < 3; ++i) {
+      GemmParams p = gp_init(ks[i], D.nqkv, D.d, D.d);
+      p.resid_kind = i ? 1 : 0;
+      gp_group(p, as[i], nullptr, B.da, B.da, Tf, 1);
+      gp_seg(p, W.hi[wi[i]], nullptr, D.d, 0);
+      TRY(run_gemm(0, 1, p, st, "da gemm"));
+    }
+    if (grads->wq || grads->wk || grads->wv) {
+      GemmParams p = gp_init(Tf, D.nqkv, D.d, D.d);
+      p.resid_kind = acc;
+      if (grads->wq) gp_group(p, as[0], nullptr, grads->wq, grads->wq, D.qd, 1);
+      if (grads->wk) gp_group(p, as[1], nullptr, grads->wk, grads->wk, D.kd, 1);
+      if (grads->wv) gp_group(p, as[2], nullptr, grads->wv, grads->wv, D.kd, 1);
+      gp_seg(p, S.a, nullptr, D.d, 0);
+      TRY(run_gemm(1, 1, p, st, "dWqkv gemm"));
+    }
+  }
+  // RMSNorm (attention) backward: dx = dx1 + ...
+  HIP_TRY(launch_rmsnorm_bwd(B.da, (const char *)x + (size_t)I.Ti * D.d * es, D.bf, nullptr, w->g_attn, D.bf, S.rstd1, B.dx1, Tf, D.d, dx_ft, nullptr, B.dg_part, n_part, st), "rmsnorm1 bwd");
+  if (grads->g_attn) HIP_TRY(launch_colsum(B.dg_part, n_part, D.d, grads->g_attn, acc, st), "dg1");
+  return MACE_OK;
+}
+
+int mace_dpo_logprob_loss(mace_handle_t h, const float *h_ft, const void *g_final, const void *w_lm,
+                          const int32_t *token_ids, const int32_t *ft_seq_offsets, const int32_t *ft_seq_offsets_host,
+                          const int32_t *prompt_lens, const int32_t *prompt_lens_host, int32_t n_pairs,
+                          const float *ref_logp, float beta, float *logp_out, float *loss_per_pair, float *loss_mean,
+                          float *clpd_out, int32_t *win_out, float *dh_ft, float *dw_lm, float *dg_final, int accumulate,
+                          void *workspace, size_t workspace_bytes, void *stream) {
+  if (!h || !h_ft || !g_final || !w_lm || !token_ids || !ft_seq_offsets || !ft_seq_offsets_host || !prompt_lens || !prompt_lens_host ||
+      !ref_logp || !logp_out || !loss_per_pair || !loss_mean)
+    return fail(MACE_INVALID_ARG, "mace_dpo_logprob_loss: null argument");
+  if (n_pairs <= 0 || n_pairs > 32767) return fail(MACE_INVALID_ARG, "n_pairs must be in 1..32767");
+  if (!std::isfinite(beta)) return fail(MACE_INVALID_ARG, "beta");
+  const Dims D(h->m);
+  const int n_seq = 2 * n_pairs;
+  if (ft_seq_offsets_host[0] != 0) return fail(MACE_INVALID_ARG, "ft_seq_offsets must start at 0");
+  long long R = 0;
+  for (int s = 0; s < n_seq; ++s) {
+    const int L = ft_seq_offsets_host[s + 1] - ft_seq_offsets_host[s], P = prompt_lens_host[s];
+    if (L < 1 || P < 1 || P > L) return fail(MACE_INVALID_ARG, "need 1 <= prompt_len <= sequence length");
+    R += L - P;
+  }
+  if (R > INT32_MAX / 2) return fail(MACE_INVALID_ARG, "too many loss rows");
+  const int Tf = ft_seq_offsets_host[n_seq];
+  if (!workspace || ((uintptr_t)workspace & 255)) return fail(MACE_INVALID_ARG, "workspace must be non-null and 256-byte aligned");
+  {
+    Bump m(nullptr);
+    plan_dpo(D, (size_t)R, n_seq, m);
+    if (m.off > workspace_bytes) return fail(MACE_WORKSPACE_TOO_SMALL, "DPO workspace too small");
+  }
+  hipStream_t st = (hipStream_t)stream;
+  Bump wsb(workspace);
+  DpoWs P = plan_dpo(D, (size_t)R, n_seq, wsb);
+  const bf16_t *e_hi = (const bf16_t *)w_lm, *e_lo = nullptr;
+  if (!D.bf) {
+    HIP_TRY(launch_split_f32((const float *)w_lm, (size_t)D.V * D.d, P.e_hi, P.e_lo, st), "split head");
+    e_hi = P.e_hi; e_lo = P.e_lo;
+  }
+  const int Ri = (int)R;
+  const bool want_grad = dh_ft || dw_lm || dg_final;
+  if (Ri > 0) {
+    HIP_TRY(launch_loss_rows(ft_seq_offsets, prompt_lens, token_ids, n_seq, P.row_idx, P.label, P.seq_id, st), "loss rows");
+    HIP_TRY(launch_rmsnorm_fwd(h_ft, false, P.row_idx, g_final, D.bf, Ri, D.d, h->m.rms_eps, P.n_hi, P.n_lo, P.rstd, st), "final rmsnorm");
+    GemmParams p = gp_init(D.d, D.d, D.d, D.V);
+    gp_group(p, P.n_hi, P.n_lo, P.logits, nullptr, Ri, D.bf ? 2 : 3);
+    gp_seg(p, e_hi, e_lo, D.V, 0);
+    TRY(run_gemm(0, 0, p, st, "lm head gemm"));
+    HIP_TRY(launch_logsoftmax_gather(P.logits, Ri, D.V, P.label, P.logp_t, P.lse, st), "log-softmax");
+  }
+  HIP_TRY(launch_dpo_pairs(P.logp_t, ft_seq_offsets, prompt_lens, n_seq, ref_logp, beta, logp_out, loss_per_pair, loss_mean, clpd_out, win_out, P.dlogp, st), "dpo pairs");
+  if (!want_grad) return MACE_OK;
+  const int acc = accumulate ? 1 : 0;
+  if (dh_ft) HIP_TRY(launch_fill_f32(dh_ft, (size_t)Tf * D.d, 0.f, st), "zero dh");
+  if (Ri == 0) {
+    if (!acc) {
+      if (dw_lm) HIP_TRY(launch_fill_f32(dw_lm, (size_t)D.V * D.d, 0.f, st), "zero dE");
+      if (dg_final) HIP_TRY(launch_fill_f32(dg_final, (size_t)D.d, 0.f, st), "zero dg");
+    }
+    return MACE_OK;
+  }
+  HIP_TRY(launch_dlogits(P.logits, Ri, D.V, P.label, P.seq_id, P.lse, P.dlogp, P.dl, st), "dlogits");
+  if (dw_lm) {
+    GemmParams p = gp_init(Ri, D.V, D.d, D.d);
+    p.resid_kind = acc;
+    gp_group(p, P.dl, nullptr, dw_lm, dw_lm, D.V, 1);
+    gp_seg(p, P.n_hi, nullptr, D.d, 0);
+    TRY(run_gemm(1, 1, p, st, "dE gemm"));
+  }
+  if (dh_ft || dg_final) {
+    GemmParams p = gp_init(D.V, D.V, D.d, D.d);
+    gp_group(p, P.dl, nullptr, P.dn, nullptr, Ri, 1);
+    gp_seg(p, e_hi, nullptr, D.d, 0);
+    TRY(run_gemm(0, 1, p, st, "dn gemm"));
+    const int n_part = Ri < DG_PARTS ? Ri : DG_PARTS;
+    // without dh_ft the row gradients still have to land somewhere: reuse the logits buffer
+    float *dx_dst = dh_ft ? dh_ft : P.logits;
+    if (!dh_ft && (size_t)Tf * D.d > (size_t)Ri * D.V) return fail(MACE_INVALID_ARG, "dg_final without dh_ft needs T_f*d <= R*V");
+    HIP_TRY(launch_rmsnorm_bwd(P.dn, h_ft, false, P.row_idx, g_final, D.bf, P.rstd, nullptr, Ri, D.d, dx_dst, nullptr, P.dg_part, n_part, st), "final rmsnorm bwd");
+    if (dg_final) HIP_TRY(launch_colsum(P.dg_part, n_part, D.d, dg_final, acc, st), "dg_final");
+  }
+  return MACE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,229 @@
+// Decode attention: one query row per request against its paged context, HBM-bound.
+//
+// Split-KV: grid (split, request, kv head); a block streams CHUNK tokens of one (request, kv head)
+// once, for all query heads of the GQA group, with 16-byte loads per lane (a token row of hd
+// elements is covered by hd/8 consecutive lanes, so a wave load touches whole token rows that
+// are contiguous inside a cache block).  Every lane keeps its own online soft-max state over the
+// tokens it sees; states are merged across lanes, waves and finally splits.
+#include "kernels.h"
+
+namespace {
+
+constexpr int CHUNK = 512;   // tokens per block
+constexpr int UNR = 4;       // token loads in flight per lane for K and for V
+
+struct Sm { float m, l; };
+
+__device__ __forceinline__ float safe_scale(float m_old, float m_new) {
+  return m_old == -INFINITY ? 0.f : exp2f(m_old - m_new);
+}
+
+template <bool CBF>
+__device__ __forceinline__ void ld8(const void *base, long long off, float v[8]) {
+  if constexpr (CBF) {
+    const uint4 u = *(const uint4 *)((const bf16_t *)base + off);
+    v[0] = __uint_as_float(u.x << 16); v[1] = __uint_as_float(u.x & 0xffff0000u);
+    v[2] = __uint_as_float(u.y << 16); v[3] = __uint_as_float(u.y & 0xffff0000u);
+    v[4] = __uint_as_float(u.z << 16); v[5] = __uint_as_float(u.z & 0xffff0000u);
+    v[6] = __uint_as_float(u.w << 16); v[7] = __uint_as_float(u.w & 0xffff0000u);
+  } else {
+    const float4 a = *(const float4 *)((const float *)base + off), b = *(const float4 *)((const float *)base + off + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
+}
+
+template <int HD, int GRP, bool CBF>
+__global__ __launch_bounds__(256) void attn_decode_kernel(const bf16_t *__restrict__ q, const void *__restrict__ ck,
+                                                          const void *__restrict__ cv, long long num_blocks, int B,
+                                                          int bshift, const int32_t *__restrict__ block_tables,
+                                                          int max_blocks, const int32_t *__restrict__ ctx_lens, int Hq,
+                                                          int Hkv, int nsplit, float *__restrict__ partial) {
+  constexpr int LPT = HD / 8;          // lanes per token row
+  constexpr int TPL = 64 / LPT;        // tokens per wave-wide load
+  __shared__ float sm[4][GRP][HD + 2];
+  const int split = blockIdx.x, req = blockIdx.y, kvh = blockIdx.z;
+  const int n_tot = ctx_lens[req] + 1;                    // cached context plus the new token
+  const int c0 = split * CHUNK;
+  if (c0 >= n_tot) return;
+  const int c1 = min(n_tot, c0 + CHUNK);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int e0 = (lane % LPT) * 8, tl = lane / LPT;
+  const float sc = 1.4426950408889634f / sqrtf((float)HD);
+
+  float qv[GRP][8];
+#pragma unroll
+  for (int gi = 0; gi < GRP; ++gi) {
+    const uint4 u = *(const uint4 *)(q + (size_t)req * Hq * HD + (size_t)(kvh * GRP + gi) * HD + e0);
+    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      qv[gi][2 * e] = __uint_as_float(w[e] << 16) * sc;
+      qv[gi][2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u) * sc;
+    }
+  }
+  float m[GRP], l[GRP], acc[GRP][8];
+#pragma unroll
+  for (int gi = 0; gi < GRP; ++gi) {
+    m[gi] = -INFINITY; l[gi] = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[gi][e] = 0.f;
+  }
+
+  const int32_t *bt = block_tables + (size_t)req * max_blocks;
+  const int wbeg = c0 + wave * (CHUNK / 4), wend = min(c1, wbeg + CHUNK / 4);
+  for (int tb = wbeg; tb < wend; tb += UNR * TPL) {
+    long long off[UNR];
+    bool ok[UNR];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const int t = tb + u * TPL + tl;
+      ok[u] = t < wend;
+      long long blk = 0;
+      if (ok[u]) {
+        blk = bt[t >> bshift];
+        ok[u] = blk >= 0 && blk < num_blocks;      // a bad table entry is ignored, never dereferenced
+      }
+      off[u] = ok[u] ? ((blk * Hkv + kvh) * B + (t & (B - 1))) * (long long)HD + e0 : 0;
+    }
+    float kf[UNR][8], vf[UNR][8];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) ld8<CBF>(ck, off[u], kf[u]);
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) ld8<CBF>(cv, off[u], vf[u]);
+#pragma unroll
+    for (int gi = 0; gi < GRP; ++gi) {
+      float sv[UNR];
+      float mx = m[gi];
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) {
+        float d = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) d += kf[u][e] * qv[gi][e];
+#pragma unroll
+        for (int o = 1; o < LPT; o <<= 1) d += __shfl_xor(d, o, 64);
+        sv[u] = ok[u] ? d : -INFINITY;
+        mx = fmaxf(mx, sv[u]);
+      }
+      if (mx == -INFINITY) continue;                // nothing valid seen yet by this lane group
+      const float alpha = safe_scale(m[gi], mx);
+      m[gi] = mx;
+      l[gi] *= alpha;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[gi][e] *= alpha;
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) {
+        const float p = exp2f(sv[u] - mx);          // exp2(-inf) = 0 for ignored tokens
+        l[gi] += p;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[gi][e] += p * vf[u][e];
+      }
+    }
+  }
+
+  // merge the TPL lane groups of the wave (lanes with equal e0)
+#pragma unroll
+  for (int gi = 0; gi < GRP; ++gi) {
+#pragma unroll
+    for (int o = LPT; o < 64; o <<= 1) {
+      const float m2 = __shfl_xor(m[gi], o, 64), l2 = __shfl_xor(l[gi], o, 64);
+      const float mn = fmaxf(m[gi], m2);
+      const float a1 = safe_scale(m[gi], mn), a2 = safe_scale(m2, mn);
+      l[gi] = l[gi] * a1 + l2 * a2;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[gi][e] = acc[gi][e] * a1 + __shfl_xor(acc[gi][e], o, 64) * a2;
+      m[gi] = mn;
+    }
+    if (lane < LPT) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sm[wave][gi][e0 + e] = acc[gi][e];
+      if (lane == 0) { sm[wave][gi][HD] = m[gi]; sm[wave][gi][HD + 1] = l[gi]; }
+    }
+  }
+  __syncthreads();
+  // merge the 4 waves; thread t handles (gi, e) pairs
+  for (int idx = tid; idx < GRP * HD; idx += 256) {
+    const int gi = idx / HD, e = idx - gi * HD;
+    float mn = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) mn = fmaxf(mn, sm[w][gi][HD]);
+    float lo = 0.f, ao = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float a = safe_scale(sm[w][gi][HD], mn);
+      lo += sm[w][gi][HD + 1] * a;
+      ao += sm[w][gi][e] * a;
+    }
+    float *dst = partial + (((size_t)req * Hq + (kvh * GRP + gi)) * nsplit + split) * (HD + 2);
+    dst[e] = ao;
+    if (e == 0) { dst[HD] = mn; dst[HD + 1] = lo; }
+  }
+}
+
+template <int HD>
+__global__ __launch_bounds__(HD) void attn_decode_combine_kernel(const float *__restrict__ partial,
+                                                                 const int32_t *__restrict__ ctx_lens, int Hq, int nsplit,
+                                                                 bf16_t *__restrict__ out) {
+  const int req = blockIdx.x, h = blockIdx.y, e = threadIdx.x;
+  const int ns = min(nsplit, (ctx_lens[req] + 1 + CHUNK - 1) / CHUNK);
+  const float *src = partial + ((size_t)req * Hq + h) * nsplit * (HD + 2);
+  float mn = -INFINITY;
+  for (int s = 0; s < ns; ++s) mn = fmaxf(mn, src[s * (HD + 2) + HD]);
+  float lo = 0.f, ao = 0.f;
+  for (int s = 0; s < ns; ++s) {
+    const float a = safe_scale(src[s * (HD + 2) + HD], mn);
+    lo += src[s * (HD + 2) + HD + 1] * a;
+    ao += src[s * (HD + 2) + e] * a;
+  }
+  out[((size_t)req * Hq + h) * HD + e] = f2bf(lo > 0.f ? ao / lo : 0.f);
+}
+
+template <int HD, int GRP, bool CBF>
+void launch_main(const bf16_t *q, const void *ck, const void *cv, long long num_blocks, int B, int bshift,
+                 const int32_t *bt, int max_blocks, const int32_t *ctx, int n_decode, int Hq, int Hkv, int nsplit,
+                 float *partial, hipStream_t st) {
+  hipLaunchKernelGGL((attn_decode_kernel<HD, GRP, CBF>), dim3(nsplit, n_decode, Hkv), dim3(256), 0, st, q, ck, cv, num_blocks, B, bshift, bt, max_blocks, ctx, Hq, Hkv, nsplit, partial);
+}
+
+template <int HD, bool CBF>
+bool launch_grp(int grp, const bf16_t *q, const void *ck, const void *cv, long long num_blocks, int B, int bshift,
+                const int32_t *bt, int max_blocks, const int32_t *ctx, int n_decode, int Hq, int Hkv, int nsplit,
+                float *partial, hipStream_t st) {
+  switch (grp) {
+    case 1: launch_main<HD, 1, CBF>(q, ck, cv, num_blocks, B, bshift, bt, max_blocks, ctx, n_decode, Hq, Hkv, nsplit, partial, st); return true;
+    case 2: launch_main<HD, 2, CBF>(q, ck, cv, num_blocks, B, bshift, bt, max_blocks, ctx, n_decode, Hq, Hkv, nsplit, partial, st); return true;
+    case 4: launch_main<HD, 4, CBF>(q, ck, cv, num_blocks, B, bshift, bt, max_blocks, ctx, n_decode, Hq, Hkv, nsplit, partial, st); return true;
+    case 8: launch_main<HD, 8, CBF>(q, ck, cv, num_blocks, B, bshift, bt, max_blocks, ctx, n_decode, Hq, Hkv, nsplit, partial, st); return true;
+    default: return false;
+  }
+}
+
+}  // namespace
+
+size_t decode_partial_floats(int n_decode, int Hq, int hd, int max_context) {
+  const size_t nsplit = (size_t)cdiv(max_context + 1, CHUNK);
+  return (size_t)n_decode * Hq * nsplit * (hd + 2);
+}
+
+hipError_t launch_attn_decode(const bf16_t *q, const void *cache_k, const void *cache_v, bool cache_bf16,
+                              long long num_blocks, int block_size, const int32_t *block_tables, int max_blocks_per_req,
+                              const int32_t *ctx_lens, int n_decode, int max_context, int Hq, int Hkv, int hd,
+                              float *partial, bf16_t *out, hipStream_t st) {
+  if (n_decode <= 0) return hipSuccess;
+  if (n_decode > 65535 || Hkv > 65535 || Hq > 65535) return hipErrorInvalidValue;
+  int bshift = 0;
+  while ((1 << bshift) < block_size) ++bshift;
+  if ((1 << bshift) != block_size) return hipErrorInvalidValue;
+  const int nsplit = cdiv(max_context + 1, CHUNK);
+  const int grp = Hq / Hkv;
+  bool ok = false;
+  if (hd == 64) ok = cache_bf16 ? launch_grp<64, true>(grp, q, cache_k, cache_v, num_blocks, block_size, bshift, block_tables, max_blocks_per_req, ctx_lens, n_decode, Hq, Hkv, nsplit, partial, st)
+                                : launch_grp<64, false>(grp, q, cache_k, cache_v, num_blocks, block_size, bshift, block_tables, max_blocks_per_req, ctx_lens, n_decode, Hq, Hkv, nsplit, partial, st);
+  else if (hd == 128) ok = cache_bf16 ? launch_grp<128, true>(grp, q, cache_k, cache_v, num_blocks, block_size, bshift, block_tables, max_blocks_per_req, ctx_lens, n_decode, Hq, Hkv, nsplit, partial, st)
+                                      : launch_grp<128, false>(grp, q, cache_k, cache_v, num_blocks, block_size, bshift, block_tables, max_blocks_per_req, ctx_lens, n_decode, Hq, Hkv, nsplit, partial, st);
+  if (!ok) return hipErrorInvalidValue;
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (hd == 64) hipLaunchKernelGGL((attn_decode_combine_kernel<64>), dim3(n_decode, Hq), dim3(64), 0, st, partial, ctx_lens, Hq, nsplit, out);
+  else hipLaunchKernelGGL((attn_decode_combine_kernel<128>), dim3(n_decode, Hq), dim3(128), 0, st, partial, ctx_lens, Hq, nsplit, out);
+  return hipGetLastError();
+}

@@ -1,0 +1,146 @@
+// DPO head kernels (Section 3.1 of the paper): loss-row bookkeeping, vocabulary log-soft-max with
+// label gather, per-sequence sums, pairwise sigmoid loss and the gradient of the logits.
+#include "kernels.h"
+
+namespace {
+
+// One block per fine-tune sequence.  Loss rows of sequence s are t = P_s-1 .. L_s-2; their
+// position in the packed list is the sum of (L_i - P_i) over the sequences before s.
+__global__ __launch_bounds__(256) void loss_rows_kernel(const int32_t *ft_seq_offsets, const int32_t *prompt_lens,
+                                                        const int32_t *token_ids, int32_t *row_idx, int32_t *label,
+                                                        int32_t *seq_id) {
+  const int s = blockIdx.x;
+  int base = 0;
+  for (int i = 0; i < s; ++i) base += (ft_seq_offsets[i + 1] - ft_seq_offsets[i]) - prompt_lens[i];
+  const int o = ft_seq_offsets[s], L = ft_seq_offsets[s + 1] - o, P = prompt_lens[s];
+  for (int i = threadIdx.x; i < L - P; i += 256) {
+    const int t = P - 1 + i;
+    row_idx[base + i] = o + t;
+    label[base + i] = token_ids[o + t + 1];
+    seq_id[base + i] = s;
+  }
+}
+
+// One block per loss row: single pass over the V logits with an online (max, sum) pair.
+__global__ __launch_bounds__(256) void logsoftmax_gather_kernel(const float *__restrict__ logits, int V,
+                                                                const int32_t *__restrict__ label,
+                                                                float *__restrict__ logp_t, float *__restrict__ lse) {
+  __shared__ float red[4];
+  const int r = blockIdx.x;
+  const float *row = logits + (size_t)r * V;
+  float m = -INFINITY, s = 0.f;
+  for (int k = 4 * threadIdx.x; k < V; k += 1024) {       // V % 4 == 0
+    const float4 v = *(const float4 *)(row + k);
+    const float mx = fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w));
+    if (mx > m) { s *= expf(m - mx); m = mx; }
+    s += expf(v.x - m) + expf(v.y - m) + expf(v.z - m) + expf(v.w - m);
+  }
+  const float mb = block_max<256>(m, red);
+  s = (m == -INFINITY) ? 0.f : s * expf(m - mb);
+  const float sb = block_sum<256>(s, red);
+  if (threadIdx.x == 0) {
+    const float l = mb + logf(sb);
+    lse[r] = l;
+    const int lab = label[r];
+    logp_t[r] = (lab >= 0 && lab < V ? row[lab] : 0.f) - l;
+  }
+}
+
+// Single block.  Sequence sums in fp64 (fixed order, deterministic), then the pair terms:
+// z = beta((logp+ - ref+) - (logp- - ref-)), loss = softplus(-z), dloss_mean/dlogp+ = (sigmoid(z)-1) beta / n_pairs.
+__global__ __launch_bounds__(256) void dpo_pairs_kernel(const float *__restrict__ logp_t, const int32_t *ft_seq_offsets,
+                                                        const int32_t *prompt_lens, int n_seq, const float *ref_logp,
+                                                        float beta, float *logp_out, float *loss_per_pair,
+                                                        float *loss_mean, float *clpd, int32_t *win, float *dlogp) {
+  __shared__ double part[256];
+  __shared__ double seqsum[2];
+  __shared__ double total;
+  const int n_pairs = n_seq / 2;
+  if (threadIdx.x == 0) total = 0.0;
+  int base = 0;
+  for (int pr = 0; pr < n_pairs; ++pr) {
+    for (int q = 0; q < 2; ++q) {
+      const int s = 2 * pr + q;
+      const int n = (ft_seq_offsets[s + 1] - ft_seq_offsets[s]) - prompt_lens[s];
+      double a = 0.0;
+      for (int i = threadIdx.x; i < n; i += 256) a += (double)logp_t[base + i];
+      part[threadIdx.x] = a;
+      __syncthreads();
+      for (int o = 128; o > 0; o >>= 1) {
+        if (threadIdx.x < o) part[threadIdx.x] += part[threadIdx.x + o];
+        __syncthreads();
+      }
+      if (threadIdx.x == 0) seqsum[q] = part[0];
+      __syncthreads();
+      base += n;
+    }
+    if (threadIdx.x == 0) {
+      const double lp = seqsum[0], lm = seqsum[1];
+      const double z = (double)beta * ((lp - (double)ref_logp[2 * pr]) - (lm - (double)ref_logp[2 * pr + 1]));
+      const double loss = fmax(-z, 0.0) + log1p(exp(-fabs(z)));
+      const double sig = 1.0 / (1.0 + exp(-z));
+      const double c = (sig - 1.0) * (double)beta / (double)n_pairs;
+      logp_out[2 * pr] = (float)lp;
+      logp_out[2 * pr + 1] = (float)lm;
+      loss_per_pair[pr] = (float)loss;
+      if (clpd) clpd[pr] = (float)(lp - lm);
+      if (win) win[pr] = (lp - lm) > 0.0 ? 1 : 0;
+      dlogp[2 * pr] = (float)c;
+      dlogp[2 * pr + 1] = (float)(-c);
+      total += loss;
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *loss_mean = n_pairs > 0 ? (float)(total / (double)n_pairs) : 0.f;
+}
+
+__global__ __launch_bounds__(256) void dlogits_kernel(const float *__restrict__ logits, int V,
+                                                      const int32_t *__restrict__ label,
+                                                      const int32_t *__restrict__ seq_id, const float *__restrict__ lse,
+                                                      const float *__restrict__ dlogp, bf16_t *__restrict__ dl) {
+  const int r = blockIdx.x;
+  const float c = dlogp[seq_id[r]], l = lse[r];
+  const int lab = label[r];
+  const float *row = logits + (size_t)r * V;
+  bf16_t *out = dl + (size_t)r * V;
+  for (int k = 4 * threadIdx.x; k < V; k += 1024) {
+    const float4 v = *(const float4 *)(row + k);
+    float o[4] = {-expf(v.x - l), -expf(v.y - l), -expf(v.z - l), -expf(v.w - l)};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (k + j == lab) o[j] += 1.0f;
+      o[j] *= c;
+    }
+    *(uint2 *)(out + k) = make_uint2(pack2(f2bf(o[0]), f2bf(o[1])), pack2(f2bf(o[2]), f2bf(o[3])));
+  }
+}
+
+}  // namespace
+
+hipError_t launch_loss_rows(const int32_t *ft_seq_offsets, const int32_t *prompt_lens, const int32_t *token_ids,
+                            int n_seq, int32_t *row_idx, int32_t *label, int32_t *seq_id, hipStream_t st) {
+  if (n_seq <= 0) return hipSuccess;
+  hipLaunchKernelGGL(loss_rows_kernel, dim3(n_seq), dim3(256), 0, st, ft_seq_offsets, prompt_lens, token_ids, row_idx, label, seq_id);
+  return hipGetLastError();
+}
+
+hipError_t launch_logsoftmax_gather(const float *logits, int rows, int V, const int32_t *label, float *logp_t,
+                                    float *lse, hipStream_t st) {
+  if (rows <= 0) return hipSuccess;
+  hipLaunchKernelGGL(logsoftmax_gather_kernel, dim3(rows), dim3(256), 0, st, logits, V, label, logp_t, lse);
+  return hipGetLastError();
+}
+
+hipError_t launch_dpo_pairs(const float *logp_t, const int32_t *ft_seq_offsets, const int32_t *prompt_lens, int n_seq,
+                            const float *ref_logp, float beta, float *logp_out, float *loss_per_pair, float *loss_mean,
+                            float *clpd, int32_t *win, float *dlogp, hipStream_t st) {
+  hipLaunchKernelGGL(dpo_pairs_kernel, dim3(1), dim3(256), 0, st, logp_t, ft_seq_offsets, prompt_lens, n_seq, ref_logp, beta, logp_out, loss_per_pair, loss_mean, clpd, win, dlogp);
+  return hipGetLastError();
+}
+
+hipError_t launch_dlogits(const float *logits, int rows, int V, const int32_t *label, const int32_t *seq_id,
+                          const float *lse, const float *dlogp, bf16_t *dl, hipStream_t st) {
+  if (rows <= 0) return hipSuccess;
+  hipLaunchKernelGGL(dlogits_kernel, dim3(rows), dim3(256), 0, st, logits, V, label, seq_id, lse, dlogp, dl);
+  return hipGetLastError();
+}

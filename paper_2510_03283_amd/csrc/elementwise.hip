@@ -1,0 +1,331 @@
+// HBM-bound row kernels: RMSNorm, rotary embedding, SwiGLU, operand splitting (fwd and bwd).
+#include "kernels.h"
+
+namespace {
+
+template <bool BF16>
+__device__ __forceinline__ void ld4(const void *p, size_t i, float v[4]) {
+  if constexpr (BF16) {
+    const uint2 u = *(const uint2 *)((const bf16_t *)p + i);
+    v[0] = __uint_as_float(u.x << 16); v[1] = __uint_as_float(u.x & 0xffff0000u);
+    v[2] = __uint_as_float(u.y << 16); v[3] = __uint_as_float(u.y & 0xffff0000u);
+  } else {
+    const float4 f = *(const float4 *)((const float *)p + i);
+    v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w;
+  }
+}
+
+__device__ __forceinline__ void st4_split(bf16_t *hi, bf16_t *lo, size_t i, const float v[4]) {
+  bf16_t h[4], l[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) split_bf(v[j], h[j], l[j]);
+  *(uint2 *)(hi + i) = make_uint2(pack2(h[0], h[1]), pack2(h[2], h[3]));
+  if (lo) *(uint2 *)(lo + i) = make_uint2(pack2(l[0], l[1]), pack2(l[2], l[3]));
+}
+
+// ------------------------------------------------------------------ RMSNorm forward
+template <bool XBF, bool GBF>
+__global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const void *x, const int32_t *row_idx, const void *g, int d,
+                                                          float eps, bf16_t *hi, bf16_t *lo, float *rstd) {
+  __shared__ float red[4];
+  const int r = blockIdx.x;
+  const size_t xin = (size_t)(row_idx ? row_idx[r] : r) * d, xo = (size_t)r * d;
+  float ss = 0.f;
+  for (int k = 4 * threadIdx.x; k < d; k += 1024) {
+    float v[4];
+    ld4<XBF>(x, xin + k, v);
+    ss += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+  }
+  ss = block_sum<256>(ss, red);
+  const float rs = 1.0f / sqrtf(ss / (float)d + eps);
+  if (rstd && threadIdx.x == 0) rstd[r] = rs;
+  for (int k = 4 * threadIdx.x; k < d; k += 1024) {
+    float v[4], gg[4];
+    ld4<XBF>(x, xin + k, v);
+    ld4<GBF>(g, k, gg);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = v[j] * rs * gg[j];
+    st4_split(hi, lo, xo + k, v);
+  }
+}
+
+// ------------------------------------------------------------------ RMSNorm backward
+constexpr int RB_MAXV = 8;   // d <= 8192
+template <bool XBF, bool GBF>
+__global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const float *dy, const void *x, const int32_t *row_idx,
+                                                          const void *g, const float *rstd, const float *resid,
+                                                          int rows, int d, float *dx_out, bf16_t *dx_bf,
+                                                          float *dg_partial) {
+  __shared__ float red[4];
+  float dgacc[RB_MAXV][4];
+#pragma unroll
+  for (int i = 0; i < RB_MAXV; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) dgacc[i][j] = 0.f;
+  for (int r = blockIdx.x; r < rows; r += gridDim.x) {
+    const size_t xr = (size_t)(row_idx ? row_idx[r] : r) * d, yr = (size_t)r * d;
+    const float rs = rstd[r];
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < RB_MAXV; ++i) {
+      const int k = 4 * threadIdx.x + 1024 * i;
+      if (k < d) {
+        float dv[4], xv[4], gg[4];
+        ld4<false>(dy, yr + k, dv);
+        ld4<XBF>(x, xr + k, xv);
+        ld4<GBF>(g, k, gg);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          s += dv[j] * gg[j] * xv[j];
+          dgacc[i][j] += dv[j] * xv[j] * rs;
+        }
+      }
+    }
+    s = block_sum<256>(s, red);
+    const float c = rs * rs * rs * s / (float)d;
+#pragma unroll
+    for (int i = 0; i < RB_MAXV; ++i) {
+      const int k = 4 * threadIdx.x + 1024 * i;
+      if (k < d) {
+        float dv[4], xv[4], gg[4], o[4];
+        ld4<false>(dy, yr + k, dv);
+        ld4<XBF>(x, xr + k, xv);
+        ld4<GBF>(g, k, gg);
+        float rr[4] = {0.f, 0.f, 0.f, 0.f};
+        if (resid) ld4<false>(resid, yr + k, rr);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) o[j] = rr[j] + rs * dv[j] * gg[j] - xv[j] * c;
+        *(float4 *)(dx_out + xr + k) = make_float4(o[0], o[1], o[2], o[3]);
+        if (dx_bf) *(uint2 *)(dx_bf + xr + k) = make_uint2(pack2(f2bf(o[0]), f2bf(o[1])), pack2(f2bf(o[2]), f2bf(o[3])));
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < RB_MAXV; ++i) {
+    const int k = 4 * threadIdx.x + 1024 * i;
+    if (k < d) *(float4 *)(dg_partial + (size_t)blockIdx.x * d + k) = make_float4(dgacc[i][0], dgacc[i][1], dgacc[i][2], dgacc[i][3]);
+  }
+}
+
+__global__ __launch_bounds__(256) void colsum_kernel(const float *part, int n_part, int d, float *out, int accumulate) {
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j >= d) return;
+  float s = 0.f;
+  for (int i = 0; i < n_part; ++i) s += part[(size_t)i * d + j];
+  out[j] = accumulate ? out[j] + s : s;
+}
+
+// ------------------------------------------------------------------ rotary embedding
+// cs[i] = (cos, sin) of pos * inv_freq[i]; the angle is formed and reduced in fp64.
+__device__ __forceinline__ void rope_table(float2 *cs, int pos, const double *inv_freq, int half) {
+  for (int i = threadIdx.x; i < half; i += blockDim.x) {
+    double s, c;
+    sincos((double)pos * inv_freq[i], &s, &c);
+    cs[i] = make_float2((float)c, (float)s);
+  }
+  __syncthreads();
+}
+
+template <bool CBF>
+__global__ __launch_bounds__(256) void rope_split_kernel(const float *qkv, const int32_t *positions,
+                                                         const double *inv_freq, int Hq, int Hkv, int hd, bf16_t *q_hi,
+                                                         bf16_t *k_hi, bf16_t *v_hi, bf16_t *q_lo, bf16_t *k_lo,
+                                                         bf16_t *v_lo, const int32_t *slot_mapping, void *cache_k,
+                                                         void *cache_v, long long num_slots, int block_size) {
+  __shared__ float2 cs[64];
+  const int r = blockIdx.x, half = hd >> 1;
+  rope_table(cs, positions[r], inv_freq, half);
+  const int qd = Hq * hd, kd = Hkv * hd, nq = qd + 2 * kd;
+  const float *in = qkv + (size_t)r * nq;
+  long long slot = -1;
+  if (slot_mapping) {
+    slot = slot_mapping[r];
+    if (slot >= num_slots) slot = -1;
+  }
+  const long long cbase = slot >= 0 ? (slot / block_size) * (long long)Hkv * block_size * hd + (slot % block_size) * (long long)hd : 0;
+  const int npair = (Hq + Hkv) * half;
+  for (int idx = threadIdx.x; idx < npair; idx += 256) {
+    const int head = idx / half, i = idx - head * half;
+    const float a = in[head * hd + i], b = in[head * hd + i + half];
+    const float2 t = cs[i];
+    const float ra = a * t.x - b * t.y, rb = b * t.x + a * t.y;
+    bf16_t ha, la, hb, lb;
+    split_bf(ra, ha, la);
+    split_bf(rb, hb, lb);
+    if (head < Hq) {
+      const size_t o = (size_t)r * qd + head * hd + i;
+      q_hi[o] = ha; q_hi[o + half] = hb;
+      if (q_lo) { q_lo[o] = la; q_lo[o + half] = lb; }
+    } else {
+      const int kh = head - Hq;
+      const size_t o = (size_t)r * kd + kh * hd + i;
+      k_hi[o] = ha; k_hi[o + half] = hb;
+      if (k_lo) { k_lo[o] = la; k_lo[o + half] = lb; }
+      if (slot >= 0) {
+        const long long c = cbase + (long long)kh * block_size * hd + i;
+        if constexpr (CBF) { ((bf16_t *)cache_k)[c] = ha; ((bf16_t *)cache_k)[c + half] = hb; }
+        else { ((float *)cache_k)[c] = ra; ((float *)cache_k)[c + half] = rb; }
+      }
+    }
+  }
+  for (int idx = threadIdx.x; idx < kd; idx += 256) {
+    const float v = in[qd + kd + idx];
+    bf16_t h, l;
+    split_bf(v, h, l);
+    v_hi[(size_t)r * kd + idx] = h;
+    if (v_lo) v_lo[(size_t)r * kd + idx] = l;
+    if (slot >= 0) {
+      const int kh = idx / hd, e = idx - kh * hd;
+      const long long c = cbase + (long long)kh * block_size * hd + e;
+      if constexpr (CBF) ((bf16_t *)cache_v)[c] = h;
+      else ((float *)cache_v)[c] = v;
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void rope_bwd_kernel(const float *dq, const float *dk, const float *dv,
+                                                       const int32_t *positions, const double *inv_freq, int Hq,
+                                                       int Hkv, int hd, bf16_t *dqkv) {
+  __shared__ float2 cs[64];
+  const int r = blockIdx.x, half = hd >> 1;
+  rope_table(cs, positions[r], inv_freq, half);
+  const int qd = Hq * hd, kd = Hkv * hd, nq = qd + 2 * kd;
+  bf16_t *out = dqkv + (size_t)r * nq;
+  const int npair = (Hq + Hkv) * half;
+  for (int idx = threadIdx.x; idx < npair; idx += 256) {
+    const int head = idx / half, i = idx - head * half;
+    const float *src = head < Hq ? dq + (size_t)r * qd + head * hd : dk + (size_t)r * kd + (head - Hq) * hd;
+    const float a = src[i], b = src[i + half];
+    const float2 t = cs[i];
+    out[head * hd + i] = f2bf(a * t.x + b * t.y);
+    out[head * hd + i + half] = f2bf(b * t.x - a * t.y);
+  }
+  for (int idx = threadIdx.x; idx < kd; idx += 256) out[qd + kd + idx] = f2bf(dv[(size_t)r * kd + idx]);
+}
+
+// ------------------------------------------------------------------ SwiGLU
+__global__ __launch_bounds__(256) void swiglu_fwd_kernel(const float *gu, int F, bf16_t *hm_hi, bf16_t *hm_lo) {
+  const int r = blockIdx.x;
+  const int k = 4 * (blockIdx.y * 256 + threadIdx.x);
+  if (k >= F) return;
+  float gv[4], uv[4], o[4];
+  ld4<false>(gu, (size_t)r * 2 * F + k, gv);
+  ld4<false>(gu, (size_t)r * 2 * F + F + k, uv);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) o[j] = gv[j] / (1.0f + expf(-gv[j])) * uv[j];
+  st4_split(hm_hi, hm_lo, (size_t)r * F + k, o);
+}
+
+__global__ __launch_bounds__(256) void swiglu_bwd_kernel(const bf16_t *dhm, const float *gu, int F, bf16_t *dgu, bf16_t *hm) {
+  const int r = blockIdx.x;
+  const int k = 4 * (blockIdx.y * 256 + threadIdx.x);
+  if (k >= F) return;
+  float gv[4], uv[4], dh[4], dg[4], du[4], h[4];
+  ld4<false>(gu, (size_t)r * 2 * F + k, gv);
+  ld4<false>(gu, (size_t)r * 2 * F + F + k, uv);
+  ld4<true>(dhm, (size_t)r * F + k, dh);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float sg = 1.0f / (1.0f + expf(-gv[j]));
+    const float si = gv[j] * sg;
+    h[j] = si * uv[j];
+    du[j] = dh[j] * si;
+    dg[j] = dh[j] * uv[j] * sg * (1.0f + gv[j] * (1.0f - sg));
+  }
+  st4_split(dgu, nullptr, (size_t)r * 2 * F + k, dg);
+  st4_split(dgu, nullptr, (size_t)r * 2 * F + F + k, du);
+  st4_split(hm, nullptr, (size_t)r * F + k, h);
+}
+
+__global__ __launch_bounds__(256) void split_f32_kernel(const float *src, size_t n, bf16_t *hi, bf16_t *lo) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+    bf16_t h, l;
+    split_bf(src[i], h, l);
+    hi[i] = h;
+    if (lo) lo[i] = l;
+  }
+}
+
+__global__ __launch_bounds__(256) void fill_f32_kernel(float *dst, size_t n, float v) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) dst[i] = v;
+}
+
+}  // namespace
+
+hipError_t launch_rmsnorm_fwd(const void *x, bool x_bf16, const int32_t *row_idx, const void *g, bool g_bf16, int rows,
+                              int d, float eps, bf16_t *hi, bf16_t *lo, float *rstd, hipStream_t st) {
+  if (rows <= 0) return hipSuccess;
+  dim3 grid(rows), blk(256);
+  if (x_bf16 && g_bf16) hipLaunchKernelGGL((rmsnorm_fwd_kernel<true, true>), grid, blk, 0, st, x, row_idx, g, d, eps, hi, lo, rstd);
+  else if (!x_bf16 && g_bf16) hipLaunchKernelGGL((rmsnorm_fwd_kernel<false, true>), grid, blk, 0, st, x, row_idx, g, d, eps, hi, lo, rstd);
+  else if (!x_bf16 && !g_bf16) hipLaunchKernelGGL((rmsnorm_fwd_kernel<false, false>), grid, blk, 0, st, x, row_idx, g, d, eps, hi, lo, rstd);
+  else hipLaunchKernelGGL((rmsnorm_fwd_kernel<true, false>), grid, blk, 0, st, x, row_idx, g, d, eps, hi, lo, rstd);
+  return hipGetLastError();
+}
+
+hipError_t launch_rmsnorm_bwd(const float *dy, const void *x, bool x_bf16, const int32_t *row_idx, const void *g,
+                              bool g_bf16, const float *rstd, const float *resid, int rows, int d, float *dx_out,
+                              bf16_t *dx_bf, float *dg_partial, int n_part, hipStream_t st) {
+  if (rows <= 0 || n_part <= 0) return hipSuccess;
+  if (d > 1024 * RB_MAXV) return hipErrorInvalidValue;
+  dim3 grid(n_part), blk(256);
+  if (x_bf16 && g_bf16) hipLaunchKernelGGL((rmsnorm_bwd_kernel<true, true>), grid, blk, 0, st, dy, x, row_idx, g, rstd, resid, rows, d, dx_out, dx_bf, dg_partial);
+  else if (!x_bf16 && g_bf16) hipLaunchKernelGGL((rmsnorm_bwd_kernel<false, true>), grid, blk, 0, st, dy, x, row_idx, g, rstd, resid, rows, d, dx_out, dx_bf, dg_partial);
+  else if (!x_bf16 && !g_bf16) hipLaunchKernelGGL((rmsnorm_bwd_kernel<false, false>), grid, blk, 0, st, dy, x, row_idx, g, rstd, resid, rows, d, dx_out, dx_bf, dg_partial);
+  else hipLaunchKernelGGL((rmsnorm_bwd_kernel<true, false>), grid, blk, 0, st, dy, x, row_idx, g, rstd, resid, rows, d, dx_out, dx_bf, dg_partial);
+  return hipGetLastError();
+}
+
+hipError_t launch_colsum(const float *part, int n_part, int d, float *out, int accumulate, hipStream_t st) {
+  hipLaunchKernelGGL(colsum_kernel, dim3(cdiv(d, 256)), dim3(256), 0, st, part, n_part, d, out, accumulate);
+  return hipGetLastError();
+}
+
+hipError_t launch_rope_split(const float *qkv, const int32_t *positions, const double *inv_freq, int rows, int Hq,
+                             int Hkv, int hd, bf16_t *q_hi, bf16_t *k_hi, bf16_t *v_hi, bf16_t *q_lo, bf16_t *k_lo,
+                             bf16_t *v_lo, const int32_t *slot_mapping, void *cache_k, void *cache_v, bool cache_bf16,
+                             long long num_slots, int block_size, hipStream_t st) {
+  if (rows <= 0) return hipSuccess;
+  if (hd > 128) return hipErrorInvalidValue;
+  if (cache_bf16)
+    hipLaunchKernelGGL((rope_split_kernel<true>), dim3(rows), dim3(256), 0, st, qkv, positions, inv_freq, Hq, Hkv, hd, q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, slot_mapping, cache_k, cache_v, num_slots, block_size);
+  else
+    hipLaunchKernelGGL((rope_split_kernel<false>), dim3(rows), dim3(256), 0, st, qkv, positions, inv_freq, Hq, Hkv, hd, q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, slot_mapping, cache_k, cache_v, num_slots, block_size);
+  return hipGetLastError();
+}
+
+hipError_t launch_rope_bwd(const float *dq, const float *dk, const float *dv, const int32_t *positions,
+                           const double *inv_freq, int rows, int Hq, int Hkv, int hd, bf16_t *dqkv, hipStream_t st) {
+  if (rows <= 0) return hipSuccess;
+  if (hd > 128) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(rope_bwd_kernel, dim3(rows), dim3(256), 0, st, dq, dk, dv, positions, inv_freq, Hq, Hkv, hd, dqkv);
+  return hipGetLastError();
+}
+
+hipError_t launch_swiglu_fwd(const float *gu, int rows, int F, bf16_t *hm_hi, bf16_t *hm_lo, hipStream_t st) {
+  if (rows <= 0) return hipSuccess;
+  hipLaunchKernelGGL(swiglu_fwd_kernel, dim3(rows, cdiv(F, 1024)), dim3(256), 0, st, gu, F, hm_hi, hm_lo);
+  return hipGetLastError();
+}
+
+hipError_t launch_swiglu_bwd(const bf16_t *dhm, const float *gu, int rows, int F, bf16_t *dgu, bf16_t *hm, hipStream_t st) {
+  if (rows <= 0) return hipSuccess;
+  hipLaunchKernelGGL(swiglu_bwd_kernel, dim3(rows, cdiv(F, 1024)), dim3(256), 0, st, dhm, gu, F, dgu, hm);
+  return hipGetLastError();
+}
+
+hipError_t launch_split_f32(const float *src, size_t n, bf16_t *hi, bf16_t *lo, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  const unsigned blocks = (unsigned)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
+  hipLaunchKernelGGL(split_f32_kernel, dim3(blocks), dim3(256), 0, st, src, n, hi, lo);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_f32(float *dst, size_t n, float v, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  const unsigned blocks = (unsigned)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
+  hipLaunchKernelGGL(fill_f32_kernel, dim3(blocks), dim3(256), 0, st, dst, n, v);
+  return hipGetLastError();
+}

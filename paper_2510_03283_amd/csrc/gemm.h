@@ -1,0 +1,41 @@
+// Grouped bf16 MFMA GEMM used by every dense contraction of the iteration.
+#pragma once
+#include "common.h"
+
+// C[m, n] = sum_k A[m, k] * B[n, k]  (+ residual), over up to three row groups that share B and
+// up to three column segments that share A.  Row groups let inference rows (one bf16 pass) and
+// fine-tune rows (two- or three-pass split operands) ride in one launch; column segments let
+// several weight matrices with separate base pointers (Wq|Wk|Wv, Wg|Wu) ride in one launch.
+//
+// Operand layouts (element type bf16):
+//   LA = 0: A is [M, K] row-major (k contiguous).   LA = 1: A is [K, M] row-major (m contiguous).
+//   LB = 0: B is [N, K] row-major (k contiguous).   LB = 1: B is [K, N] row-major (n contiguous).
+// Requirements checked by gemm_launch: K % 64 == 0 for a k-contiguous operand; M % 8 == 0
+// (N % 8 == 0) for an m- (n-) contiguous operand; all leading dimensions and column offsets
+// multiples of 8 elements; pointers 16-byte aligned.
+struct GemmMGroup {
+  const bf16_t *a[2];   // [0] = hi (or only) operand, [1] = lo term (passes 2..)
+  void *c;              // first output row of the group
+  const void *resid;    // first residual row of the group (may be null)
+  int M;                // rows in the group
+  int npass;            // 1: A0*B0   2: + A1*B0   3: + A0*B1
+};
+struct GemmNSeg {
+  const bf16_t *b[2];   // [0] = hi (or only) operand, [1] = lo term (pass 3)
+  int N;                // columns in the segment
+  int c_col;            // first output column of the segment
+};
+struct GemmParams {
+  GemmMGroup mg[3];
+  GemmNSeg ns[3];
+  int n_mg, n_ns;
+  int K;
+  long long lda, ldb, ldc, ldr;
+  int out_bf16;     // 0: C is fp32, 1: C is bf16
+  int resid_kind;   // 0 none, 1 fp32, 2 bf16 ; C = acc + resid
+  int mt_start[4];  // filled by gemm_launch
+  int nt_start[4];
+};
+
+// Returns hipSuccess or the launch error; a non-null *why is set on a rejected shape.
+hipError_t gemm_launch(int LA, int LB, GemmParams &p, hipStream_t stream, const char **why);

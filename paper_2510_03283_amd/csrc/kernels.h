@@ -1,0 +1,87 @@
+// Host-callable launchers of the non-GEMM kernels.  All pointers are device pointers.
+// Every launcher returns the HIP launch status.  "hi"/"lo" are the two bf16 terms of a value
+// (lo pointers may be null: then only the rounded value is written).
+#pragma once
+#include "common.h"
+
+// ---- elementwise.hip -------------------------------------------------------------------------
+// Row-wise RMSNorm: out = x * rsqrt(mean(x^2) + eps) * g.  x is fp32 or bf16 [*, d] (row r reads
+// input row row_idx[r] when row_idx is non-null), g is fp32 or bf16 [d].  rstd (nullable) gets
+// the row scale.
+hipError_t launch_rmsnorm_fwd(const void *x, bool x_bf16, const int32_t *row_idx, const void *g, bool g_bf16,
+                              int rows, int d, float eps, bf16_t *hi, bf16_t *lo, float *rstd, hipStream_t st);
+// RMSNorm backward.  dx_out[out_row] = resid[r] + rstd*(dy*g) - x*rstd^3*mean((dy*g)*x), where
+// out_row = row_idx ? row_idx[r] : r and x is read at the same row; resid (nullable) fp32.
+// dg_partial [n_part, d] receives per-block partial sums of dy*x*rstd (reduce with
+// launch_colsum).  dx_bf (nullable) gets a bf16 copy of dx_out rows (same row mapping).
+hipError_t launch_rmsnorm_bwd(const float *dy, const void *x, bool x_bf16, const int32_t *row_idx, const void *g,
+                              bool g_bf16, const float *rstd, const float *resid, int rows, int d,
+                              float *dx_out, bf16_t *dx_bf, float *dg_partial, int n_part, hipStream_t st);
+// out[j] (+)= sum_i part[i, j]
+hipError_t launch_colsum(const float *part, int n_part, int d, float *out, int accumulate, hipStream_t st);
+// Rotary embedding of q and k inside qkv fp32 [rows, (Hq+2Hkv)*hd], split into head-major bf16
+// outputs q [rows, Hq*hd], k, v [rows, Hkv*hd]; optionally scatter k, v (rounded to the cache
+// type) into the paged cache at slot_mapping (null = no cache write).
+hipError_t launch_rope_split(const float *qkv, const int32_t *positions, const double *inv_freq, int rows, int Hq,
+                             int Hkv, int hd, bf16_t *q_hi, bf16_t *k_hi, bf16_t *v_hi, bf16_t *q_lo, bf16_t *k_lo,
+                             bf16_t *v_lo, const int32_t *slot_mapping, void *cache_k, void *cache_v, bool cache_bf16,
+                             long long num_slots, int block_size, hipStream_t st);
+// Transposed rotation of dq (fp32 [rows, Hq*hd]) and dk, copy of dv (fp32 [rows, Hkv*hd]) into
+// dqkv bf16 [rows, (Hq+2Hkv)*hd].
+hipError_t launch_rope_bwd(const float *dq, const float *dk, const float *dv, const int32_t *positions,
+                           const double *inv_freq, int rows, int Hq, int Hkv, int hd, bf16_t *dqkv, hipStream_t st);
+// hm = silu(G) * U from gu fp32 [rows, 2F] (G = columns [0,F), U = [F,2F)).
+hipError_t launch_swiglu_fwd(const float *gu, int rows, int F, bf16_t *hm_hi, bf16_t *hm_lo, hipStream_t st);
+// dU = dhm*silu(G), dG = dhm*U*sig(G)*(1+G*(1-sig(G))) -> dgu bf16 [rows, 2F]; hm (bf16) recomputed.
+hipError_t launch_swiglu_bwd(const bf16_t *dhm, const float *gu, int rows, int F, bf16_t *dgu, bf16_t *hm, hipStream_t st);
+// fp32 -> (hi, lo) bf16, n elements; lo nullable.
+hipError_t launch_split_f32(const float *src, size_t n, bf16_t *hi, bf16_t *lo, hipStream_t st);
+hipError_t launch_fill_f32(float *dst, size_t n, float v, hipStream_t st);
+
+// ---- kv_cache.hip ----------------------------------------------------------------------------
+hipError_t launch_kv_append(void *cache_k, void *cache_v, bool bf16, long long num_slots, int block_size, int Hkv,
+                            int hd, const void *k_new, const void *v_new, const int32_t *slot_mapping, int n,
+                            hipStream_t st);
+hipError_t launch_kv_gather(const void *cache_k, const void *cache_v, bool bf16, long long num_blocks, int block_size,
+                            int Hkv, int hd, const int32_t *block_table, int ctx_len, void *k_out, void *v_out,
+                            long long *slots_out, hipStream_t st);
+
+// ---- attn_fwd.hip ----------------------------------------------------------------------------
+// Varlen causal attention over n_seq sequences.  seg points at n_seq+1 row offsets (device)
+// ABSOLUTE in the batch; row_base is subtracted to index q/k/v/o (which start at the first row
+// of this class).  lse (nullable) fp32 [rows, Hq].  split: operands are (hi, lo) pairs.
+hipError_t launch_attn_fwd(const bf16_t *q_hi, const bf16_t *k_hi, const bf16_t *v_hi, const bf16_t *q_lo,
+                           const bf16_t *k_lo, const bf16_t *v_lo, const int32_t *seg, int row_base, int n_seq,
+                           int max_len, int Hq, int Hkv, int hd, bf16_t *o_hi, bf16_t *o_lo, float *lse,
+                           hipStream_t st);
+// ---- attn_decode.hip -------------------------------------------------------------------------
+// One query row per request against its paged context of ctx_len[r]+1 tokens.  q bf16
+// [n_decode, Hq*hd] (rows of the decode class), out bf16 same shape.  partial: fp32 scratch of
+// decode_partial_floats() floats.
+size_t decode_partial_floats(int n_decode, int Hq, int hd, int max_context);
+hipError_t launch_attn_decode(const bf16_t *q, const void *cache_k, const void *cache_v, bool cache_bf16,
+                              long long num_blocks, int block_size, const int32_t *block_tables, int max_blocks_per_req,
+                              const int32_t *ctx_lens, int n_decode, int max_context, int Hq, int Hkv, int hd,
+                              float *partial, bf16_t *out, hipStream_t st);
+// ---- attn_bwd.hip ----------------------------------------------------------------------------
+// Backward of the varlen causal attention of the fine-tune sequences (bf16 operands, fp32 out).
+// dvec: fp32 scratch [rows, Hq].
+hipError_t launch_attn_bwd(const bf16_t *q, const bf16_t *k, const bf16_t *v, const bf16_t *o, const bf16_t *d_o,
+                           const float *lse, const int32_t *seg, int row_base, int n_seq, int max_len, int rows,
+                           int Hq, int Hkv, int hd, float *dvec, float *dq, float *dk, float *dv, hipStream_t st);
+
+// ---- dpo_head.hip ----------------------------------------------------------------------------
+// For every loss row (sequence s, t = P_s-1 .. L_s-2, in sequence order): row_idx = index of row
+// t among the fine-tune rows, label = token_ids[t+1], seq_id = s.
+hipError_t launch_loss_rows(const int32_t *ft_seq_offsets, const int32_t *prompt_lens, const int32_t *token_ids,
+                            int n_seq, int32_t *row_idx, int32_t *label, int32_t *seq_id, hipStream_t st);
+// logp_t[r] = logits[r, label[r]] - logsumexp(logits[r, :]); lse[r] kept.
+hipError_t launch_logsoftmax_gather(const float *logits, int rows, int V, const int32_t *label, float *logp_t,
+                                    float *lse, hipStream_t st);
+// Per-sequence sums, pair losses, metrics and dloss_mean/dlogp per sequence.
+hipError_t launch_dpo_pairs(const float *logp_t, const int32_t *ft_seq_offsets, const int32_t *prompt_lens, int n_seq,
+                            const float *ref_logp, float beta, float *logp_out, float *loss_per_pair, float *loss_mean,
+                            float *clpd, int32_t *win, float *dlogp, hipStream_t st);
+// dl[r, j] = dlogp[seq_id[r]] * ([j == label[r]] - exp(logits[r, j] - lse[r])) as bf16.
+hipError_t launch_dlogits(const float *logits, int rows, int V, const int32_t *label, const int32_t *seq_id,
+                          const float *lse, const float *dlogp, bf16_t *dl, hipStream_t st);

@@ -1,0 +1,138 @@
+"""Runs one hybrid iteration of a synthetic workload on the GPU through the C-ABI binding.
+
+Only plumbing lives here: uploading the seeded inputs, allocating buffers with torch, and
+calling the library entry points in order (forward of all rows, DPO head, backward of the
+fine-tune rows).  Used by the GPU tests, the smoke check and bench.py."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as B
+from .synth import Workload
+
+_WNAMES = ("g1", "wq", "wk", "wv", "wo", "g2", "wg", "wu", "wd")
+
+
+class DeviceIteration:
+    def __init__(self, wl: Workload, device: str = "cuda:0", load_cache: bool = True):
+        self.wl = wl
+        self.dev = torch.device(device)
+        m, b = wl.dims, wl.batch
+        self.io_dtype = torch.bfloat16 if m.io_bf16 else torch.float32
+        self.h = B.mace_create(m.d_model, m.n_q_heads, m.n_kv_heads, m.head_dim, m.d_ff, m.vocab, m.rms_eps,
+                               m.rope_theta, B.MACE_BF16 if m.io_bf16 else B.MACE_F32)
+        up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(self.dev)
+        upio = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.dev).to(self.io_dtype).contiguous()
+        self.w = {k: upio(wl.weights[k]) for k in _WNAMES}
+        self.E = upio(wl.weights["E"])
+        self.gf = upio(wl.weights["gf"])
+        self.w_struct = B.layer_weights_struct(self.w)
+        self.x = upio(wl.x)
+
+        # descriptor arrays
+        self.T, self.Tp, self.Td, self.Tf = b.n_tokens, b.t_prefill, b.t_decode, b.t_ft
+        self.Ti = self.Tp + self.Td
+        self.R = b.n_loss_rows
+        seg = np.asarray(b.seg_offsets, dtype=np.int32)
+        slots = []
+        for i, L in enumerate(b.prefill_lens):
+            slots.append(B.mace_kv_slot_mapping(b.prefill_block_tables[i], b.block_size, 0, int(L)))
+        for j, n in enumerate(b.decode_ctx):
+            nb = -(-(int(n) + 1) // b.block_size)
+            slots.append(B.mace_kv_slot_mapping(b.decode_block_tables[j][:nb], b.block_size, int(n), 1))
+        self.slot_mapping_host = np.concatenate(slots).astype(np.int32) if slots else np.zeros(0, np.int32)
+        self.seg_dev = up(seg)
+        self.pos_dev = up(np.asarray(b.positions, dtype=np.int32))
+        self.slot_dev = up(self.slot_mapping_host) if self.Ti else None
+        self.bt_dev = up(np.ascontiguousarray(np.maximum(b.decode_block_tables, 0), dtype=np.int32)) if self.Td else None
+        self.ctx_dev = up(np.asarray(b.decode_ctx, dtype=np.int32)) if self.Td else None
+        self.batch = B.BatchDesc(b.n_prefill, b.n_decode, b.n_ft_seq, self.T, seg, self.seg_dev, self.pos_dev,
+                                 self.slot_dev, self.bt_dev, np.asarray(b.decode_ctx, dtype=np.int32), self.ctx_dev,
+                                 b.max_blocks_per_req)
+        self.tok_ft = up(np.asarray(b.token_ids[self.Ti:], dtype=np.int32)) if self.Tf else None
+        ft_off = (seg[b.n_prefill + b.n_decode:] - self.Ti).astype(np.int32)
+        self.ft_off_host = ft_off
+        self.ft_off_dev = up(ft_off)
+        self.prompt_host = np.asarray(b.ft_prompt_lens, dtype=np.int32)
+        self.prompt_dev = up(self.prompt_host)
+        self.ref_dev = up(np.asarray(wl.ref_logp, dtype=np.float32))
+        self.n_pairs = b.n_ft_seq // 2
+
+        # paged cache
+        cshape = (b.num_blocks, m.n_kv_heads, b.block_size, m.head_dim)
+        self.cache_k = torch.zeros(cshape, dtype=self.io_dtype, device=self.dev)
+        self.cache_v = torch.zeros(cshape, dtype=self.io_dtype, device=self.dev)
+        self.cache = B.kv_cache_struct(self.cache_k, self.cache_v, b.num_blocks, b.block_size)
+        if load_cache and self.Td and wl.ctx_k is not None:
+            self.load_context(wl.ctx_k, wl.ctx_v)
+
+        # buffers
+        max_ctx = int(b.decode_ctx.max()) if self.Td else 0
+        self.saved = torch.empty(max(B.mace_fwd_saved_bytes(self.h, self.Tf), 256), dtype=torch.uint8, device=self.dev)
+        self.ws = torch.empty(B.mace_workspace_bytes(self.h, self.T, self.Tf, self.Td, max_ctx, self.R), dtype=torch.uint8, device=self.dev)
+        f32 = dict(dtype=torch.float32, device=self.dev)
+        self.y = torch.empty((self.T, m.d_model), **f32)
+        self.logp = torch.empty(max(b.n_ft_seq, 1), **f32)
+        self.loss_pair = torch.empty(max(self.n_pairs, 1), **f32)
+        self.loss_mean = torch.empty(1, **f32)
+        self.clpd = torch.empty(max(self.n_pairs, 1), **f32)
+        self.win = torch.empty(max(self.n_pairs, 1), dtype=torch.int32, device=self.dev)
+        self.dh = torch.empty((self.Tf, m.d_model), **f32)
+        self.dE = torch.empty((m.vocab, m.d_model), **f32)
+        self.dgf = torch.empty(m.d_model, **f32)
+        self.dx = torch.empty((self.Tf, m.d_model), **f32)
+        self.grads = {k: torch.empty(self.w[k].shape, **f32) for k in _WNAMES}
+        self.g_struct = B.layer_grads_struct(self.grads)
+
+    def load_context(self, ctx_k, ctx_v):
+        """Place the already-cached rows of every decode request through mace_kv_cache_append."""
+        b = self.wl.batch
+        slots, ks, vs = [], [], []
+        for j, n in enumerate(b.decode_ctx):
+            n = int(n)
+            if n == 0:
+                continue
+            nb = -(-n // b.block_size)
+            slots.append(B.mace_kv_slot_mapping(b.decode_block_tables[j][:nb], b.block_size, 0, n))
+            ks.append(ctx_k[j]); vs.append(ctx_v[j])
+        if not slots:
+            return
+        sl = torch.from_numpy(np.concatenate(slots).astype(np.int32)).to(self.dev)
+        k = torch.from_numpy(np.concatenate(ks).astype(np.float32)).to(self.dev).to(self.io_dtype).contiguous()
+        v = torch.from_numpy(np.concatenate(vs).astype(np.float32)).to(self.dev).to(self.io_dtype).contiguous()
+        B.mace_kv_cache_append(self.h, self.cache, k, v, sl, int(sl.numel()))
+
+    def forward(self):
+        B.mace_hybrid_layer_fwd(self.h, self.w_struct, self.batch, self.cache if self.Ti else None, self.x, self.y,
+                                self.saved, self.ws)
+
+    def dpo(self, backward: bool = True):
+        y_ft = self.y[self.Ti:]
+        B.mace_dpo_logprob_loss(self.h, y_ft, self.gf, self.E, self.tok_ft, self.ft_off_dev, self.ft_off_host,
+                                self.prompt_dev, self.prompt_host, self.n_pairs, self.ref_dev, self.wl.beta, self.logp,
+                                self.loss_pair, self.loss_mean, self.clpd, self.win,
+                                self.dh if backward else None, self.dE if backward else None,
+                                self.dgf if backward else None, 0, self.ws)
+
+    def backward(self, dy=None):
+        B.mace_hybrid_layer_bwd(self.h, self.w_struct, self.batch, self.x, self.dh if dy is None else dy, self.saved,
+                                self.dx, self.g_struct, 0, self.ws)
+
+    def step(self):
+        """One pass of the whole hot path: forward of all rows, DPO head fwd+bwd, layer backward."""
+        self.forward()
+        if self.n_pairs:
+            self.dpo(True)
+            self.backward()
+
+    def close(self):
+        if self.h is not None:
+            B.mace_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
