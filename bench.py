@@ -1,0 +1,115 @@
+#!/usr/bin/env python3
+"""Benchmark of one hybrid iteration (all hot-path steps) of the edge-small configuration on one MI355X.
+
+A step = forward of all rows (prefill + decode + fine-tune), DPO head forward and backward, and
+the layer backward of the fine-tune rows, over one synthetic mixed batch that is resident in HBM.
+Prints ONE JSON line; see the design doc for the meaning of every field."""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "mixed-batch tokens/s per layer (prefill+decode+DPO) & % of MFMA/HBM roofline"
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0
+
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of the dominant kernel, bytes per launch (see profiles/); None = not measured
+TRAFFIC_BYTES_PER_LAUNCH = None
+
+
+def cpu_baseline(wl):
+    """The oracle as it stands, timed once on the whole workload on the host cores."""
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from helpers import run_oracle
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    t0 = time.time()
+    run_oracle(wl, backward=True)
+    dt = time.time() - t0
+    return {"value": wl.batch.n_tokens / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"whole workload, 1 pass ({wl.batch.n_tokens} rows, {dt:.1f} s)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="edge", help="synthetic configuration (default: the one the metric is quoted on)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true", help="do not bracket launches with events")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2510_03283_amd import binding as B
+    from paper_2510_03283_amd import synth
+    from paper_2510_03283_amd.harness import DeviceIteration
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    B.load()   # fails loudly when the HIP library is not built
+    wl = synth.make_workload(args.workload)
+    it = DeviceIteration(wl)
+    for _ in range(args.warmup):
+        it.step()
+    torch.cuda.synchronize()
+    if not args.no_profile:
+        B.mace_profile_enable(it.h, True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        it.step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = B.mace_profile_collect(it.h) if not args.no_profile else {}
+    if not args.no_profile:
+        B.mace_profile_enable(it.h, False)
+
+    ms = dt / args.steps * 1e3
+    T = it.T
+    out = {
+        "metric": METRIC, "value": T * args.steps / dt, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload} (BASELINE.json configs[{synth.CONFIG_ORDER.index(args.workload)}])",
+                   "rows": T, "prefill_rows": it.Tp, "decode_rows": it.Td, "ft_rows": it.Tf, "loss_rows": it.R,
+                   "decode_context_tokens": int(wl.batch.decode_ctx.sum()), "n_pairs": it.n_pairs},
+    }
+    if prof:
+        dom = max((k for k in prof if prof[k]["launches"]), key=lambda k: prof[k]["ms"])
+        e = prof[dom]
+        avg_ms = e["ms"] / e["launches"]
+        if e["flops"] > 0:
+            ach = e["flops"] / e["launches"] / (avg_ms * 1e-3) / 1e12
+            roof = {"bound": "mfma", "kernel": dom, "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": ach / PEAK_BF16_TFLOPS, "traffic": TRAFFIC_BYTES_PER_LAUNCH,
+                    "avg_launch_ms": avg_ms, "launches_per_step": e["launches"] / args.steps}
+        else:
+            ach = e["bytes"] / e["launches"] / (avg_ms * 1e-3) / 1e9
+            roof = {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": ach / PEAK_HBM_GBS, "traffic": TRAFFIC_BYTES_PER_LAUNCH,
+                    "avg_launch_ms": avg_ms, "launches_per_step": e["launches"] / args.steps}
+        out["roofline"] = roof
+        out["kernel_ms_per_step"] = {k: round(v["ms"] / args.steps, 4) for k, v in prof.items() if v["launches"]}
+        out["kernel_tflops"] = {k: round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 1) for k, v in prof.items() if v["launches"] and v["flops"] > 0}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    it.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -45,9 +45,8 @@ enum { MACE_F32 = 0, MACE_BF16 = 1 };
 
 typedef struct mace_ctx *mace_handle_t;
 
-/* Model dimensions.  Constraints (else MACE_BAD_SHAPE): head_dim is 64 or 128; n_q_heads is a
- * multiple of n_kv_heads; d_model, n_q_heads*head_dim and d_ff are multiples of 64; vocab is a
- * multiple of 32. */
+/* Model dimensions.  Constraints (else MACE_BAD_SHAPE): head_dim is 64 or 128; n_q_heads /
+ * n_kv_heads is 1, 2, 4 or 8; d_model (<= 8192), d_ff and vocab are multiples of 64. */
 typedef struct {
   int32_t d_model, n_q_heads, n_kv_heads, head_dim, d_ff, vocab;
   float rms_eps;       /* RMSNorm epsilon */
@@ -168,6 +167,22 @@ int mace_dpo_logprob_loss(mace_handle_t h, const float *h_ft, const void *g_fina
                           float *clpd_out, int32_t *win_out, float *dh_ft, float *dw_lm,
                           float *dg_final, int accumulate, void *workspace, size_t workspace_bytes,
                           void *stream);
+
+/* Instrumentation for benchmarks (not part of the paper's method).  When enabled, every kernel
+ * launch of the three iteration calls is preceded by a HIP event recorded on the call's stream
+ * and each call ends with one more, so launch i lasts event[i+1] - event[i] on that stream.
+ * mace_profile_collect waits for the last event (host-synchronising), sums launches, milliseconds
+ * and algorithmic flops per kernel class into out[0 .. *n_out) (max_entries >= 16), and clears
+ * the record.  At most 32768 launches are recorded between two collects; later ones are not timed. */
+typedef struct {
+  char name[48];      /* kernel class: gemm_nt, gemm_nn, gemm_tn, attn_fwd_prefill, attn_fwd_ft, attn_decode, ... */
+  int64_t launches;
+  double ms;          /* summed duration */
+  double flops;       /* summed algorithmic flops (GEMM classes: 2*M*N*K once per launch, extra operand passes not counted) */
+  double bytes;       /* summed algorithmic bytes where the class is HBM-bound, else 0 */
+} mace_profile_entry_t;
+int mace_profile_enable(mace_handle_t h, int on);
+int mace_profile_collect(mace_handle_t h, mace_profile_entry_t *out, int32_t max_entries, int32_t *n_out);
 
 #ifdef __cplusplus
 }

@@ -18,7 +18,7 @@ MACE_F32, MACE_BF16 = 0, 1
 EXPORTS = [
     "mace_create", "mace_destroy", "mace_last_error", "mace_fwd_saved_bytes", "mace_workspace_bytes",
     "mace_kv_slot_mapping", "mace_kv_cache_append", "mace_kv_cache_gather", "mace_hybrid_layer_fwd",
-    "mace_hybrid_layer_bwd", "mace_dpo_logprob_loss",
+    "mace_hybrid_layer_bwd", "mace_dpo_logprob_loss", "mace_profile_enable", "mace_profile_collect",
 ]
 
 
@@ -49,6 +49,11 @@ class BatchT(C.Structure):
                 ("seg_offsets_host", C.c_void_p), ("seg_offsets", C.c_void_p), ("positions", C.c_void_p),
                 ("slot_mapping", C.c_void_p), ("block_tables", C.c_void_p), ("context_lens_host", C.c_void_p),
                 ("context_lens", C.c_void_p), ("max_blocks_per_req", C.c_int32)]
+
+
+class ProfileEntryT(C.Structure):
+    _fields_ = [("name", C.c_char * 48), ("launches", C.c_int64), ("ms", C.c_double), ("flops", C.c_double),
+                ("bytes", C.c_double)]
 
 
 def lib_path() -> str:
@@ -86,6 +91,10 @@ def load():
     lib.mace_hybrid_layer_bwd.restype = C.c_int
     lib.mace_dpo_logprob_loss.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, f32, vp, vp, vp, vp, vp, vp, vp, vp, C.c_int, vp, sz, vp]
     lib.mace_dpo_logprob_loss.restype = C.c_int
+    lib.mace_profile_enable.argtypes = [vp, C.c_int]
+    lib.mace_profile_enable.restype = C.c_int
+    lib.mace_profile_collect.argtypes = [vp, C.POINTER(ProfileEntryT), i32, C.POINTER(i32)]
+    lib.mace_profile_collect.restype = C.c_int
     _lib = lib
     return lib
 
@@ -198,3 +207,16 @@ def mace_dpo_logprob_loss(h, h_ft, g_final, w_lm, token_ids, ft_seq_offsets, ft_
                                         _dev(loss_per_pair), _dev(loss_mean), _dev(clpd_out), _dev(win_out), _dev(dh_ft),
                                         _dev(dw_lm), _dev(dg_final), int(accumulate), _dev(workspace),
                                         workspace.numel() * workspace.element_size(), _stream(stream)), "mace_dpo_logprob_loss")
+
+
+def mace_profile_enable(h, on: bool):
+    _check(load().mace_profile_enable(h, int(on)), "mace_profile_enable")
+
+
+def mace_profile_collect(h) -> dict:
+    """Per kernel class: launches, summed ms, summed algorithmic flops and bytes."""
+    arr = (ProfileEntryT * 16)()
+    n = C.c_int32(0)
+    _check(load().mace_profile_collect(h, arr, 16, C.byref(n)), "mace_profile_collect")
+    return {arr[i].name.decode(): dict(launches=int(arr[i].launches), ms=float(arr[i].ms), flops=float(arr[i].flops),
+                                       bytes=float(arr[i].bytes)) for i in range(n.value)}

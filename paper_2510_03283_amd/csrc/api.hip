@@ -9,12 +9,33 @@
 #include "gemm.h"
 #include "kernels.h"
 
+// Optional in-stream timing: one event before every launch and one at the end of a call, so the
+// time of launch i is event[i+1] - event[i] on the stream the kernels run on.
+struct ProfMark {
+  int tag;         // index into PROF_TAGS, or -1 for the closing event of a call
+  double flops, bytes;
+};
 struct mace_ctx {
   mace_model_t m;
   double *inv_freq;   // device [head_dim/2]
+  bool prof_on = false;
+  std::vector<hipEvent_t> prof_events;
+  std::vector<ProfMark> prof_marks;
 };
 
 namespace {
+
+const char *const PROF_TAGS[] = {"gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd_prefill", "attn_fwd_ft", "attn_decode",
+                                 "attn_bwd", "rmsnorm", "rope", "swiglu", "logsoftmax", "dlogits", "misc"};
+enum { T_GEMM_NT, T_GEMM_NN, T_GEMM_TN, T_ATTN_PREFILL, T_ATTN_FT, T_ATTN_DECODE, T_ATTN_BWD, T_RMSNORM, T_ROPE,
+       T_SWIGLU, T_LOGSOFTMAX, T_DLOGITS, T_MISC, T_COUNT };
+constexpr size_t PROF_MAX_MARKS = 1 << 15;
+
+void prof_mark(mace_ctx *h, hipStream_t st, int tag, double flops = 0.0, double bytes = 0.0) {
+  if (!h->prof_on || h->prof_marks.size() >= h->prof_events.size()) return;
+  if (hipEventRecord(h->prof_events[h->prof_marks.size()], st) != hipSuccess) return;
+  h->prof_marks.push_back({tag, flops, bytes});
+}
 
 thread_local std::string g_err;
 
@@ -201,7 +222,13 @@ DpoWs plan_dpo(const Dims &D, size_t R, size_t n_seq, Bump &w) {
   return P;
 }
 
-int run_gemm(int LA, int LB, GemmParams &p, hipStream_t st, const char *where) {
+int run_gemm(mace_ctx *h, int LA, int LB, GemmParams &p, hipStream_t st, const char *where) {
+  if (h->prof_on) {
+    double mn = 0.0;
+    for (int g = 0; g < p.n_mg; ++g)
+      for (int s = 0; s < p.n_ns; ++s) mn += (double)p.mg[g].M * (double)p.ns[s].N;
+    prof_mark(h, st, LA == 1 ? T_GEMM_TN : (LB == 1 ? T_GEMM_NN : T_GEMM_NT), 2.0 * mn * (double)p.K);
+  }
   const char *why = nullptr;
   hipError_t e = gemm_launch(LA, LB, p, st, &why);
   if (e != hipSuccess) return fail(why ? MACE_BAD_SHAPE : MACE_HIP_ERROR, std::string(where) + ": " + (why ? why : hipGetErrorString(e)));
@@ -305,7 +332,46 @@ int mace_create(mace_handle_t *out, const mace_model_t *model) {
 void mace_destroy(mace_handle_t h) {
   if (!h) return;
   if (h->inv_freq) (void)hipFree(h->inv_freq);
+  for (hipEvent_t e : h->prof_events) (void)hipEventDestroy(e);
   delete h;
+}
+
+int mace_profile_enable(mace_handle_t h, int on) {
+  if (!h) return fail(MACE_INVALID_ARG, "handle is null");
+  h->prof_marks.clear();
+  if (on && h->prof_events.empty()) {
+    h->prof_events.reserve(PROF_MAX_MARKS);
+    for (size_t i = 0; i < PROF_MAX_MARKS; ++i) {
+      hipEvent_t e;
+      HIP_TRY(hipEventCreate(&e), "hipEventCreate");
+      h->prof_events.push_back(e);
+    }
+  }
+  h->prof_on = on != 0;
+  return MACE_OK;
+}
+
+int mace_profile_collect(mace_handle_t h, mace_profile_entry_t *out, int32_t max_entries, int32_t *n_out) {
+  if (!h || !out || !n_out || max_entries < T_COUNT) return fail(MACE_INVALID_ARG, "mace_profile_collect: bad argument");
+  const size_t n = h->prof_marks.size();
+  if (n) HIP_TRY(hipEventSynchronize(h->prof_events[n - 1]), "hipEventSynchronize");
+  for (int t = 0; t < T_COUNT; ++t) {
+    memset(&out[t], 0, sizeof(out[t]));
+    snprintf(out[t].name, sizeof(out[t].name), "%s", PROF_TAGS[t]);
+  }
+  for (size_t i = 0; i + 1 < n; ++i) {
+    const ProfMark &m = h->prof_marks[i];
+    if (m.tag < 0) continue;
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, h->prof_events[i], h->prof_events[i + 1]), "hipEventElapsedTime");
+    out[m.tag].launches += 1;
+    out[m.tag].ms += ms;
+    out[m.tag].flops += m.flops;
+    out[m.tag].bytes += m.bytes;
+  }
+  *n_out = T_COUNT;
+  h->prof_marks.clear();
+  return MACE_OK;
 }
 
 size_t mace_fwd_saved_bytes(mace_handle_t h, int32_t n_ft_tokens) {
@@ -361,6 +427,7 @@ int mace_kv_cache_append(mace_handle_t h, mace_kv_cache_t *cache, const void *k_
   TRY(check_cache(cache));
   if (n < 0 || (n > 0 && (!k_new || !v_new || !slot_mapping))) return fail(MACE_INVALID_ARG, "mace_kv_cache_append: bad argument");
   const Dims D(h->m);
+  prof_mark(h, (hipStream_t)stream, T_MISC);
   HIP_TRY(launch_kv_append(cache->k, cache->v, D.bf, cache->num_blocks * cache->block_size, cache->block_size, D.Hkv, D.hd, k_new, v_new, slot_mapping, n, (hipStream_t)stream), "kv append");
   return MACE_OK;
 }
@@ -371,6 +438,7 @@ int mace_kv_cache_gather(mace_handle_t h, const mace_kv_cache_t *cache, const in
   TRY(check_cache(cache));
   if (ctx_len < 0 || (ctx_len > 0 && (!block_table || !k_out || !v_out))) return fail(MACE_INVALID_ARG, "mace_kv_cache_gather: bad argument");
   const Dims D(h->m);
+  prof_mark(h, (hipStream_t)stream, T_MISC);
   HIP_TRY(launch_kv_gather(cache->k, cache->v, D.bf, cache->num_blocks, cache->block_size, D.Hkv, D.hd, block_table, ctx_len, k_out, v_out, (long long *)slots_out, (hipStream_t)stream), "kv gather");
   return MACE_OK;
 }
@@ -415,7 +483,9 @@ int mace_hybrid_layer_fwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
   const int resid_x = D.bf ? 2 : 1;
 
   // 1. RMSNorm (attention)
+  prof_mark(h, st, T_RMSNORM);
   HIP_TRY(launch_rmsnorm_fwd(x, D.bf, nullptr, w->g_attn, D.bf, I.Ti, D.d, h->m.rms_eps, F.a_i, nullptr, nullptr, st), "rmsnorm1");
+  prof_mark(h, st, T_RMSNORM);
   HIP_TRY(launch_rmsnorm_fwd(xb + (size_t)I.Ti * D.d * es, D.bf, nullptr, w->g_attn, D.bf, I.Tf, D.d, h->m.rms_eps, S.a, F.a_lo, S.rstd1, st), "rmsnorm1 ft");
   // 2. QKV projection, all rows in one launch
   {
@@ -425,19 +495,26 @@ int mace_hybrid_layer_fwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
     gp_seg(p, W.hi[W_Q], W.lo[W_Q], D.qd, 0);
     gp_seg(p, W.hi[W_K], W.lo[W_K], D.kd, D.qd);
     gp_seg(p, W.hi[W_V], W.lo[W_V], D.kd, D.qd + D.kd);
-    TRY(run_gemm(0, 0, p, st, "qkv gemm"));
+    TRY(run_gemm(h, 0, 0, p, st, "qkv gemm"));
   }
   // 3. RoPE, operand split, KV append of the inference rows
-  if (I.Ti > 0)
+  if (I.Ti > 0) {
+    prof_mark(h, st, T_ROPE);
     HIP_TRY(launch_rope_split(F.qkv_i, batch->positions, h->inv_freq, I.Ti, D.Hq, D.Hkv, D.hd, F.q_i, F.k_i, F.v_i, nullptr, nullptr, nullptr,
                               batch->slot_mapping, cache->k, cache->v, D.bf, cache->num_blocks * cache->block_size, cache->block_size, st), "rope");
+  }
+  prof_mark(h, st, T_ROPE);
   HIP_TRY(launch_rope_split(F.qkv_f, batch->positions + I.Ti, h->inv_freq, I.Tf, D.Hq, D.Hkv, D.hd, S.q, S.k, S.v, F.q_lo, F.k_lo, F.v_lo,
                             nullptr, nullptr, nullptr, D.bf, 0, 1, st), "rope ft");
   // 4. attention: prefill (causal), decode (paged), fine-tune (causal, split operands, LSE kept)
+  prof_mark(h, st, T_ATTN_PREFILL);
   HIP_TRY(launch_attn_fwd(F.q_i, F.k_i, F.v_i, nullptr, nullptr, nullptr, batch->seg_offsets, 0, batch->n_prefill, I.max_prefill, D.Hq, D.Hkv, D.hd, F.o_i, nullptr, nullptr, st), "prefill attention");
-  if (I.Td > 0)
+  if (I.Td > 0) {
+    prof_mark(h, st, T_ATTN_DECODE);
     HIP_TRY(launch_attn_decode(F.q_i + (size_t)I.Tp * D.qd, cache->k, cache->v, D.bf, cache->num_blocks, cache->block_size, batch->block_tables, batch->max_blocks_per_req,
                                batch->context_lens, I.Td, I.max_ctx, D.Hq, D.Hkv, D.hd, F.dec_partial, F.o_i + (size_t)I.Tp * D.qd, st), "decode attention");
+  }
+  prof_mark(h, st, T_ATTN_FT);
   HIP_TRY(launch_attn_fwd(S.q, S.k, S.v, F.q_lo, F.k_lo, F.v_lo, batch->seg_offsets + batch->n_prefill + batch->n_decode, I.Ti, batch->n_ft_seq, I.max_ft, D.Hq, D.Hkv, D.hd, S.o, F.o_lo, S.lse, st), "ft attention");
   // 5. output projection + residual
   {
@@ -446,10 +523,12 @@ int mace_hybrid_layer_fwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
     gp_group(p, S.o, F.o_lo, S.x1, xb + (size_t)I.Ti * D.d * es, I.Tf, np_ft);
     gp_group(p, F.o_i, nullptr, F.x1_i, x, I.Ti, 1);
     gp_seg(p, W.hi[W_O], W.lo[W_O], D.d, 0);
-    TRY(run_gemm(0, 0, p, st, "o gemm"));
+    TRY(run_gemm(h, 0, 0, p, st, "o gemm"));
   }
   // 6. RMSNorm (MLP), gate/up projection, SwiGLU, down projection + residual
+  prof_mark(h, st, T_RMSNORM);
   HIP_TRY(launch_rmsnorm_fwd(F.x1_i, false, nullptr, w->g_mlp, D.bf, I.Ti, D.d, h->m.rms_eps, F.b_i, nullptr, nullptr, st), "rmsnorm2");
+  prof_mark(h, st, T_RMSNORM);
   HIP_TRY(launch_rmsnorm_fwd(S.x1, false, nullptr, w->g_mlp, D.bf, I.Tf, D.d, h->m.rms_eps, S.b, F.b_lo, S.rstd2, st), "rmsnorm2 ft");
   {
     GemmParams p = gp_init(D.d, D.d, D.d, 2 * D.F);
@@ -457,9 +536,11 @@ int mace_hybrid_layer_fwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
     gp_group(p, F.b_i, nullptr, F.gu_i, nullptr, I.Ti, 1);
     gp_seg(p, W.hi[W_G], W.lo[W_G], D.F, 0);
     gp_seg(p, W.hi[W_U], W.lo[W_U], D.F, D.F);
-    TRY(run_gemm(0, 0, p, st, "gate/up gemm"));
+    TRY(run_gemm(h, 0, 0, p, st, "gate/up gemm"));
   }
+  prof_mark(h, st, T_SWIGLU);
   HIP_TRY(launch_swiglu_fwd(F.gu_i, I.Ti, D.F, F.hm_i, nullptr, st), "swiglu");
+  prof_mark(h, st, T_SWIGLU);
   HIP_TRY(launch_swiglu_fwd(S.gu, I.Tf, D.F, F.hm_hi, F.hm_lo, st), "swiglu ft");
   {
     GemmParams p = gp_init(D.F, D.F, D.F, D.d);
@@ -467,8 +548,9 @@ int mace_hybrid_layer_fwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
     gp_group(p, F.hm_hi, F.hm_lo, y + (size_t)I.Ti * D.d, S.x1, I.Tf, np_ft);
     gp_group(p, F.hm_i, nullptr, y, F.x1_i, I.Ti, 1);
     gp_seg(p, W.hi[W_D], W.lo[W_D], D.d, 0);
-    TRY(run_gemm(0, 0, p, st, "down gemm"));
+    TRY(run_gemm(h, 0, 0, p, st, "down gemm"));
   }
+  prof_mark(h, st, -1);
   return MACE_OK;
 }
 
@@ -501,6 +583,7 @@ int mace_hybrid_layer_bwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
   const int acc = accumulate ? 1 : 0;
   const int n_part = Tf < DG_PARTS ? Tf : DG_PARTS;
 
+  prof_mark(h, st, T_MISC);
   HIP_TRY(launch_split_f32(dy_ft, (size_t)Tf * D.d, B.dy_bf, nullptr, st), "cast dy");
   // MLP: dHm = dY Wd ; SwiGLU backward ; dWd = dY^T Hm
   {
@@ -508,27 +591,28 @@ int mace_hybrid_layer_bwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
     p.out_bf16 = 1;
     gp_group(p, B.dy_bf, nullptr, B.dhm, nullptr, Tf, 1);
     gp_seg(p, W.hi[W_D], nullptr, D.F, 0);
-    TRY(run_gemm(0, 1, p, st, "dhm gemm"));
+    TRY(run_gemm(h, 0, 1, p, st, "dhm gemm"));
   }
+  prof_mark(h, st, T_SWIGLU);
   HIP_TRY(launch_swiglu_bwd(B.dhm, S.gu, Tf, D.F, B.dgu, B.hm, st), "swiglu bwd");
   if (grads->w_down) {
     GemmParams p = gp_init(Tf, D.d, D.F, D.F);
     p.resid_kind = acc;
     gp_group(p, B.dy_bf, nullptr, grads->w_down, grads->w_down, D.d, 1);
     gp_seg(p, B.hm, nullptr, D.F, 0);
-    TRY(run_gemm(1, 1, p, st, "dWd gemm"));
+    TRY(run_gemm(h, 1, 1, p, st, "dWd gemm"));
   }
   // db = dG Wg + dU Wu ; dWg = dG^T b ; dWu = dU^T b
   {
     GemmParams p = gp_init(D.F, 2 * D.F, D.d, D.d);
     gp_group(p, B.dgu, nullptr, B.db, nullptr, Tf, 1);
     gp_seg(p, W.hi[W_G], nullptr, D.d, 0);
-    TRY(run_gemm(0, 1, p, st, "db gemm (gate)"));
+    TRY(run_gemm(h, 0, 1, p, st, "db gemm (gate)"));
     GemmParams p2 = gp_init(D.F, 2 * D.F, D.d, D.d);
     p2.resid_kind = 1;
     gp_group(p2, B.dgu + D.F, nullptr, B.db, B.db, Tf, 1);
     gp_seg(p2, W.hi[W_U], nullptr, D.d, 0);
-    TRY(run_gemm(0, 1, p2, st, "db gemm (up)"));
+    TRY(run_gemm(h, 0, 1, p2, st, "db gemm (up)"));
   }
   if (grads->w_gate || grads->w_up) {
     GemmParams p = gp_init(Tf, 2 * D.F, D.d, D.d);
@@ -536,29 +620,33 @@ int mace_hybrid_layer_bwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
     if (grads->w_gate) gp_group(p, B.dgu, nullptr, grads->w_gate, grads->w_gate, D.F, 1);
     if (grads->w_up) gp_group(p, B.dgu + D.F, nullptr, grads->w_up, grads->w_up, D.F, 1);
     gp_seg(p, S.b, nullptr, D.d, 0);
-    TRY(run_gemm(1, 1, p, st, "dWg/dWu gemm"));
+    TRY(run_gemm(h, 1, 1, p, st, "dWg/dWu gemm"));
   }
   // RMSNorm (MLP) backward: dx1 = dy + ...
+  prof_mark(h, st, T_RMSNORM);
   HIP_TRY(launch_rmsnorm_bwd(B.db, S.x1, false, nullptr, w->g_mlp, D.bf, S.rstd2, dy_ft, Tf, D.d, B.dx1, B.dx1_bf, B.dg_part, n_part, st), "rmsnorm2 bwd");
-  if (grads->g_mlp) HIP_TRY(launch_colsum(B.dg_part, n_part, D.d, grads->g_mlp, acc, st), "dg2");
+  if (grads->g_mlp) { prof_mark(h, st, T_MISC); HIP_TRY(launch_colsum(B.dg_part, n_part, D.d, grads->g_mlp, acc, st), "dg2");
+  }
   // attention output projection
   {
     GemmParams p = gp_init(D.d, D.d, D.qd, D.qd);
     p.out_bf16 = 1;
     gp_group(p, B.dx1_bf, nullptr, B.dattn, nullptr, Tf, 1);
     gp_seg(p, W.hi[W_O], nullptr, D.qd, 0);
-    TRY(run_gemm(0, 1, p, st, "dattn gemm"));
+    TRY(run_gemm(h, 0, 1, p, st, "dattn gemm"));
   }
   if (grads->wo) {
     GemmParams p = gp_init(Tf, D.d, D.qd, D.qd);
     p.resid_kind = acc;
     gp_group(p, B.dx1_bf, nullptr, grads->wo, grads->wo, D.d, 1);
     gp_seg(p, S.o, nullptr, D.qd, 0);
-    TRY(run_gemm(1, 1, p, st, "dWo gemm"));
+    TRY(run_gemm(h, 1, 1, p, st, "dWo gemm"));
   }
   // attention backward, RoPE backward
+  prof_mark(h, st, T_ATTN_BWD);
   HIP_TRY(launch_attn_bwd(S.q, S.k, S.v, S.o, B.dattn, S.lse, batch->seg_offsets + batch->n_prefill + batch->n_decode, I.Ti, batch->n_ft_seq, I.max_ft, Tf,
                           D.Hq, D.Hkv, D.hd, B.dvec, B.dq, B.dk, B.dv, st), "attention bwd");
+  prof_mark(h, st, T_ROPE);
   HIP_TRY(launch_rope_bwd(B.dq, B.dk, B.dv, batch->positions + I.Ti, h->inv_freq, Tf, D.Hq, D.Hkv, D.hd, B.dqkv, st), "rope bwd");
   // da = dq Wq + dk Wk + dv Wv ; dWq, dWk, dWv
   {
@@ -570,7 +658,7 @@ int mace_hybrid_layer_bwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
       p.resid_kind = i ? 1 : 0;
       gp_group(p, as[i], nullptr, B.da, B.da, Tf, 1);
       gp_seg(p, W.hi[wi[i]], nullptr, D.d, 0);
-      TRY(run_gemm(0, 1, p, st, "da gemm"));
+      TRY(run_gemm(h, 0, 1, p, st, "da gemm"));
     }
     if (grads->wq || grads->wk || grads->wv) {
       GemmParams p = gp_init(Tf, D.nqkv, D.d, D.d);
@@ -579,12 +667,15 @@ int mace_hybrid_layer_bwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
       if (grads->wk) gp_group(p, as[1], nullptr, grads->wk, grads->wk, D.kd, 1);
       if (grads->wv) gp_group(p, as[2], nullptr, grads->wv, grads->wv, D.kd, 1);
       gp_seg(p, S.a, nullptr, D.d, 0);
-      TRY(run_gemm(1, 1, p, st, "dWqkv gemm"));
+      TRY(run_gemm(h, 1, 1, p, st, "dWqkv gemm"));
     }
   }
   // RMSNorm (attention) backward: dx = dx1 + ...
+  prof_mark(h, st, T_RMSNORM);
   HIP_TRY(launch_rmsnorm_bwd(B.da, (const char *)x + (size_t)I.Ti * D.d * es, D.bf, nullptr, w->g_attn, D.bf, S.rstd1, B.dx1, Tf, D.d, dx_ft, nullptr, B.dg_part, n_part, st), "rmsnorm1 bwd");
-  if (grads->g_attn) HIP_TRY(launch_colsum(B.dg_part, n_part, D.d, grads->g_attn, acc, st), "dg1");
+  if (grads->g_attn) { prof_mark(h, st, T_MISC); HIP_TRY(launch_colsum(B.dg_part, n_part, D.d, grads->g_attn, acc, st), "dg1");
+  }
+  prof_mark(h, st, -1);
   return MACE_OK;
 }
 
@@ -621,51 +712,64 @@ int mace_dpo_logprob_loss(mace_handle_t h, const float *h_ft, const void *g_fina
   DpoWs P = plan_dpo(D, (size_t)R, n_seq, wsb);
   const bf16_t *e_hi = (const bf16_t *)w_lm, *e_lo = nullptr;
   if (!D.bf) {
+    prof_mark(h, st, T_MISC);
     HIP_TRY(launch_split_f32((const float *)w_lm, (size_t)D.V * D.d, P.e_hi, P.e_lo, st), "split head");
     e_hi = P.e_hi; e_lo = P.e_lo;
   }
   const int Ri = (int)R;
   const bool want_grad = dh_ft || dw_lm || dg_final;
   if (Ri > 0) {
+    prof_mark(h, st, T_MISC);
     HIP_TRY(launch_loss_rows(ft_seq_offsets, prompt_lens, token_ids, n_seq, P.row_idx, P.label, P.seq_id, st), "loss rows");
+    prof_mark(h, st, T_RMSNORM);
     HIP_TRY(launch_rmsnorm_fwd(h_ft, false, P.row_idx, g_final, D.bf, Ri, D.d, h->m.rms_eps, P.n_hi, P.n_lo, P.rstd, st), "final rmsnorm");
     GemmParams p = gp_init(D.d, D.d, D.d, D.V);
     gp_group(p, P.n_hi, P.n_lo, P.logits, nullptr, Ri, D.bf ? 2 : 3);
     gp_seg(p, e_hi, e_lo, D.V, 0);
-    TRY(run_gemm(0, 0, p, st, "lm head gemm"));
+    TRY(run_gemm(h, 0, 0, p, st, "lm head gemm"));
+    prof_mark(h, st, T_LOGSOFTMAX);
     HIP_TRY(launch_logsoftmax_gather(P.logits, Ri, D.V, P.label, P.logp_t, P.lse, st), "log-softmax");
   }
+  prof_mark(h, st, T_MISC);
   HIP_TRY(launch_dpo_pairs(P.logp_t, ft_seq_offsets, prompt_lens, n_seq, ref_logp, beta, logp_out, loss_per_pair, loss_mean, clpd_out, win_out, P.dlogp, st), "dpo pairs");
-  if (!want_grad) return MACE_OK;
+  if (!want_grad) { prof_mark(h, st, -1); return MACE_OK; }
   const int acc = accumulate ? 1 : 0;
-  if (dh_ft) HIP_TRY(launch_fill_f32(dh_ft, (size_t)Tf * D.d, 0.f, st), "zero dh");
+  if (dh_ft) { prof_mark(h, st, T_MISC); HIP_TRY(launch_fill_f32(dh_ft, (size_t)Tf * D.d, 0.f, st), "zero dh");
+  }
   if (Ri == 0) {
     if (!acc) {
-      if (dw_lm) HIP_TRY(launch_fill_f32(dw_lm, (size_t)D.V * D.d, 0.f, st), "zero dE");
-      if (dg_final) HIP_TRY(launch_fill_f32(dg_final, (size_t)D.d, 0.f, st), "zero dg");
+      if (dw_lm) { prof_mark(h, st, T_MISC); HIP_TRY(launch_fill_f32(dw_lm, (size_t)D.V * D.d, 0.f, st), "zero dE");
+  }
+      if (dg_final) { prof_mark(h, st, T_MISC); HIP_TRY(launch_fill_f32(dg_final, (size_t)D.d, 0.f, st), "zero dg");
+  }
     }
+    prof_mark(h, st, -1);
     return MACE_OK;
   }
+  prof_mark(h, st, T_DLOGITS);
   HIP_TRY(launch_dlogits(P.logits, Ri, D.V, P.label, P.seq_id, P.lse, P.dlogp, P.dl, st), "dlogits");
   if (dw_lm) {
     GemmParams p = gp_init(Ri, D.V, D.d, D.d);
     p.resid_kind = acc;
     gp_group(p, P.dl, nullptr, dw_lm, dw_lm, D.V, 1);
     gp_seg(p, P.n_hi, nullptr, D.d, 0);
-    TRY(run_gemm(1, 1, p, st, "dE gemm"));
+    TRY(run_gemm(h, 1, 1, p, st, "dE gemm"));
   }
   if (dh_ft || dg_final) {
     GemmParams p = gp_init(D.V, D.V, D.d, D.d);
     gp_group(p, P.dl, nullptr, P.dn, nullptr, Ri, 1);
     gp_seg(p, e_hi, nullptr, D.d, 0);
-    TRY(run_gemm(0, 1, p, st, "dn gemm"));
+    TRY(run_gemm(h, 0, 1, p, st, "dn gemm"));
     const int n_part = Ri < DG_PARTS ? Ri : DG_PARTS;
     // without dh_ft the row gradients still have to land somewhere: reuse the logits buffer
     float *dx_dst = dh_ft ? dh_ft : P.logits;
     if (!dh_ft && (size_t)Tf * D.d > (size_t)Ri * D.V) return fail(MACE_INVALID_ARG, "dg_final without dh_ft needs T_f*d <= R*V");
+    prof_mark(h, st, T_RMSNORM);
     HIP_TRY(launch_rmsnorm_bwd(P.dn, h_ft, false, P.row_idx, g_final, D.bf, P.rstd, nullptr, Ri, D.d, dx_dst, nullptr, P.dg_part, n_part, st), "final rmsnorm bwd");
-    if (dg_final) HIP_TRY(launch_colsum(P.dg_part, n_part, D.d, dg_final, acc, st), "dg_final");
+    if (dg_final) { prof_mark(h, st, T_MISC); HIP_TRY(launch_colsum(P.dg_part, n_part, D.d, dg_final, acc, st), "dg_final");
+    }
   }
+  prof_mark(h, st, -1);
   return MACE_OK;
 }
 

@@ -1,0 +1,59 @@
+"""CPU-side checks of the boundary: the shared library loads, exports every symbol that
+include/mace.h declares, and its host-only entry point (slot mapping) is integer-exact."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "mace.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mace_[a-z_0-9]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2510_03283_amd import binding, build
+    if not os.path.exists(binding.lib_path()):
+        build.build_library()
+    return binding.load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    from paper_2510_03283_amd import binding
+    syms = declared_symbols()
+    assert len(syms) >= 11
+    for s in syms:
+        assert hasattr(lib, s), f"{s} declared in mace.h but not exported"
+    assert sorted(binding.EXPORTS) == syms
+
+
+def test_slot_mapping_matches_oracle_bit_exactly(lib):
+    from oracle import mace_oracle as O
+    from paper_2510_03283_amd import binding as B
+    rng = np.random.default_rng(0)
+    for Bsz in (1, 2, 16, 64):
+        for _ in range(5):
+            nb = int(rng.integers(1, 40))
+            bt = rng.permutation(1000)[:nb].astype(np.int32)
+            start = int(rng.integers(0, nb * Bsz))
+            n = int(rng.integers(0, nb * Bsz - start + 1))
+            got = B.mace_kv_slot_mapping(bt, Bsz, start, n)
+            assert got.dtype == np.int32
+            assert np.array_equal(got.astype(np.int64), O.slot_mapping(bt, Bsz, start, n))
+    # block-boundary context: the new token of a request with 32 cached tokens opens block 2
+    assert list(B.mace_kv_slot_mapping(np.array([7, 3, 9], np.int32), 16, 32, 1)) == [9 * 16]
+
+
+def test_slot_mapping_error_paths(lib):
+    from paper_2510_03283_amd import binding as B
+    with pytest.raises(B.MaceError):
+        B.mace_kv_slot_mapping(np.array([1, 2], np.int32), 16, 30, 5)     # runs past the table
+    with pytest.raises(B.MaceError):
+        B.mace_kv_slot_mapping(np.array([1, -1], np.int32), 16, 16, 1)    # negative block id
+    with pytest.raises(B.MaceError):
+        B.mace_kv_slot_mapping(np.array([1, 2], np.int32), 12, 0, 1)      # block size not a power of two

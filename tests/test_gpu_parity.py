@@ -1,0 +1,230 @@
+"""GPU parity: the HIP library, called through its C ABI, against the fp64 CPU oracle on the same
+seeded inputs.  Bars (from the benchmark definition): cache slots, gather indices and gathered
+payload bit-exact; outputs max|a-b|/max|b| <= 1e-2; |loss - loss_oracle| <= 1e-3; gradients
+||a-b||_F/||b||_F <= 2e-2."""
+import numpy as np
+import pytest
+
+from helpers import max_abs_norm_err, rel_fro_err, run_oracle
+from paper_2510_03283_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL_OUT, TOL_LOSS, TOL_GRAD = 1e-2, 1e-3, 2e-2
+
+
+@pytest.fixture(scope="module")
+def torch_mod():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2510_03283_amd import binding
+    binding.load()          # no fallback: a missing library is an error
+    return torch
+
+
+def check_iteration(torch, wl, label, check_grads=True):
+    """Run forward + DPO head + backward on the GPU and compare everything with the oracle."""
+    from paper_2510_03283_amd.harness import DeviceIteration
+    ref = run_oracle(wl, backward=check_grads)
+    it = DeviceIteration(wl)
+    try:
+        print(f"[{label}] T={it.T} (prefill {it.Tp}, decode {it.Td}, ft {it.Tf}), loss rows {it.R}", flush=True)
+        it.forward()
+        torch.cuda.synchronize()
+        y = it.y.cpu().numpy()
+        assert np.all(np.isfinite(y))
+        for nm, lo, hi in (("prefill", 0, it.Tp), ("decode", it.Tp, it.Ti), ("ft", it.Ti, it.T)):
+            if hi > lo:
+                e = max_abs_norm_err(y[lo:hi], ref["y"][lo:hi])
+                print(f"[{label}] y {nm}: {e:.2e}", flush=True)
+                assert e <= TOL_OUT, (label, nm, e)
+        # integer side: the slots the library computed are the oracle's, bit for bit
+        assert np.array_equal(it.slot_mapping_host.astype(np.int64), ref["slots"])
+        if it.Ti:
+            ck, cv = it.cache_k.float().cpu().numpy(), it.cache_v.float().cpu().numpy()
+            assert max_abs_norm_err(ck, ref["cache_k"]) <= TOL_OUT and max_abs_norm_err(cv, ref["cache_v"]) <= TOL_OUT
+        if it.n_pairs == 0:
+            return
+        it.dpo(check_grads)
+        torch.cuda.synchronize()
+        head = ref["head"]
+        logp = it.logp.cpu().numpy()[:2 * it.n_pairs].astype(np.float64)
+        dl = abs(it.loss_mean.item() - head["loss_mean"])
+        dlp = np.abs(it.loss_pair.cpu().numpy()[:it.n_pairs] - head["loss_per_pair"]).max()
+        print(f"[{label}] |dloss| {dl:.2e}, worst pair {dlp:.2e}, max |dlogp| {np.abs(logp - head['logp']).max():.2e}", flush=True)
+        assert dl <= TOL_LOSS and dlp <= TOL_LOSS, (label, dl, dlp)
+        clpd = it.clpd.cpu().numpy()[:it.n_pairs]
+        assert np.allclose(clpd, logp[0::2] - logp[1::2], rtol=1e-6, atol=1e-4)
+        assert np.array_equal(it.win.cpu().numpy()[:it.n_pairs], (clpd > 0).astype(np.int32))
+        assert np.array_equal(it.win.cpu().numpy()[:it.n_pairs], head["win"])
+        if not check_grads:
+            return
+        for nm, a, b in (("dh", it.dh, ref["dy_ft"]), ("dE", it.dE, ref["grads"]["E"]), ("dgf", it.dgf, ref["grads"]["gf"])):
+            e = rel_fro_err(a.cpu().numpy(), b)
+            print(f"[{label}] {nm}: {e:.2e}", flush=True)
+            assert e <= TOL_GRAD, (label, nm, e)
+        # rows without loss get an exactly zero gradient
+        dh = it.dh.cpu().numpy()
+        assert np.array_equal(dh == 0, ref["dy_ft"] == 0) or np.all(dh[ref["dy_ft"] == 0] == 0)
+        it.backward()
+        torch.cuda.synchronize()
+        e = rel_fro_err(it.dx.cpu().numpy(), ref["dx_ft"])
+        print(f"[{label}] dx: {e:.2e}", flush=True)
+        assert e <= TOL_GRAD
+        for k in it.grads:
+            e = rel_fro_err(it.grads[k].cpu().numpy(), ref["grads"][k])
+            print(f"[{label}] d{k}: {e:.2e}", flush=True)
+            assert e <= TOL_GRAD, (label, k, e)
+    finally:
+        it.close()
+
+
+def custom_workload(name, dims, prefill, decode, n_pairs, prompt, resp, block_size=16, seed=77):
+    spec = synth.ConfigSpec(name, seed, dims, list(prefill), None, list(decode), None, n_pairs, prompt, None, resp,
+                            ref_mode="len", block_size=block_size)
+    synth.CONFIGS[name] = spec
+    try:
+        return synth.make_workload(name)
+    finally:
+        del synth.CONFIGS[name]
+
+
+# ------------------------------------------------------------------ whole configurations
+
+def test_tiny_iteration(torch_mod):
+    check_iteration(torch_mod, synth.make_workload("tiny"), "tiny")
+
+
+def test_edge_iteration_full_size(torch_mod):
+    """The benchmark workload at full size, in the launch configuration bench.py times."""
+    check_iteration(torch_mod, synth.make_workload("edge"), "edge")
+
+
+@pytest.fixture(scope="module")
+def weights_7b():
+    return synth.make_weights(synth.CONFIGS["7b"])
+
+
+def test_7b_subsampled(torch_mod, weights_7b):
+    """7B-class layer (hd 128, MHA, d 4096): one prefill request, two decode requests and one pair
+    with their full per-request shapes."""
+    wl = synth.make_workload("7b", n_prefill=1, n_decode=2, n_pairs=1, weights=weights_7b)
+    check_iteration(torch_mod, wl, "7b[1,2,1]")
+
+
+def test_7b_decode_heavy_subsampled(torch_mod, weights_7b):
+    """Decode-heavy shapes: contexts up to 8192 tokens (many KV splits per request); forward only."""
+    wl = synth.make_workload("7b_decode", n_prefill=0, n_decode=6, n_pairs=1, weights=weights_7b)
+    check_iteration(torch_mod, wl, "7b_decode[0,6,1]", check_grads=False)
+
+
+# ------------------------------------------------------------------ ragged and degenerate batches
+
+SMALL = dict(d_model=256, d_ff=448, vocab=1024)
+
+
+@pytest.mark.parametrize("hq,hkv,hd,bf", [(4, 4, 64, True), (4, 1, 64, True), (8, 1, 64, False), (2, 2, 128, True), (4, 2, 128, False)])
+def test_ragged_batches(torch_mod, hq, hkv, hd, bf):
+    dims = synth.ModelDims(n_q_heads=hq, n_kv_heads=hkv, head_dim=hd, io_bf16=bf, **SMALL)
+    wl = custom_workload("ragged", dims, prefill=[1, 63, 64, 65, 129, 200], decode=[0, 1, 15, 16, 17, 511, 512, 513, 1100],
+                         n_pairs=2, prompt=5, resp=(1, 140))
+    check_iteration(torch_mod, wl, f"ragged Hq{hq} Hkv{hkv} hd{hd} bf{bf}")
+
+
+@pytest.mark.parametrize("bs", [1, 4, 128])
+def test_block_sizes(torch_mod, bs):
+    dims = synth.ModelDims(n_q_heads=4, n_kv_heads=2, head_dim=64, **SMALL)
+    wl = custom_workload("blocks", dims, prefill=[7, 130], decode=[0, 3, 127, 128, 300], n_pairs=1, prompt=3, resp=(2, 9), block_size=bs)
+    check_iteration(torch_mod, wl, f"block_size {bs}")
+
+
+@pytest.mark.parametrize("prefill,decode,pairs", [([], [], 2), ([50, 3], [], 0), ([], [40, 2], 0), ([9], [5], 1)])
+def test_empty_classes(torch_mod, prefill, decode, pairs):
+    dims = synth.ModelDims(n_q_heads=4, n_kv_heads=4, head_dim=64, **SMALL)
+    wl = custom_workload("empty", dims, prefill=prefill, decode=decode, n_pairs=pairs, prompt=4, resp=(3, 20))
+    check_iteration(torch_mod, wl, f"classes {len(prefill)}/{len(decode)}/{pairs}")
+
+
+def test_batch_composition_invariance(torch_mod):
+    """Colocation must not change results (Fig. 1): a decode request alone gives the same bits as
+    inside the mixed batch, and so does a prefill request."""
+    torch = torch_mod
+    from paper_2510_03283_amd.harness import DeviceIteration
+    dims = synth.ModelDims(n_q_heads=4, n_kv_heads=2, head_dim=64, **SMALL)
+    full = custom_workload("mix", dims, prefill=[70], decode=[90], n_pairs=1, prompt=6, resp=(10, 30))
+    alone = custom_workload("mix", dims, prefill=[70], decode=[], n_pairs=0, prompt=6, resp=(10, 30))
+    a, b = DeviceIteration(full), DeviceIteration(alone)
+    a.forward(); b.forward()
+    torch.cuda.synchronize()
+    assert torch.equal(a.y[:70], b.y[:70])
+    a.close(); b.close()
+
+
+# ------------------------------------------------------------------ paged cache entry points
+
+@pytest.mark.parametrize("bf,bs", [(True, 16), (False, 16), (True, 1), (True, 64)])
+def test_kv_append_gather_bit_exact(torch_mod, bf, bs):
+    torch = torch_mod
+    from oracle import mace_oracle as O
+    from paper_2510_03283_amd import binding as B
+    Hkv, hd, n = 2, 64, 157
+    h = B.mace_create(256, 4, Hkv, hd, 448, 1024, 1e-6, 1e4, B.MACE_BF16 if bf else B.MACE_F32)
+    dt = torch.bfloat16 if bf else torch.float32
+    rng = np.random.default_rng(5)
+    nb = -(-n // bs)
+    table = rng.permutation(nb + 9)[:nb].astype(np.int32)
+    num_blocks = nb + 9
+    k_np = synth.round_to_bf16(rng.normal(size=(n, Hkv, hd)).astype(np.float32))
+    v_np = synth.round_to_bf16(rng.normal(size=(n, Hkv, hd)).astype(np.float32))
+    slots = B.mace_kv_slot_mapping(table, bs, 0, n)
+    assert np.array_equal(slots.astype(np.int64), O.slot_mapping(table, bs, 0, n))
+    slots_skip = slots.copy()
+    slots_skip[[3, 50]] = -1
+    ck = torch.zeros((num_blocks, Hkv, bs, hd), dtype=dt, device="cuda")
+    cv = torch.zeros_like(ck)
+    cache = B.kv_cache_struct(ck, cv, num_blocks, bs)
+    k_d, v_d = torch.from_numpy(k_np).cuda().to(dt), torch.from_numpy(v_np).cuda().to(dt)
+    B.mace_kv_cache_append(h, cache, k_d, v_d, torch.from_numpy(slots_skip).cuda(), n)
+    # oracle side
+    ock, ocv = O.new_cache(num_blocks, Hkv, bs, hd), O.new_cache(num_blocks, Hkv, bs, hd)
+    O.kv_append(ock, k_np, slots_skip); O.kv_append(ocv, v_np, slots_skip)
+    torch.cuda.synchronize()
+    assert np.array_equal(ck.float().cpu().numpy().astype(np.float64), ock)
+    assert np.array_equal(cv.float().cpu().numpy().astype(np.float64), ocv)
+    # gather back
+    ko, vo = torch.empty((n, Hkv, hd), dtype=dt, device="cuda"), torch.empty((n, Hkv, hd), dtype=dt, device="cuda")
+    so = torch.empty(n, dtype=torch.int64, device="cuda")
+    B.mace_kv_cache_gather(h, cache, torch.from_numpy(table).cuda(), n, ko, vo, so)
+    torch.cuda.synchronize()
+    gk, gs = O.kv_gather(ock, table, n)
+    assert np.array_equal(so.cpu().numpy(), gs)
+    assert np.array_equal(ko.float().cpu().numpy().astype(np.float64), gk)
+    B.mace_destroy(h)
+
+
+def test_error_paths_return_codes(torch_mod):
+    torch = torch_mod
+    from paper_2510_03283_amd import binding as B
+    for bad in (dict(head_dim=80), dict(n_kv_heads=3), dict(d_model=200), dict(vocab=1000), dict(n_q_heads=12, n_kv_heads=1)):
+        kw = dict(d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=64, d_ff=448, vocab=1024, rms_eps=1e-6, rope_theta=1e4, io_dtype=B.MACE_BF16)
+        kw.update(bad)
+        with pytest.raises(B.MaceError):
+            B.mace_create(**kw)
+    from paper_2510_03283_amd.harness import DeviceIteration
+    wl = synth.make_workload("tiny")
+    it = DeviceIteration(wl)
+    small = torch.empty(1024, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.MaceError, match="workspace"):
+        B.mace_hybrid_layer_fwd(it.h, it.w_struct, it.batch, it.cache, it.x, it.y, it.saved, small)
+    bad = B.BatchDesc(2, 4, 2, it.T, np.asarray(wl.batch.seg_offsets) + 1, it.seg_dev, it.pos_dev, it.slot_dev, it.bt_dev,
+                      np.asarray(wl.batch.decode_ctx, np.int32), it.ctx_dev, wl.batch.max_blocks_per_req)
+    with pytest.raises(B.MaceError):
+        B.mace_hybrid_layer_fwd(it.h, it.w_struct, bad, it.cache, it.x, it.y, it.saved, it.ws)
+    too_long = B.BatchDesc(2, 4, 2, it.T, wl.batch.seg_offsets, it.seg_dev, it.pos_dev, it.slot_dev, it.bt_dev,
+                           np.asarray(wl.batch.decode_ctx, np.int32) + 100000, it.ctx_dev, wl.batch.max_blocks_per_req)
+    with pytest.raises(B.MaceError, match="block table"):
+        B.mace_hybrid_layer_fwd(it.h, it.w_struct, too_long, it.cache, it.x, it.y, it.saved, it.ws)
+    it.step()        # the handle still works after rejected calls
+    torch.cuda.synchronize()
+    assert torch.isfinite(it.loss_mean).all()
+    it.close()
