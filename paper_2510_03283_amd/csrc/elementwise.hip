@@ -107,12 +107,22 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const float *dy, const
   }
 }
 
+// 32 columns per block; the 8 thread rows of a block stride over the partial rows, then reduce in LDS.
 __global__ __launch_bounds__(256) void colsum_kernel(const float *part, int n_part, int d, float *out, int accumulate) {
-  const int j = blockIdx.x * 256 + threadIdx.x;
-  if (j >= d) return;
+  __shared__ float red[8][33];
+  const int c = threadIdx.x & 31, rg = threadIdx.x >> 5;
+  const int j = blockIdx.x * 32 + c;
   float s = 0.f;
-  for (int i = 0; i < n_part; ++i) s += part[(size_t)i * d + j];
-  out[j] = accumulate ? out[j] + s : s;
+  if (j < d)
+    for (int i = rg; i < n_part; i += 8) s += part[(size_t)i * d + j];
+  red[rg][c] = s;
+  __syncthreads();
+  if (rg == 0 && j < d) {
+    float t = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) t += red[k][c];
+    out[j] = accumulate ? out[j] + t : t;
+  }
 }
 
 // ------------------------------------------------------------------ rotary embedding
@@ -279,7 +289,7 @@ hipError_t launch_rmsnorm_bwd(const float *dy, const void *x, bool x_bf16, const
 }
 
 hipError_t launch_colsum(const float *part, int n_part, int d, float *out, int accumulate, hipStream_t st) {
-  hipLaunchKernelGGL(colsum_kernel, dim3(cdiv(d, 256)), dim3(256), 0, st, part, n_part, d, out, accumulate);
+  hipLaunchKernelGGL(colsum_kernel, dim3(cdiv(d, 32)), dim3(256), 0, st, part, n_part, d, out, accumulate);
   return hipGetLastError();
 }
 

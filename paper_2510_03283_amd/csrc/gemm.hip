@@ -139,28 +139,32 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const GemmPar
   sb.store(Bs);
   __syncthreads();
 
+  bf16x8_t af[2][TM], bfr[2][TN];                 // fragments double-buffered over the k steps
   for (int it = 0; it < n_it; ++it) {
     const int cur = it & 1;
     if (it + 1 < n_it) issue(it + 1);             // global loads fly during the MFMA phase
     const bf16_t *Ac = As + cur * SA::ELEMS, *Bc = Bs + cur * SB::ELEMS;
-    bf16x8_t af[2][TM], bfr[2][TN];               // fragments double-buffered over the k steps
 #pragma unroll
     for (int i = 0; i < TM; ++i) af[0][i] = SA::frag(Ac, aoff[i], 0);
 #pragma unroll
     for (int j = 0; j < TN; ++j) bfr[0][j] = SB::frag(Bc, boff[j], 0);
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
+      // the LDS reads of step kk+1 are issued ahead of the MFMAs of step kk; the fences keep the
+      // compiler from sinking them back next to their uses
       if (kk + 1 < BK / 16) {
 #pragma unroll
         for (int i = 0; i < TM; ++i) af[(kk + 1) & 1][i] = SA::frag(Ac, aoff[i], kk + 1);
 #pragma unroll
         for (int j = 0; j < TN; ++j) bfr[(kk + 1) & 1][j] = SB::frag(Bc, boff[j], kk + 1);
       }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
     if (it + 1 < n_it) {
       sa.store(As + (cur ^ 1) * SA::ELEMS);
@@ -170,22 +174,26 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const GemmPar
   }
 
   // epilogue: accumulator register r of a 32x32 tile holds row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
+  const int rk = p.resid_kind, obf = p.out_bf16;
+  const long long ldc = p.ldc, ldr = p.ldr;
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int col = n0 + wn * WTN + j * 32 + (lane & 31);
+      const int rbase = m0 + wm * WTM + i * 32 + 4 * (lane >> 5);
       if (col >= N) continue;
+      const long long cc = S.c_col + col;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (row >= M) continue;
-        float v = acc[i][j][r];
-        if (p.resid_kind == 1) v += ((const float *)G.resid)[(long long)row * p.ldr + S.c_col + col];
-        else if (p.resid_kind == 2) v += bf2f(((const bf16_t *)G.resid)[(long long)row * p.ldr + S.c_col + col]);
-        const long long o = (long long)row * p.ldc + S.c_col + col;
-        if (p.out_bf16) ((bf16_t *)G.c)[o] = f2bf(v);
-        else ((float *)G.c)[o] = v;
+        const int row = rbase + 8 * (r >> 2) + (r & 3);
+        if (row < M) {
+          float v = acc[i][j][r];
+          if (rk == 1) v += ((const float *)G.resid)[row * ldr + cc];
+          else if (rk == 2) v += bf2f(((const bf16_t *)G.resid)[row * ldr + cc]);
+          if (obf) ((bf16_t *)G.c)[row * ldc + cc] = f2bf(v);
+          else ((float *)G.c)[row * ldc + cc] = v;
+        }
       }
     }
   }
