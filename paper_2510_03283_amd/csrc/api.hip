@@ -196,7 +196,7 @@ BwdWs plan_bwd(const Dims &D, size_t Tf, Bump &w) {
 struct DpoWs {
   int32_t *row_idx, *label, *seq_id;
   bf16_t *n_hi, *n_lo, *dl, *e_hi, *e_lo;
-  float *rstd, *logits, *logp_t, *lse, *dlogp, *dn, *dg_part;
+  float *rstd, *logits, *logp_t, *lse, *dlogp, *dn, *dn_part, *dg_part;
 };
 DpoWs plan_dpo(const Dims &D, size_t R, size_t n_seq, Bump &w) {
   DpoWs P;
@@ -212,6 +212,7 @@ DpoWs plan_dpo(const Dims &D, size_t R, size_t n_seq, Bump &w) {
   P.dlogp = w.take<float>(n_seq);
   P.dl = w.take<bf16_t>(R * D.V);
   P.dn = w.take<float>(R * D.d);
+  P.dn_part = w.take<float>(R * D.d * (size_t)(gemm_suggest_k_splits((int)R, D.d, D.V) > 1 ? gemm_suggest_k_splits((int)R, D.d, D.V) : 0));
   P.dg_part = w.take<float>((size_t)DG_PARTS * D.d);
   if (!D.bf) {
     P.e_hi = w.take<bf16_t>((size_t)D.V * D.d);
@@ -756,10 +757,14 @@ int mace_dpo_logprob_loss(mace_handle_t h, const float *h_ft, const void *g_fina
     TRY(run_gemm(h, 1, 1, p, st, "dE gemm"));
   }
   if (dh_ft || dg_final) {
+    // small output, reduction over the whole vocabulary: slice k so that every CU has work
+    const int ks = gemm_suggest_k_splits(Ri, D.d, D.V);
     GemmParams p = gp_init(D.V, D.V, D.d, D.d);
-    gp_group(p, P.dl, nullptr, P.dn, nullptr, Ri, 1);
+    gp_group(p, P.dl, nullptr, ks > 1 ? P.dn_part : P.dn, nullptr, Ri, 1);
     gp_seg(p, e_hi, nullptr, D.d, 0);
+    if (ks > 1) { p.k_splits = ks; p.c_split_stride = (long long)Ri * D.d; }
     TRY(run_gemm(h, 0, 1, p, st, "dn gemm"));
+    if (ks > 1) { prof_mark(h, st, T_MISC); HIP_TRY(launch_sum_partials(P.dn_part, ks, (size_t)Ri * D.d, P.dn, st), "dn partial sums"); }
     const int n_part = Ri < DG_PARTS ? Ri : DG_PARTS;
     // without dh_ft the row gradients still have to land somewhere: reuse the logits buffer
     float *dx_dst = dh_ft ? dh_ft : P.logits;

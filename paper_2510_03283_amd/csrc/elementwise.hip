@@ -257,6 +257,18 @@ __global__ __launch_bounds__(256) void split_f32_kernel(const float *src, size_t
   }
 }
 
+__global__ __launch_bounds__(256) void sum_partials_kernel(const float *part, int n_part, size_t n, float *out) {
+  const size_t stride = (size_t)gridDim.x * 256 * 4;
+  for (size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4; i < n; i += stride) {   // n % 4 == 0
+    float4 a = *(const float4 *)(part + i);
+    for (int s = 1; s < n_part; ++s) {
+      const float4 b = *(const float4 *)(part + (size_t)s * n + i);
+      a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    }
+    *(float4 *)(out + i) = a;
+  }
+}
+
 __global__ __launch_bounds__(256) void fill_f32_kernel(float *dst, size_t n, float v) {
   const size_t stride = (size_t)gridDim.x * 256;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) dst[i] = v;
@@ -337,5 +349,13 @@ hipError_t launch_fill_f32(float *dst, size_t n, float v, hipStream_t st) {
   if (n == 0) return hipSuccess;
   const unsigned blocks = (unsigned)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
   hipLaunchKernelGGL(fill_f32_kernel, dim3(blocks), dim3(256), 0, st, dst, n, v);
+  return hipGetLastError();
+}
+
+hipError_t launch_sum_partials(const float *part, int n_part, size_t n, float *out, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  if (n % 4) return hipErrorInvalidValue;
+  const size_t want = (n / 4 + 255) / 256;
+  hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)(want < 4096 ? want : 4096)), dim3(256), 0, st, part, n_part, n, out);
   return hipGetLastError();
 }

@@ -33,9 +33,15 @@ struct GemmParams {
   long long lda, ldb, ldc, ldr;
   int out_bf16;     // 0: C is fp32, 1: C is bf16
   int resid_kind;   // 0 none, 1 fp32, 2 bf16 ; C = acc + resid
+  int k_splits;     // > 1: grid.y slices of the k range; slice z writes fp32 partial sums at C + z * c_split_stride
+  long long c_split_stride;   // elements
   int mt_start[4];  // filled by gemm_launch
   int nt_start[4];
 };
+
+// Number of k slices worth using for a single-group, single-segment problem (1 = none): small
+// outputs with a long reduction leave most CUs idle otherwise.
+int gemm_suggest_k_splits(int M, int N, int K);
 
 // Returns hipSuccess or the launch error; a non-null *why is set on a rejected shape.
 hipError_t gemm_launch(int LA, int LB, GemmParams &p, hipStream_t stream, const char **why);

@@ -1,71 +1,98 @@
-// bf16 MFMA GEMM for gfx950: 32x32x16 MFMA tiles, LDS double buffer, 64-wide k tiles.
+// bf16 MFMA GEMM for gfx950: 32x32x16 MFMA tiles, direct global->LDS operand loads, LDS double
+// buffer of 64-wide k tiles.
 //
-// Operand tiles are staged global -> registers -> LDS with 16-byte accesses in the layout they
-// have in memory: a k-contiguous operand as [row][k], a row-contiguous operand as [k][row].
-// MFMA fragments (8 consecutive k of one row per lane) come from one 16-byte LDS read in the
-// first case and from two transposing 8-byte LDS reads (ds_read_b64_tr_b16) in the second, so
-// the NN and TN forms need no transposed copies in HBM and no in-register shuffles.
+// Tiles sit in LDS in the layout they have in memory: a k-contiguous operand as [row][k], a
+// row-contiguous operand as [k][row].  MFMA fragments (8 consecutive k of one row per lane) come
+// from one 16-byte LDS read in the first case and from two transposing 8-byte LDS reads
+// (ds_read_b64_tr_b16) in the second, so the NN and TN forms need no transposed copies in HBM
+// and no in-register shuffles.
 #include "gemm.h"
+
+#include <cmath>
 
 namespace {
 
 constexpr int BK = 64;          // k extent of an LDS tile
+constexpr int NSTAGES = 2;
 
 typedef __attribute__((ext_vector_type(4))) short s16x4_t;
 typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
 
-// Global -> register -> LDS staging of one operand tile of ROWS rows (m or n) by BK.
-// LAYOUT 0: memory [row][k];  LDS [ROWS][BK + 8]   (pitch 144 B: 16-byte fragment reads conflict-free)
-// LAYOUT 1: memory [k][row];  LDS [BK][ROWS + 32]  (pitch = 64 B mod 256 B: 4 k-rows of a transposing read hit disjoint banks)
-template <int ROWS, int LAYOUT, int NTHR>
-struct TileStage {
-  static constexpr int PITCH = LAYOUT == 0 ? BK + 8 : ROWS + 32;
-  static constexpr int ELEMS = LAYOUT == 0 ? ROWS * PITCH : BK * PITCH;   // per stage
-  static constexpr int NCH = ROWS * BK / 8;            // 16-byte chunks of the tile
-  static constexpr int NV = (NCH + NTHR - 1) / NTHR;   // chunks per thread
-  static constexpr int CPR = LAYOUT == 0 ? BK / 8 : ROWS / 8;   // chunks per memory row
-  uint4 r[NV];
+constexpr int GROUP_M = 8;   // m tiles per swizzle group (L2 reuse of the B tiles)
 
-  // rows: valid extent of the row index; K: valid extent of k (only checked for LAYOUT 1, where k is a token count)
-  __device__ __forceinline__ void load(const bf16_t *base, long long ld, int row0, int rows, int k0, int K) {
+// Operand tiles go global -> LDS directly (global_load_lds_dwordx4): no staging registers and no
+// LDS store instructions.  A wave-wide load writes 64 consecutive 16-byte chunks, so LDS tiles
+// are unpadded; bank conflicts are avoided by an XOR swizzle that is applied through the choice
+// of the global address each lane fetches.
+__device__ __align__(16) uint4 g_zero16 = {0u, 0u, 0u, 0u};   // source of out-of-range chunks
+
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void gbl_void_t;
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {   // vmcnt <= N, no wait on the other counters
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+template <int ROWS, int LAYOUT, int BKT, int NTHR>
+struct DirectStage {
+  static constexpr int ELEMS = ROWS * BKT;
+  static constexpr int NCH = ROWS * BKT / 8;             // 16-byte chunks
+  static constexpr int NI = NCH / NTHR;                  // wave-wide loads per wave
+  static_assert(NCH % NTHR == 0, "tile must split evenly over the waves");
+  static constexpr int CPR = LAYOUT == 0 ? BKT / 8 : ROWS / 8;   // chunks per LDS row
+  static constexpr int RPB = LAYOUT == 0 ? 16 / CPR : 1;         // LDS rows per 256 bytes (LAYOUT 0)
+
+  // LAYOUT 0: LDS [row][BKT], chunk position pos holds logical k-chunk pos ^ ((row / RPB) % CPR)
+  // LAYOUT 1: LDS [k][ROWS],  chunk position pos holds logical row-chunk pos ^ ((k & 3) << 2)
+  static __device__ __forceinline__ void issue(const bf16_t *base, long long ld, int row0, int rows, int k0, int K, bf16_t *S) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      const int c = threadIdx.x + NTHR * i;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (NCH % NTHR == 0 || c < NCH) {
-        if constexpr (LAYOUT == 0) {
-          const int gr = row0 + c / CPR;
-          if (gr < rows) v = *(const uint4 *)(base + (long long)gr * ld + k0 + (c % CPR) * 8);
-        } else {
-          const int k = k0 + c / CPR, gr = row0 + (c % CPR) * 8;
-          if (k < K && gr < rows) v = *(const uint4 *)(base + (long long)k * ld + gr);
-        }
+    for (int i = 0; i < NI; ++i) {
+      const int q = wave + (NTHR / 64) * i;
+      const int chunk = q * 64 + lane;
+      const int lr = chunk / CPR, pos = chunk % CPR;
+      const bf16_t *src;
+      bool ok;
+      if constexpr (LAYOUT == 0) {
+        const int kc = pos ^ ((lr / RPB) % CPR);
+        const int gr = row0 + lr;
+        ok = gr < rows;
+        src = base + (long long)gr * ld + k0 + kc * 8;
+      } else {
+        const int c = pos ^ ((lr & 3) << 2);
+        const int k = k0 + lr, gr = row0 + 8 * c;
+        ok = k < K && gr < rows;
+        src = base + (long long)k * ld + gr;
       }
-      r[i] = v;
+      if (!ok) src = (const bf16_t *)&g_zero16;
+      __builtin_amdgcn_global_load_lds((gbl_void_t *)src, (lds_void_t *)(S + q * 512), 16, 0, 0);
     }
   }
-  __device__ __forceinline__ void store(bf16_t *S) const {
-#pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      const int c = threadIdx.x + NTHR * i;
-      if (NCH % NTHR == 0 || c < NCH) *(uint4 *)(S + (c / CPR) * PITCH + (c % CPR) * 8) = r[i];
+  // per-lane fragment address pieces
+  struct Frag { int base; int sw; };
+  static __device__ __forceinline__ Frag frag_init(int r0, int lane) {
+    Frag f;
+    if constexpr (LAYOUT == 0) {
+      const int row = r0 + (lane & 31);
+      f.base = row * BKT;
+      f.sw = (row / RPB) % CPR;
+    } else {
+      const int grp = lane >> 4, j = lane & 15;
+      const int chunk = ((r0 >> 3) + 2 * (grp & 1) + ((j & 3) >> 1)) ^ ((j >> 2) << 2);
+      f.base = (8 * (grp >> 1) + (j >> 2)) * ROWS + chunk * 8 + 4 * (j & 1);
+      f.sw = 0;
     }
+    return f;
   }
-  // Per-lane element offset of the fragment of MFMA tile row block r0 (k step 0); add frag_step(kk).
-  static __device__ __forceinline__ int frag_base(int r0, int lane) {
-    if constexpr (LAYOUT == 0) return (r0 + (lane & 31)) * PITCH + (lane >> 5) * 8;
-    else {
-      const int grp = lane >> 4, j = lane & 15;          // 16-lane groups: (k half, row half)
-      return (8 * (grp >> 1) + (j >> 2)) * PITCH + r0 + 16 * (grp & 1) + 4 * (j & 3);
-    }
-  }
-  static __device__ __forceinline__ bf16x8_t frag(const bf16_t *S, int off, int kk) {
-    if constexpr (LAYOUT == 0) return *(const bf16x8_t *)(S + off + kk * 16);
-    else {
-      // lane j of a 16-lane group receives column j of the 4(k) x 16(row) patch the group addresses
-      const bf16_t *p = S + off + kk * 16 * PITCH;
+  static __device__ __forceinline__ bf16x8_t frag(const bf16_t *S, const Frag &f, int kk, int lane) {
+    if constexpr (LAYOUT == 0) {
+      const int c = (2 * kk + (lane >> 5)) ^ f.sw;
+      return *(const bf16x8_t *)(S + f.base + c * 8);
+    } else {
+      const bf16_t *p = S + f.base + kk * 16 * ROWS;
       const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)p);
-      const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(p + 4 * PITCH));
+      const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(p + 4 * ROWS));
       typedef __attribute__((ext_vector_type(8))) short s16x8_t;
       const s16x8_t v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
       return __builtin_bit_cast(bf16x8_t, v);
@@ -73,22 +100,20 @@ struct TileStage {
   }
 };
 
-constexpr int GROUP_M = 8;   // m tiles per swizzle group (L2 reuse of the B tiles)
-
-template <int BM, int BN, int WGM, int WGN, int LA, int LB>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const GemmParams p) {
+template <int BM, int BN, int WGM, int WGN, int LA, int LB, int BKT, int NST>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(const GemmParams p) {
   constexpr int NTHR = 64 * WGM * WGN;
-  constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile
-  constexpr int TM = WTM / 32, TN = WTN / 32;    // 32x32 MFMA tiles per wave
-  using SA = TileStage<BM, LA, NTHR>;
-  using SB = TileStage<BN, LB, NTHR>;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  constexpr int NKK = BKT / 16;
+  constexpr int P = NST - 1;                      // tiles in flight ahead of the one being multiplied
+  using SA = DirectStage<BM, LA, BKT, NTHR>;
+  using SB = DirectStage<BN, LB, BKT, NTHR>;
+  constexpr int STAGE = SA::ELEMS + SB::ELEMS;
+  constexpr int LPT = SA::NI + SB::NI;            // loads per thread per tile
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  bf16_t *As = (bf16_t *)smem_raw;               // [2] stages of A
-  bf16_t *Bs = As + 2 * SA::ELEMS;               // [2] stages of B
+  bf16_t *lds = (bf16_t *)smem_raw;
 
-  // block -> tile.  Consecutive block ids go to different XCDs (8 of them, one L2 each), so each
-  // XCD takes a contiguous chunk of the tile list; inside it tiles run over GROUP_M m tiles at
-  // a time so that the tiles resident on one XCD share A and B panels.
   const int total_mt = p.mt_start[p.n_mg], total_nt = p.nt_start[p.n_ns];
   const int total = total_mt * total_nt;
   int v;
@@ -107,7 +132,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const GemmPar
   const GemmNSeg &S = p.ns[s];
   const int m0 = (mt_g - p.mt_start[g]) * BM, n0 = (nt_g - p.nt_start[s]) * BN;
   const int M = G.M, N = S.N, K = p.K;
-
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
 
@@ -119,44 +143,53 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const GemmPar
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int nk = (K + BK - 1) / BK;
+  // split-K: grid.y slices the k tiles; slice z writes its partial sums at C + z * c_split_stride
+  const int nk_all = (K + BKT - 1) / BKT;
+  const int nk_per = (nk_all + (int)gridDim.y - 1) / (int)gridDim.y;
+  const int kt0 = (int)blockIdx.y * nk_per;
+  const int nk = max(0, min(nk_per, nk_all - kt0));
   const int n_it = nk * G.npass;
-  SA sa;
-  SB sb;
-  auto issue = [&](int it) {
-    const int pass = it / nk, kt = it - pass * nk;
-    sa.load(G.a[pass == 1 ? 1 : 0], p.lda, m0, M, kt * BK, K);
-    sb.load(S.b[pass == 2 ? 1 : 0], p.ldb, n0, N, kt * BK, K);
+  auto issue = [&](int it, int stage) {
+    const int pass = it / nk, kt = kt0 + it - pass * nk;
+    bf16_t *st = lds + stage * STAGE;
+    SA::issue(G.a[pass == 1 ? 1 : 0], p.lda, m0, M, kt * BKT, K, st);
+    SB::issue(S.b[pass == 2 ? 1 : 0], p.ldb, n0, N, kt * BKT, K, st + SA::ELEMS);
   };
-  int aoff[TM], boff[TN];
+  typename SA::Frag fa[TM];
+  typename SB::Frag fb[TN];
 #pragma unroll
-  for (int i = 0; i < TM; ++i) aoff[i] = SA::frag_base(wm * WTM + i * 32, lane);
+  for (int i = 0; i < TM; ++i) fa[i] = SA::frag_init(wm * WTM + i * 32, lane);
 #pragma unroll
-  for (int j = 0; j < TN; ++j) boff[j] = SB::frag_base(wn * WTN + j * 32, lane);
+  for (int j = 0; j < TN; ++j) fb[j] = SB::frag_init(wn * WTN + j * 32, lane);
 
-  issue(0);
-  sa.store(As);
-  sb.store(Bs);
-  __syncthreads();
+  // prologue: the first P tiles are requested
+#pragma unroll
+  for (int t = 0; t < P; ++t)
+    if (t < n_it) issue(t, t);
 
-  bf16x8_t af[2][TM], bfr[2][TN];                 // fragments double-buffered over the k steps
+  int st_cur = 0;
   for (int it = 0; it < n_it; ++it) {
-    const int cur = it & 1;
-    if (it + 1 < n_it) issue(it + 1);             // global loads fly during the MFMA phase
-    const bf16_t *Ac = As + cur * SA::ELEMS, *Bc = Bs + cur * SB::ELEMS;
+    // tile `it` has landed once at most the loads of the P-1 younger tiles are outstanding
+    if (it + P - 1 < n_it) wait_vmcnt<(P - 1) * LPT>();
+    else wait_vmcnt<0>();
+    __syncthreads();   // tile it visible to every wave; every wave is done with the stage of tile it-1
+    {
+      const int st_new = st_cur == 0 ? NST - 1 : st_cur - 1;   // stage of tile it-1 == stage of tile it+P
+      if (it + P < n_it) issue(it + P, st_new);
+    }
+    const bf16_t *Ac = lds + st_cur * STAGE, *Bc = Ac + SA::ELEMS;
+    bf16x8_t af[2][TM], bfr[2][TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) af[0][i] = SA::frag(Ac, aoff[i], 0);
+    for (int i = 0; i < TM; ++i) af[0][i] = SA::frag(Ac, fa[i], 0, lane);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) bfr[0][j] = SB::frag(Bc, boff[j], 0);
+    for (int j = 0; j < TN; ++j) bfr[0][j] = SB::frag(Bc, fb[j], 0, lane);
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      // the LDS reads of step kk+1 are issued ahead of the MFMAs of step kk; the fences keep the
-      // compiler from sinking them back next to their uses
-      if (kk + 1 < BK / 16) {
+    for (int kk = 0; kk < NKK; ++kk) {
+      if (kk + 1 < NKK) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) af[(kk + 1) & 1][i] = SA::frag(Ac, aoff[i], kk + 1);
+        for (int i = 0; i < TM; ++i) af[(kk + 1) & 1][i] = SA::frag(Ac, fa[i], kk + 1, lane);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bfr[(kk + 1) & 1][j] = SB::frag(Bc, boff[j], kk + 1);
+        for (int j = 0; j < TN; ++j) bfr[(kk + 1) & 1][j] = SB::frag(Bc, fb[j], kk + 1, lane);
       }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -166,11 +199,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const GemmPar
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
-    if (it + 1 < n_it) {
-      sa.store(As + (cur ^ 1) * SA::ELEMS);
-      sb.store(Bs + (cur ^ 1) * SB::ELEMS);
-    }
-    __syncthreads();
+    st_cur = st_cur == NST - 1 ? 0 : st_cur + 1;
   }
 
   // epilogue: accumulator register r of a 32x32 tile holds row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
@@ -183,7 +212,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_kernel(const GemmPar
       const int col = n0 + wn * WTN + j * 32 + (lane & 31);
       const int rbase = m0 + wm * WTM + i * 32 + 4 * (lane >> 5);
       if (col >= N) continue;
-      const long long cc = S.c_col + col;
+      const long long cc = S.c_col + col + (long long)blockIdx.y * p.c_split_stride;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row = rbase + 8 * (r >> 2) + (r & 3);
@@ -209,21 +238,21 @@ int count_tiles(GemmParams &p) {
   return mt * nt;
 }
 
-template <int BM, int BN, int WGM, int WGN, int LA, int LB>
-hipError_t launch_t(GemmParams &p, hipStream_t stream) {
+template <int BM, int BN, int WGM, int WGN, int LA, int LB, int BKT, int NST>
+hipError_t launch_dl(GemmParams &p, hipStream_t stream) {
   const int tiles = count_tiles<BM, BN>(p);
   if (tiles == 0) return hipSuccess;
   constexpr int NTHR = 64 * WGM * WGN;
-  constexpr size_t lds = (size_t)2 * (TileStage<BM, LA, NTHR>::ELEMS + TileStage<BN, LB, NTHR>::ELEMS) * sizeof(bf16_t);
+  constexpr size_t lds = (size_t)NST * (BM + BN) * BKT * sizeof(bf16_t);
   static_assert(lds <= 160 * 1024, "LDS budget of a gfx950 CU");
-  static bool attr_done = false;   // per instantiation; setting it twice is harmless
+  static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void *)gemm_bf16_kernel<BM, BN, WGM, WGN, LA, LB>,
+    hipError_t e = hipFuncSetAttribute((const void *)gemm_bf16_dl_kernel<BM, BN, WGM, WGN, LA, LB, BKT, NST>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WGM, WGN, LA, LB>), dim3((unsigned)tiles), dim3(NTHR), lds, stream, p);
+  hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, LA, LB, BKT, NST>), dim3((unsigned)tiles, (unsigned)(p.k_splits > 1 ? p.k_splits : 1)), dim3(NTHR), lds, stream, p);
   return hipGetLastError();
 }
 
@@ -231,31 +260,34 @@ bool aligned16(const void *q) { return ((uintptr_t)q & 15) == 0; }
 
 int g_force_tile = -1;
 
+// Tile choice.  256x256 tiles (8 waves, one block per CU) do 0.75 LDS fragment reads per MFMA and
+// half the L2 traffic of 128x128 tiles (4 waves, two blocks per CU), but quantise worse on small
+// problems: compare the fraction of (CU x round) slots each choice keeps busy, with a 15 %
+// handicap for the small tile's lower efficiency.
 template <int LA, int LB>
 hipError_t launch_layout(GemmParams &p, hipStream_t stream) {
   int tile = g_force_tile;
   if (tile < 0) {
-    // 256x256 tiles (8 waves) halve the LDS and L2 traffic per flop; use them once they still
-    // give every CU at least two tiles, else 128x128 tiles (4 waves, two blocks per CU).
     GemmParams q = p;
-    tile = count_tiles<256, 256>(q) >= 512 ? 3 : 0;
+    const int ks = p.k_splits > 1 ? p.k_splits : 1;
+    const double t256 = (double)count_tiles<256, 256>(q) * ks, t128 = (double)count_tiles<128, 128>(q) * ks;
+    const double e256 = t256 / (std::ceil(t256 / 256.0) * 256.0), e128 = t128 / (std::ceil(t128 / 512.0) * 512.0);
+    tile = e256 * 1.15 >= e128 ? 1 : 0;
   }
-  switch (tile) {
-    case 3: return launch_t<256, 256, 2, 4, LA, LB>(p, stream);
-    case 4: return launch_t<256, 128, 4, 2, LA, LB>(p, stream);
-    default: return launch_t<128, 128, 2, 2, LA, LB>(p, stream);
-  }
+  if (tile == 1) return launch_dl<256, 256, 2, 4, LA, LB, BK, NSTAGES>(p, stream);
+  return launch_dl<128, 128, 2, 2, LA, LB, BK, NSTAGES>(p, stream);
 }
 
 }  // namespace
 
-// development hook: pin the tile configuration (-1 = automatic)
+// development hook: pin the tile configuration (0 = 128x128, 1 = 256x256, -1 = automatic)
 void gemm_force_tile(int id) { g_force_tile = id; }
 
 hipError_t gemm_launch(int LA, int LB, GemmParams &p, hipStream_t stream, const char **why) {
   *why = nullptr;
   if (p.n_mg < 1 || p.n_mg > 3 || p.n_ns < 1 || p.n_ns > 3) { *why = "gemm: group count"; return hipErrorInvalidValue; }
   if (p.K <= 0) { *why = "gemm: K <= 0"; return hipErrorInvalidValue; }
+  if (p.k_splits > 1 && (p.resid_kind || p.out_bf16 || p.c_split_stride <= 0)) { *why = "gemm: split-K needs fp32 output without residual"; return hipErrorInvalidValue; }
   if ((LA == 0 || LB == 0) && p.K % BK) { *why = "gemm: K of a k-contiguous operand must be a multiple of 64"; return hipErrorInvalidValue; }
   if (p.lda % 8 || p.ldb % 8) { *why = "gemm: leading dimension not a multiple of 8"; return hipErrorInvalidValue; }
   for (int g = 0; g < p.n_mg; ++g) {
@@ -279,4 +311,14 @@ hipError_t gemm_launch(int LA, int LB, GemmParams &p, hipStream_t stream, const 
   if (LA == 1 && LB == 1) return launch_layout<1, 1>(p, stream);
   *why = "gemm: unsupported layout";
   return hipErrorInvalidValue;
+}
+
+int gemm_suggest_k_splits(int M, int N, int K) {
+  const long long tiles = (long long)cdiv(M, 128) * cdiv(N, 128);
+  const int nk = cdiv(K, BK);
+  if (tiles >= 256 || nk < 32) return 1;
+  long long sp = 512 / tiles;
+  if (sp > nk / 16) sp = nk / 16;
+  if (sp > 8) sp = 8;
+  return sp < 2 ? 1 : (int)sp;
 }

@@ -37,6 +37,8 @@ hipError_t launch_swiglu_bwd(const bf16_t *dhm, const float *gu, int rows, int F
 // fp32 -> (hi, lo) bf16, n elements; lo nullable.
 hipError_t launch_split_f32(const float *src, size_t n, bf16_t *hi, bf16_t *lo, hipStream_t st);
 hipError_t launch_fill_f32(float *dst, size_t n, float v, hipStream_t st);
+// out[i] = sum_s part[s * n + i], n % 4 == 0 (partial sums of a split-K GEMM, fixed order).
+hipError_t launch_sum_partials(const float *part, int n_part, size_t n, float *out, hipStream_t st);
 
 // ---- kv_cache.hip ----------------------------------------------------------------------------
 hipError_t launch_kv_append(void *cache_k, void *cache_v, bool bf16, long long num_slots, int block_size, int Hkv,
