@@ -259,6 +259,7 @@ void gp_seg(GemmParams &p, const bf16_t *b_hi, const bf16_t *b_lo, int N, int c_
 
 struct BatchInfo {
   int Tp, Td, Tf, Ti, T, n_seq_all, max_prefill, max_ft, max_ctx;
+  double pairs_prefill, pairs_ft;   // sum of L(L+1)/2 (query, key) pairs, for the algorithmic flop counts
 };
 
 int check_batch(const mace_batch_t *b, BatchInfo &I) {
@@ -269,12 +270,13 @@ int check_batch(const mace_batch_t *b, BatchInfo &I) {
   const int32_t *so = b->seg_offsets_host;
   if (so[0] != 0 || so[ns] != b->n_tokens) return fail(MACE_INVALID_ARG, "seg_offsets must start at 0 and end at n_tokens");
   I.max_prefill = I.max_ft = I.max_ctx = 0;
+  I.pairs_prefill = I.pairs_ft = 0.0;
   for (int i = 0; i < ns; ++i) {
     const int L = so[i + 1] - so[i];
     if (L < 0) return fail(MACE_INVALID_ARG, "seg_offsets not non-decreasing");
-    if (i < b->n_prefill) I.max_prefill = L > I.max_prefill ? L : I.max_prefill;
+    if (i < b->n_prefill) { I.max_prefill = L > I.max_prefill ? L : I.max_prefill; I.pairs_prefill += 0.5 * L * (L + 1.0); }
     else if (i < b->n_prefill + b->n_decode) { if (L != 1) return fail(MACE_INVALID_ARG, "a decode request must have exactly one row"); }
-    else I.max_ft = L > I.max_ft ? L : I.max_ft;
+    else { I.max_ft = L > I.max_ft ? L : I.max_ft; I.pairs_ft += 0.5 * L * (L + 1.0); }
   }
   I.Tp = so[b->n_prefill];
   I.Td = b->n_decode;
@@ -508,14 +510,16 @@ int mace_hybrid_layer_fwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
   HIP_TRY(launch_rope_split(F.qkv_f, batch->positions + I.Ti, h->inv_freq, I.Tf, D.Hq, D.Hkv, D.hd, S.q, S.k, S.v, F.q_lo, F.k_lo, F.v_lo,
                             nullptr, nullptr, nullptr, D.bf, 0, 1, st), "rope ft");
   // 4. attention: prefill (causal), decode (paged), fine-tune (causal, split operands, LSE kept)
-  prof_mark(h, st, T_ATTN_PREFILL);
+  prof_mark(h, st, T_ATTN_PREFILL, 4.0 * D.hd * D.Hq * I.pairs_prefill);
   HIP_TRY(launch_attn_fwd(F.q_i, F.k_i, F.v_i, nullptr, nullptr, nullptr, batch->seg_offsets, 0, batch->n_prefill, I.max_prefill, D.Hq, D.Hkv, D.hd, F.o_i, nullptr, nullptr, st), "prefill attention");
   if (I.Td > 0) {
-    prof_mark(h, st, T_ATTN_DECODE);
+    double kv_tokens = 0.0;
+    for (int i = 0; i < I.Td; ++i) kv_tokens += (double)batch->context_lens_host[i] + 1.0;
+    prof_mark(h, st, T_ATTN_DECODE, 4.0 * kv_tokens * D.Hq * D.hd, kv_tokens * 2.0 * D.Hkv * D.hd * (D.bf ? 2.0 : 4.0));
     HIP_TRY(launch_attn_decode(F.q_i + (size_t)I.Tp * D.qd, cache->k, cache->v, D.bf, cache->num_blocks, cache->block_size, batch->block_tables, batch->max_blocks_per_req,
                                batch->context_lens, I.Td, I.max_ctx, D.Hq, D.Hkv, D.hd, F.dec_partial, F.o_i + (size_t)I.Tp * D.qd, st), "decode attention");
   }
-  prof_mark(h, st, T_ATTN_FT);
+  prof_mark(h, st, T_ATTN_FT, 4.0 * D.hd * D.Hq * I.pairs_ft);
   HIP_TRY(launch_attn_fwd(S.q, S.k, S.v, F.q_lo, F.k_lo, F.v_lo, batch->seg_offsets + batch->n_prefill + batch->n_decode, I.Ti, batch->n_ft_seq, I.max_ft, D.Hq, D.Hkv, D.hd, S.o, F.o_lo, S.lse, st), "ft attention");
   // 5. output projection + residual
   {
@@ -644,7 +648,7 @@ int mace_hybrid_layer_bwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
     TRY(run_gemm(h, 1, 1, p, st, "dWo gemm"));
   }
   // attention backward, RoPE backward
-  prof_mark(h, st, T_ATTN_BWD);
+  prof_mark(h, st, T_ATTN_BWD, 10.0 * D.hd * D.Hq * I.pairs_ft);
   HIP_TRY(launch_attn_bwd(S.q, S.k, S.v, S.o, B.dattn, S.lse, batch->seg_offsets + batch->n_prefill + batch->n_decode, I.Ti, batch->n_ft_seq, I.max_ft, Tf,
                           D.Hq, D.Hkv, D.hd, B.dvec, B.dq, B.dk, B.dv, st), "attention bwd");
   prof_mark(h, st, T_ROPE);
@@ -728,7 +732,7 @@ int mace_dpo_logprob_loss(mace_handle_t h, const float *h_ft, const void *g_fina
     gp_group(p, P.n_hi, P.n_lo, P.logits, nullptr, Ri, D.bf ? 2 : 3);
     gp_seg(p, e_hi, e_lo, D.V, 0);
     TRY(run_gemm(h, 0, 0, p, st, "lm head gemm"));
-    prof_mark(h, st, T_LOGSOFTMAX);
+    prof_mark(h, st, T_LOGSOFTMAX, 0.0, (double)Ri * D.V * 4.0);
     HIP_TRY(launch_logsoftmax_gather(P.logits, Ri, D.V, P.label, P.logp_t, P.lse, st), "log-softmax");
   }
   prof_mark(h, st, T_MISC);
@@ -747,7 +751,7 @@ int mace_dpo_logprob_loss(mace_handle_t h, const float *h_ft, const void *g_fina
     prof_mark(h, st, -1);
     return MACE_OK;
   }
-  prof_mark(h, st, T_DLOGITS);
+  prof_mark(h, st, T_DLOGITS, 0.0, (double)Ri * D.V * 6.0);
   HIP_TRY(launch_dlogits(P.logits, Ri, D.V, P.label, P.seq_id, P.lse, P.dlogp, P.dl, st), "dlogits");
   if (dw_lm) {
     GemmParams p = gp_init(Ri, D.V, D.d, D.d);

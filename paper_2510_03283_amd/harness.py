@@ -15,7 +15,10 @@ _WNAMES = ("g1", "wq", "wk", "wv", "wo", "g2", "wg", "wu", "wd")
 
 
 class DeviceIteration:
-    def __init__(self, wl: Workload, device: str = "cuda:0", load_cache: bool = True):
+    def __init__(self, wl: Workload, device: str = "cuda:0", load_cache: bool = True, device_cache_seed=None):
+        """device_cache_seed: fill the cached contexts with N(0,1) values drawn on the GPU (torch
+        generator) instead of uploading wl.ctx_k / ctx_v - for benchmark workloads whose cache
+        (tens of GB) is too large to generate on the host.  Not used by parity tests."""
         self.wl = wl
         self.dev = torch.device(device)
         m, b = wl.dims, wl.batch
@@ -64,7 +67,14 @@ class DeviceIteration:
         self.cache_k = torch.zeros(cshape, dtype=self.io_dtype, device=self.dev)
         self.cache_v = torch.zeros(cshape, dtype=self.io_dtype, device=self.dev)
         self.cache = B.kv_cache_struct(self.cache_k, self.cache_v, b.num_blocks, b.block_size)
-        if load_cache and self.Td and wl.ctx_k is not None:
+        if device_cache_seed is not None and self.Td:
+            gen = torch.Generator(device=self.dev)
+            gen.manual_seed(int(device_cache_seed))
+            for c in (self.cache_k, self.cache_v):       # block by block to bound temporary memory
+                step = max(1, (1 << 28) // (c[0].numel()))
+                for b0 in range(0, c.shape[0], step):
+                    c[b0:b0 + step] = torch.randn(c[b0:b0 + step].shape, generator=gen, device=self.dev, dtype=torch.float32).to(self.io_dtype)
+        elif load_cache and self.Td and wl.ctx_k is not None:
             self.load_context(wl.ctx_k, wl.ctx_v)
 
         # buffers
