@@ -4,7 +4,9 @@
 // once, for all query heads of the GQA group, with 16-byte loads per lane (a token row of hd
 // elements is covered by hd/8 consecutive lanes, so a wave load touches whole token rows that
 // are contiguous inside a cache block).  Every lane keeps its own online soft-max state over the
-// tokens it sees; states are merged across lanes, waves and finally splits.
+// tokens it sees; states are merged across lanes, waves and finally splits.  bf16 caches use packed
+// dot products (v_dot2_f32_bf16) for q.k, DPP row operations for the per-token reduction and
+// nontemporal loads (the cache is read once per iteration and should not displace the weights).
 #include "kernels.h"
 
 namespace {
@@ -12,27 +14,34 @@ namespace {
 constexpr int CHUNK = 512;   // tokens per block
 constexpr int UNR = 4;       // token loads in flight per lane for K and for V
 
-struct Sm { float m, l; };
-
 __device__ __forceinline__ float safe_scale(float m_old, float m_new) {
   return m_old == -INFINITY ? 0.f : exp2f(m_old - m_new);
 }
 
-template <bool CBF>
-__device__ __forceinline__ void ld8(const void *base, long long off, float v[8]) {
-  if constexpr (CBF) {
-    const uint4 u = *(const uint4 *)((const bf16_t *)base + off);
-    v[0] = __uint_as_float(u.x << 16); v[1] = __uint_as_float(u.x & 0xffff0000u);
-    v[2] = __uint_as_float(u.y << 16); v[3] = __uint_as_float(u.y & 0xffff0000u);
-    v[4] = __uint_as_float(u.z << 16); v[5] = __uint_as_float(u.z & 0xffff0000u);
-    v[6] = __uint_as_float(u.w << 16); v[7] = __uint_as_float(u.w & 0xffff0000u);
-  } else {
-    const float4 a = *(const float4 *)((const float *)base + off), b = *(const float4 *)((const float *)base + off + 4);
-    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-  }
+// Sum over the LPT (8 or 16) consecutive lanes that share a token row, result in every lane, with
+// DPP row operations (quad swaps, then mirrors inside 8 and 16 lanes) - no LDS traffic.
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true));
+}
+template <int LPT>
+__device__ __forceinline__ float group_sum(float d) {
+  d += dpp_mov<0xB1>(d);                         // quad_perm [1,0,3,2]
+  d += dpp_mov<0x4E>(d);                         // quad_perm [2,3,0,1]
+  d += dpp_mov<0x141>(d);                        // row_half_mirror: the other quad of the 8 lanes
+  if constexpr (LPT == 16) d += dpp_mov<0x140>(d);   // row_mirror: the other half of the 16 lanes
+  return d;
 }
 
-template <int HD, int GRP, bool CBF>
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
+}
+
+// FAST: block_size >= tokens per wave-wide load, so the tokens of one load share a cache block
+// and the block-table entry is read once per load (wave-uniform) instead of once per lane.
+template <int HD, int GRP, bool CBF, bool FAST>
 __global__ __launch_bounds__(256) void attn_decode_kernel(const bf16_t *__restrict__ q, const void *__restrict__ ck,
                                                           const void *__restrict__ cv, long long num_blocks, int B,
                                                           int bshift, const int32_t *__restrict__ block_tables,
@@ -40,6 +49,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const bf16_t *__restri
                                                           int Hkv, int nsplit, float *__restrict__ partial) {
   constexpr int LPT = HD / 8;          // lanes per token row
   constexpr int TPL = 64 / LPT;        // tokens per wave-wide load
+  constexpr int NW = CBF ? 4 : 8;      // 32-bit words of the 8 elements a lane holds
   __shared__ float sm[4][GRP][HD + 2];
   const int split = blockIdx.x, req = blockIdx.y, kvh = blockIdx.z;
   const int n_tot = ctx_lens[req] + 1;                    // cached context plus the new token
@@ -50,15 +60,17 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const bf16_t *__restri
   const int e0 = (lane % LPT) * 8, tl = lane / LPT;
   const float sc = 1.4426950408889634f / sqrtf((float)HD);
 
+  // q: packed bf16 pairs for the bf16 cache (dot2), scaled floats for the fp32 cache
+  uint32_t qp[GRP][4];
   float qv[GRP][8];
 #pragma unroll
   for (int gi = 0; gi < GRP; ++gi) {
     const uint4 u = *(const uint4 *)(q + (size_t)req * Hq * HD + (size_t)(kvh * GRP + gi) * HD + e0);
-    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+    qp[gi][0] = u.x; qp[gi][1] = u.y; qp[gi][2] = u.z; qp[gi][3] = u.w;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      qv[gi][2 * e] = __uint_as_float(w[e] << 16) * sc;
-      qv[gi][2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u) * sc;
+      qv[gi][2 * e] = __uint_as_float(qp[gi][e] << 16);
+      qv[gi][2 * e + 1] = __uint_as_float(qp[gi][e] & 0xffff0000u);
     }
   }
   float m[GRP], l[GRP], acc[GRP][8];
@@ -76,20 +88,47 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const bf16_t *__restri
     bool ok[UNR];
 #pragma unroll
     for (int u = 0; u < UNR; ++u) {
-      const int t = tb + u * TPL + tl;
+      const int t0 = tb + u * TPL, t = t0 + tl;
       ok[u] = t < wend;
       long long blk = 0;
-      if (ok[u]) {
+      if constexpr (FAST) {
+        // t0 is a multiple of TPL <= B: the TPL tokens sit in one block, t0 < wend holds for the first lanes
+        blk = t0 < wend ? __builtin_amdgcn_readfirstlane(bt[t0 >> bshift]) : -1;
+      } else if (ok[u]) {
         blk = bt[t >> bshift];
-        ok[u] = blk >= 0 && blk < num_blocks;      // a bad table entry is ignored, never dereferenced
       }
+      ok[u] = ok[u] && blk >= 0 && blk < num_blocks;      // a bad table entry is ignored, never dereferenced
       off[u] = ok[u] ? ((blk * Hkv + kvh) * B + (t & (B - 1))) * (long long)HD + e0 : 0;
     }
-    float kf[UNR][8], vf[UNR][8];
+    uint32_t kr[UNR][NW], vr[UNR][NW];
 #pragma unroll
-    for (int u = 0; u < UNR; ++u) ld8<CBF>(ck, off[u], kf[u]);
+    for (int u = 0; u < UNR; ++u) {
+      if constexpr (CBF) {
+        const u32x4_t a = __builtin_nontemporal_load((const u32x4_t *)((const bf16_t *)ck + off[u]));   // streamed once
+        kr[u][0] = a.x; kr[u][1] = a.y; kr[u][2] = a.z; kr[u][3] = a.w;
+      } else {
+        const uint4 a = *(const uint4 *)((const float *)ck + off[u]), b2 = *(const uint4 *)((const float *)ck + off[u] + 4);
+        kr[u][0] = a.x; kr[u][1] = a.y; kr[u][2] = a.z; kr[u][3] = a.w; kr[u][4] = b2.x; kr[u][5] = b2.y; kr[u][6] = b2.z; kr[u][7] = b2.w;
+      }
+    }
 #pragma unroll
-    for (int u = 0; u < UNR; ++u) ld8<CBF>(cv, off[u], vf[u]);
+    for (int u = 0; u < UNR; ++u) {
+      if constexpr (CBF) {
+        const u32x4_t a = __builtin_nontemporal_load((const u32x4_t *)((const bf16_t *)cv + off[u]));
+        vr[u][0] = a.x; vr[u][1] = a.y; vr[u][2] = a.z; vr[u][3] = a.w;
+      } else {
+        const uint4 a = *(const uint4 *)((const float *)cv + off[u]), b2 = *(const uint4 *)((const float *)cv + off[u] + 4);
+        vr[u][0] = a.x; vr[u][1] = a.y; vr[u][2] = a.z; vr[u][3] = a.w; vr[u][4] = b2.x; vr[u][5] = b2.y; vr[u][6] = b2.z; vr[u][7] = b2.w;
+      }
+    }
+    float vf[UNR][8];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        if constexpr (CBF) vf[u][e] = __uint_as_float((e & 1) ? (vr[u][e >> 1] & 0xffff0000u) : (vr[u][e >> 1] << 16));
+        else vf[u][e] = __uint_as_float(vr[u][e]);
+      }
 #pragma unroll
     for (int gi = 0; gi < GRP; ++gi) {
       float sv[UNR];
@@ -97,10 +136,14 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const bf16_t *__restri
 #pragma unroll
       for (int u = 0; u < UNR; ++u) {
         float d = 0.f;
+        if constexpr (CBF) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) d += kf[u][e] * qv[gi][e];
+          for (int e = 0; e < 4; ++e) d = dot2_bf16(kr[u][e], qp[gi][e], d);
+        } else {
 #pragma unroll
-        for (int o = 1; o < LPT; o <<= 1) d += __shfl_xor(d, o, 64);
+          for (int e = 0; e < 8; ++e) d += __uint_as_float(kr[u][e]) * qv[gi][e];
+        }
+        d = group_sum<LPT>(d) * sc;
         sv[u] = ok[u] ? d : -INFINITY;
         mx = fmaxf(mx, sv[u]);
       }
@@ -181,7 +224,10 @@ template <int HD, int GRP, bool CBF>
 void launch_main(const bf16_t *q, const void *ck, const void *cv, long long num_blocks, int B, int bshift,
                  const int32_t *bt, int max_blocks, const int32_t *ctx, int n_decode, int Hq, int Hkv, int nsplit,
                  float *partial, hipStream_t st) {
-  hipLaunchKernelGGL((attn_decode_kernel<HD, GRP, CBF>), dim3(nsplit, n_decode, Hkv), dim3(256), 0, st, q, ck, cv, num_blocks, B, bshift, bt, max_blocks, ctx, Hq, Hkv, nsplit, partial);
+  if (B >= 64 / (HD / 8))
+    hipLaunchKernelGGL((attn_decode_kernel<HD, GRP, CBF, true>), dim3(nsplit, n_decode, Hkv), dim3(256), 0, st, q, ck, cv, num_blocks, B, bshift, bt, max_blocks, ctx, Hq, Hkv, nsplit, partial);
+  else
+    hipLaunchKernelGGL((attn_decode_kernel<HD, GRP, CBF, false>), dim3(nsplit, n_decode, Hkv), dim3(256), 0, st, q, ck, cv, num_blocks, B, bshift, bt, max_blocks, ctx, Hq, Hkv, nsplit, partial);
 }
 
 template <int HD, bool CBF>
