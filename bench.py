@@ -19,8 +19,10 @@ METRIC = "mixed-batch tokens/s per layer (prefill+decode+DPO) & % of MFMA/HBM ro
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
 PEAK_HBM_GBS = 8000.0
 
-# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of the dominant kernel, bytes per launch (see profiles/); None = not measured
-TRAFFIC_BYTES_PER_LAUNCH = None
+# rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, scaled by a plain copy, bytes per launch averaged over one step's
+# launches of the class: (workload, kernel class) -> bytes.  Source: profiles/bench_edge_gemm_nt_hbm_traffic.md
+# and profiles/bench_7b_decode_attn_decode_hbm_traffic.md.  Not measured -> null.
+TRAFFIC_BYTES_PER_LAUNCH = {("edge", "gemm_nt"): 5.996e8, ("7b_decode", "attn_decode"): 2.2127e10}
 
 
 def cpu_baseline(wl):
@@ -47,6 +49,8 @@ def main():
     ap.add_argument("--workload", default="edge", help="synthetic configuration (default: the one the metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket launches with events")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run three plain 1 GiB device copies (reference dispatches for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -64,6 +68,13 @@ def main():
     big_cache = args.workload in ("7b", "7b_decode", "7b_ft")     # cached contexts drawn on the GPU
     wl = synth.make_workload(args.workload, with_cache=not big_cache)
     it = DeviceIteration(wl, device_cache_seed=wl.spec.seed if big_cache else None)
+    if args.calib_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB read + 1 GiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         it.step()
     torch.cuda.synchronize()
@@ -97,12 +108,12 @@ def main():
         if dom not in hbm_classes and e["flops"] > 0:
             ach = e["flops"] / e["launches"] / (avg_ms * 1e-3) / 1e12
             roof = {"bound": "mfma", "kernel": dom, "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": ach / PEAK_BF16_TFLOPS, "traffic": TRAFFIC_BYTES_PER_LAUNCH,
+                    "frac": ach / PEAK_BF16_TFLOPS, "traffic": TRAFFIC_BYTES_PER_LAUNCH.get((args.workload, dom)),
                     "avg_launch_ms": avg_ms, "launches_per_step": e["launches"] / args.steps}
         else:
             ach = e["bytes"] / e["launches"] / (avg_ms * 1e-3) / 1e9
             roof = {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": ach / PEAK_HBM_GBS, "traffic": TRAFFIC_BYTES_PER_LAUNCH,
+                    "frac": ach / PEAK_HBM_GBS, "traffic": TRAFFIC_BYTES_PER_LAUNCH.get((args.workload, dom)),
                     "avg_launch_ms": avg_ms, "launches_per_step": e["launches"] / args.steps}
         out["roofline"] = roof
         out["kernel_ms_per_step"] = {k: round(v["ms"] / args.steps, 4) for k, v in prof.items() if v["launches"]}
