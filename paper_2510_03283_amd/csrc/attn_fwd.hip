@@ -1,36 +1,39 @@
 // Varlen causal attention forward on bf16 MFMA (gfx950), for prefill rows (plain bf16 operands)
 // and fine-tune rows (two-term bf16 operands, three products per contraction, LSE saved).
 //
-// One block = 128 queries of one (sequence, query head): 4 waves x 32 queries.  Scores are formed
-// transposed, S^T = K Q^T, so that a lane owns ONE query column: its soft-max state (running
-// max, running sum) is a per-lane scalar and P^T is already laid out as the B operand of
-// O^T = V^T P^T.  K tiles sit in LDS as [key][hd]; V tiles are transposed on the way in to
-// [hd][key'] with key' = key with bits 2 and 3 swapped, which makes the 8 keys a lane needs for
-// one MFMA contiguous (one 16-byte LDS read).
+// One block = 32*NW queries of one (sequence, query head): NW waves x 32 queries.  Scores are
+// formed transposed, S^T = K Q^T, so that a lane owns ONE query column: its soft-max state
+// (running max, running sum) is a per-lane scalar and P^T is already laid out as the B operand
+// of O^T = V^T P^T.  K and V tiles of 64 keys go global -> LDS directly in their memory layout,
+// two stages deep (the loads of tile i+1 fly while tile i is multiplied; one barrier per tile);
+// K fragments are plain 16-byte LDS reads, V^T fragments come from transposing LDS reads of the
+// untransposed V tile (see attn_tile.h).
+#include "attn_tile.h"
 #include "kernels.h"
 
 namespace {
 
-constexpr int QB = 128;   // queries per block
+using namespace attn;
+
 constexpr int KB = 64;    // keys per LDS tile
 
 __device__ __forceinline__ bf16x8_t as_bf8(uint4 u) { return __builtin_bit_cast(bf16x8_t, u); }
 
-template <int HD, bool SPLIT>
-__global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t *__restrict__ q_hi, const bf16_t *__restrict__ k_hi,
-                                                       const bf16_t *__restrict__ v_hi, const bf16_t *__restrict__ q_lo,
-                                                       const bf16_t *__restrict__ k_lo, const bf16_t *__restrict__ v_lo,
-                                                       const int32_t *__restrict__ seg, int row_base, int Hq, int Hkv,
-                                                       bf16_t *__restrict__ o_hi, bf16_t *__restrict__ o_lo,
-                                                       float *__restrict__ lse) {
+template <int HD, bool SPLIT, int NW>
+__global__ __launch_bounds__(64 * NW) void attn_fwd_kernel(const bf16_t *__restrict__ q_hi, const bf16_t *__restrict__ k_hi,
+                                                           const bf16_t *__restrict__ v_hi, const bf16_t *__restrict__ q_lo,
+                                                           const bf16_t *__restrict__ k_lo, const bf16_t *__restrict__ v_lo,
+                                                           const int32_t *__restrict__ seg, int row_base, int Hq, int Hkv,
+                                                           bf16_t *__restrict__ o_hi, bf16_t *__restrict__ o_lo,
+                                                           float *__restrict__ lse) {
   constexpr int NT = SPLIT ? 2 : 1;
-  constexpr int KP = HD + 8;       // pitch of a K row in LDS
-  constexpr int VP = KB + 8;       // pitch of a V^T row in LDS
+  constexpr int QB = 32 * NW;
   constexpr int NKK = HD / 16;     // MFMA k-steps over the head dimension
   constexpr int NOT = HD / 32;     // 32-row tiles of O^T
+  using T = Tile<KB, HD, 64 * NW>;
+  constexpr int STAGE = 2 * NT * T::ELEMS;         // K (hi, lo), V (hi, lo)
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  bf16_t *Ks = (bf16_t *)smem_raw;                 // [NT][KB][KP]
-  bf16_t *Vt = Ks + NT * KB * KP;                  // [NT][HD][VP]
+  bf16_t *lds = (bf16_t *)smem_raw;                // [2][STAGE]
 
   const int s = blockIdx.y, h = blockIdx.z, kvh = h / (Hq / Hkv);
   const int r0 = seg[s] - row_base, L = seg[s + 1] - seg[s];
@@ -40,6 +43,20 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t *__restrict_
   const int qw0 = q0 + wave * 32;                        // first query of this wave
   const int qi = qw0 + j;                                // this lane's query (may be >= L: computed, not stored)
   const size_t qld = (size_t)Hq * HD, kld = (size_t)Hkv * HD;
+  const bf16_t *kbase[2] = {k_hi + (size_t)r0 * kld + (size_t)kvh * HD, SPLIT ? k_lo + (size_t)r0 * kld + (size_t)kvh * HD : nullptr};
+  const bf16_t *vbase[2] = {v_hi + (size_t)r0 * kld + (size_t)kvh * HD, SPLIT ? v_lo + (size_t)r0 * kld + (size_t)kvh * HD : nullptr};
+
+  const int kend = min(L, q0 + QB);
+  const int ntiles = (kend + KB - 1) / KB;
+  auto issue_tile = [&](int it) {
+    bf16_t *S = lds + (it & 1) * STAGE;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      T::issue(kbase[t], kld, it * KB, L, S + t * T::ELEMS);
+      T::issue(vbase[t], kld, it * KB, L, S + (NT + t) * T::ELEMS);
+    }
+  };
+  issue_tile(0);
 
   // Q fragments (B operand of S^T): 8 consecutive head-dim elements per k-step, kept in registers
   bf16x8_t qf[NT][NKK];
@@ -55,57 +72,30 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t *__restrict_
     if constexpr (SPLIT) qf[1][kk] = as_bf8(vl);
   }
 
+  // lane's K row inside a 32-key sub-tile: MFMA row j reads tile row swap23(j), so that register
+  // r = 8*mm + e of S^T holds key 16*mm + 8*g + e
+  const typename T::FragK fk = T::frag_k_init(swap23(j));
+  typename T::FragT fv[NOT];
+#pragma unroll
+  for (int t = 0; t < NOT; ++t) fv[t] = T::frag_t_init(32 * t, lane);
+
   f32x16_t oacc[NOT];
 #pragma unroll
   for (int t = 0; t < NOT; ++t)
 #pragma unroll
     for (int r = 0; r < 16; ++r) oacc[t][r] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;                  // log2-domain running max; partial running sum
+  float m_run = -INFINITY, l_run = 0.f;                  // running max of the raw scores; partial running sum
   const float sc = 1.4426950408889634f / sqrtf((float)HD);
 
-  const int kend = min(L, q0 + QB);
-  for (int kb = 0; kb < kend; kb += KB) {
-    __syncthreads();
-    // ---- stage K tile [key][hd] and V tile transposed [hd][key']
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      const bf16_t *kp = t ? k_lo : k_hi;
-      const bf16_t *vp = t ? v_lo : v_hi;
-      for (int c = tid; c < KB * HD / 8; c += 256) {
-        const int key = c / (HD / 8), ch = c % (HD / 8);
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (kb + key < L) v = *(const uint4 *)(kp + (size_t)(r0 + kb + key) * kld + (size_t)kvh * HD + ch * 8);
-        *(uint4 *)(Ks + (t * KB + key) * KP + ch * 8) = v;
-      }
-      for (int c = tid; c < (KB / 4) * (HD / 8); c += 256) {
-        const int hb = c % (HD / 8), kq = c / (HD / 8);           // 8 head-dim elements x 4 keys
-        uint32_t d[4][4];
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-          uint4 v = make_uint4(0, 0, 0, 0);
-          const int key = kb + 4 * kq + jj;
-          if (key < L) v = *(const uint4 *)(vp + (size_t)(r0 + key) * kld + (size_t)kvh * HD + hb * 8);
-          d[jj][0] = v.x; d[jj][1] = v.y; d[jj][2] = v.z; d[jj][3] = v.w;
-        }
-        const int kq2 = (kq & ~3) | ((kq & 1) << 1) | ((kq >> 1) & 1);   // swap key bits 2 and 3
-#pragma unroll
-        for (int m = 0; m < 8; ++m) {
-          uint32_t w0, w1;
-          if (m & 1) {
-            w0 = (d[0][m >> 1] >> 16) | (d[1][m >> 1] & 0xffff0000u);
-            w1 = (d[2][m >> 1] >> 16) | (d[3][m >> 1] & 0xffff0000u);
-          } else {
-            w0 = (d[0][m >> 1] & 0xffffu) | (d[1][m >> 1] << 16);
-            w1 = (d[2][m >> 1] & 0xffffu) | (d[3][m >> 1] << 16);
-          }
-          *(uint2 *)(Vt + (t * HD + hb * 8 + m) * VP + 4 * kq2) = make_uint2(w0, w1);
-        }
-      }
-    }
-    __syncthreads();
+  for (int it = 0; it < ntiles; ++it) {
+    wait_vmcnt<0>();
+    __syncthreads();                                     // tile it has landed; stage (it+1)&1 is free
+    if (it + 1 < ntiles) issue_tile(it + 1);
+    const int kb = it * KB;
     if (kb > qw0 + 31) continue;                         // every key of the tile is in this wave's future
+    const bf16_t *Kh = lds + (it & 1) * STAGE, *Kl = Kh + T::ELEMS, *Vh = Kh + NT * T::ELEMS, *Vl = Vh + T::ELEMS;
 
-    // ---- S^T = K Q^T for the two 32-key sub-tiles; lane owns query j, register r owns key
+    // ---- S^T = K Q^T for the two 32-key sub-tiles; lane owns query j, register r owns a key
     f32x16_t sacc[2];
 #pragma unroll
     for (int st = 0; st < 2; ++st) {
@@ -113,30 +103,35 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t *__restrict_
       for (int r = 0; r < 16; ++r) sacc[st][r] = 0.f;
 #pragma unroll
       for (int kk = 0; kk < NKK; ++kk) {
-        const bf16x8_t a = *(const bf16x8_t *)(Ks + (st * 32 + j) * KP + kk * 16 + g * 8);
+        const bf16x8_t a = T::frag_k(Kh + st * 32 * HD, fk, kk, g);
         sacc[st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0][kk], sacc[st], 0, 0, 0);
         if constexpr (SPLIT) {
           sacc[st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[1][kk], sacc[st], 0, 0, 0);
-          const bf16x8_t al = *(const bf16x8_t *)(Ks + (KB + st * 32 + j) * KP + kk * 16 + g * 8);
+          const bf16x8_t al = T::frag_k(Kl + st * 32 * HD, fk, kk, g);
           sacc[st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, qf[0][kk], sacc[st], 0, 0, 0);
         }
       }
     }
-    // ---- mask, online soft-max (log2 domain)
-    float mx = -INFINITY;
+    // ---- mask (only tiles that touch the diagonal or the end of the sequence), online soft-max
+    if (kb + KB - 1 > qw0 || kb + KB > L) {
+#pragma unroll
+      for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = kb + st * 32 + 16 * (r >> 3) + 8 * g + (r & 7);
+          if (!(key <= qi && key < L)) sacc[st][r] = -INFINITY;
+        }
+    }
+    float mx = sacc[0][0];
 #pragma unroll
     for (int st = 0; st < 2; ++st)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = kb + st * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-        const float t = (key <= qi && key < L) ? sacc[st][r] * sc : -INFINITY;
-        sacc[st][r] = t;
-        mx = fmaxf(mx, t);
-      }
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[st][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m_run, mx);                // finite from the first tile on (key 0 <= every query)
-    const float alpha = exp2f(m_run - m_new);
+    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * sc);
     m_run = m_new;
+    const float mb = m_new * sc;
     float ps = 0.f;
     bf16x8_t pf[NT][2][2];
 #pragma unroll
@@ -146,13 +141,11 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t *__restrict_
         uint32_t wh[4], wl[4];
 #pragma unroll
         for (int e = 0; e < 8; e += 2) {
-          const float p0 = exp2f(sacc[st][8 * mm + e] - m_new), p1 = exp2f(sacc[st][8 * mm + e + 1] - m_new);
+          const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[st][8 * mm + e], sc, -mb));
+          const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[st][8 * mm + e + 1], sc, -mb));
           ps += p0 + p1;
-          bf16_t h0, l0, h1, l1;
-          split_bf(p0, h0, l0);
-          split_bf(p1, h1, l1);
-          wh[e >> 1] = pack2(h0, h1);
-          wl[e >> 1] = pack2(l0, l1);
+          if constexpr (SPLIT) split_pk_bf16(p0, p1, wh[e >> 1], wl[e >> 1]);
+          else wh[e >> 1] = cvt_pk_bf16(p0, p1);
         }
         pf[0][st][mm] = as_bf8(make_uint4(wh[0], wh[1], wh[2], wh[3]));
         if constexpr (SPLIT) pf[1][st][mm] = as_bf8(make_uint4(wl[0], wl[1], wl[2], wl[3]));
@@ -167,11 +160,11 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t *__restrict_
       for (int st = 0; st < 2; ++st)
 #pragma unroll
         for (int mm = 0; mm < 2; ++mm) {
-          const bf16x8_t a = *(const bf16x8_t *)(Vt + (t * 32 + j) * VP + st * 32 + mm * 16 + g * 8);
+          const bf16x8_t a = T::frag_t(Vh, fv[t], 2 * st + mm);
           oacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[0][st][mm], oacc[t], 0, 0, 0);
           if constexpr (SPLIT) {
             oacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[1][st][mm], oacc[t], 0, 0, 0);
-            const bf16x8_t al = *(const bf16x8_t *)(Vt + (HD + t * 32 + j) * VP + st * 32 + mm * 16 + g * 8);
+            const bf16x8_t al = T::frag_t(Vl, fv[t], 2 * st + mm);
             oacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, pf[0][st][mm], oacc[t], 0, 0, 0);
           }
         }
@@ -187,31 +180,31 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16_t *__restrict_
     for (int t = 0; t < NOT; ++t)
 #pragma unroll
       for (int rq = 0; rq < 4; ++rq) {
-        bf16_t hh[4], ll[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) split_bf(oacc[t][4 * rq + e] * inv, hh[e], ll[e]);
+        uint32_t h0, l0, h1, l1;
+        split_pk_bf16(oacc[t][4 * rq] * inv, oacc[t][4 * rq + 1] * inv, h0, l0);
+        split_pk_bf16(oacc[t][4 * rq + 2] * inv, oacc[t][4 * rq + 3] * inv, h1, l1);
         const size_t o = ob + t * 32 + 8 * rq + 4 * g;
-        *(uint2 *)(o_hi + o) = make_uint2(pack2(hh[0], hh[1]), pack2(hh[2], hh[3]));
-        if (o_lo) *(uint2 *)(o_lo + o) = make_uint2(pack2(ll[0], ll[1]), pack2(ll[2], ll[3]));
+        *(uint2 *)(o_hi + o) = make_uint2(h0, h1);
+        if (o_lo) *(uint2 *)(o_lo + o) = make_uint2(l0, l1);
       }
-    if (lse && g == 0) lse[(size_t)(r0 + qi) * Hq + h] = (m_run + log2f(l_tot)) * 0.6931471805599453f;
+    if (lse && g == 0) lse[(size_t)(r0 + qi) * Hq + h] = (m_run * sc + log2f(l_tot)) * 0.6931471805599453f;
   }
 }
 
-template <int HD, bool SPLIT>
+template <int HD, bool SPLIT, int NW>
 hipError_t launch_t(const bf16_t *q_hi, const bf16_t *k_hi, const bf16_t *v_hi, const bf16_t *q_lo, const bf16_t *k_lo,
                     const bf16_t *v_lo, const int32_t *seg, int row_base, int n_seq, int max_len, int Hq, int Hkv,
                     bf16_t *o_hi, bf16_t *o_lo, float *lse, hipStream_t st) {
   constexpr int NT = SPLIT ? 2 : 1;
-  constexpr size_t lds = (size_t)NT * (KB * (HD + 8) + HD * (KB + 8)) * sizeof(bf16_t);
+  constexpr size_t lds = (size_t)2 * 2 * NT * KB * HD * sizeof(bf16_t);
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void *)attn_fwd_kernel<HD, SPLIT>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = hipFuncSetAttribute((const void *)attn_fwd_kernel<HD, SPLIT, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  dim3 grid(cdiv(max_len, QB), n_seq, Hq);
-  hipLaunchKernelGGL((attn_fwd_kernel<HD, SPLIT>), grid, dim3(256), lds, st, q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, Hq, Hkv, o_hi, o_lo, lse);
+  dim3 grid(cdiv(max_len, 32 * NW), n_seq, Hq);
+  hipLaunchKernelGGL((attn_fwd_kernel<HD, SPLIT, NW>), grid, dim3(64 * NW), lds, st, q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, Hq, Hkv, o_hi, o_lo, lse);
   return hipGetLastError();
 }
 
@@ -225,9 +218,10 @@ hipError_t launch_attn_fwd(const bf16_t *q_hi, const bf16_t *k_hi, const bf16_t 
   if (n_seq > 65535 || Hq > 65535) return hipErrorInvalidValue;
   const bool split = q_lo != nullptr;
   if (split && (!k_lo || !v_lo)) return hipErrorInvalidValue;
-  if (hd == 64) return split ? launch_t<64, true>(q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, n_seq, max_len, Hq, Hkv, o_hi, o_lo, lse, st)
-                             : launch_t<64, false>(q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, n_seq, max_len, Hq, Hkv, o_hi, o_lo, lse, st);
-  if (hd == 128) return split ? launch_t<128, true>(q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, n_seq, max_len, Hq, Hkv, o_hi, o_lo, lse, st)
-                              : launch_t<128, false>(q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, n_seq, max_len, Hq, Hkv, o_hi, o_lo, lse, st);
+  // two-term operands at head dim 128 need 128 KB of LDS per block: 8 waves share it
+  if (hd == 64) return split ? launch_t<64, true, 4>(q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, n_seq, max_len, Hq, Hkv, o_hi, o_lo, lse, st)
+                             : launch_t<64, false, 4>(q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, n_seq, max_len, Hq, Hkv, o_hi, o_lo, lse, st);
+  if (hd == 128) return split ? launch_t<128, true, 8>(q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, n_seq, max_len, Hq, Hkv, o_hi, o_lo, lse, st)
+                              : launch_t<128, false, 4>(q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, n_seq, max_len, Hq, Hkv, o_hi, o_lo, lse, st);
   return hipErrorInvalidValue;
 }

@@ -30,6 +30,19 @@ __device__ __forceinline__ void split_bf(float f, bf16_t &hi, bf16_t &lo) {
 
 __device__ __forceinline__ uint32_t pack2(bf16_t a, bf16_t b) { return (uint32_t)a | ((uint32_t)b << 16); }
 
+// Two fp32 -> one packed bf16 pair (a in the low half) with the hardware conversion
+// (v_cvt_pk_bf16_f32, round to nearest even), and the two-term form of a pair.
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float a, float b) {
+  const f32x2_t v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+__device__ __forceinline__ void split_pk_bf16(float a, float b, uint32_t &hi, uint32_t &lo) {
+  hi = cvt_pk_bf16(a, b);
+  lo = cvt_pk_bf16(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xffff0000u));
+}
+
 // Element load of an io tensor (fp32 or bf16) as fp32.
 template <bool BF16>
 __device__ __forceinline__ float ld_io(const void *p, size_t i) {
