@@ -7,59 +7,22 @@
 //    walks the queries of every query head of its GQA group, and accumulates
 //    dV^T = dO^T P and dK^T = Q^T dS.
 // P is recomputed from the saved log-sum-exp; D = rowsum(dO * O) comes from a small pre-kernel.
-// Tiles that feed the "transposed" products are transposed while they are staged into LDS, with
-// bits 2 and 3 of the row index swapped so that a lane's 8 reduction indices are contiguous.
+// Tiles of 64 rows go global -> LDS directly in their memory layout, two stages deep; the same
+// tile feeds the products that reduce over the head dimension (16-byte reads) and those that
+// reduce over the tile rows (transposing reads), see attn_tile.h.
+#include "attn_tile.h"
 #include "kernels.h"
 
 namespace {
+
+using namespace attn;
 
 constexpr int TB = 64;    // rows per staged LDS tile
 
 __device__ __forceinline__ bf16x8_t as_bf8(uint4 u) { return __builtin_bit_cast(bf16x8_t, u); }
 
-// dst[TB][HD+8] <- rows row0 .. row0+TB-1 of src (pitch ld), zero beyond row_end.
-template <int HD>
-__device__ __forceinline__ void stage_rows(bf16_t *dst, const bf16_t *src, size_t ld, int row0, int row_end) {
-  for (int c = threadIdx.x; c < TB * HD / 8; c += 256) {
-    const int row = c / (HD / 8), ch = c % (HD / 8);
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (row0 + row < row_end) v = *(const uint4 *)(src + (size_t)(row0 + row) * ld + ch * 8);
-    *(uint4 *)(dst + row * (HD + 8) + ch * 8) = v;
-  }
-}
-
-// dst[HD][TB+8] <- transpose of the same rows; source row i lands in column swap23(i).
-template <int HD>
-__device__ __forceinline__ void stage_rows_t(bf16_t *dst, const bf16_t *src, size_t ld, int row0, int row_end) {
-  for (int c = threadIdx.x; c < (TB / 4) * (HD / 8); c += 256) {
-    const int hb = c % (HD / 8), rq = c / (HD / 8);
-    uint32_t d[4][4];
-#pragma unroll
-    for (int jj = 0; jj < 4; ++jj) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      const int row = row0 + 4 * rq + jj;
-      if (row < row_end) v = *(const uint4 *)(src + (size_t)row * ld + hb * 8);
-      d[jj][0] = v.x; d[jj][1] = v.y; d[jj][2] = v.z; d[jj][3] = v.w;
-    }
-    const int rq2 = (rq & ~3) | ((rq & 1) << 1) | ((rq >> 1) & 1);
-#pragma unroll
-    for (int m = 0; m < 8; ++m) {
-      uint32_t w0, w1;
-      if (m & 1) {
-        w0 = (d[0][m >> 1] >> 16) | (d[1][m >> 1] & 0xffff0000u);
-        w1 = (d[2][m >> 1] >> 16) | (d[3][m >> 1] & 0xffff0000u);
-      } else {
-        w0 = (d[0][m >> 1] & 0xffffu) | (d[1][m >> 1] << 16);
-        w1 = (d[2][m >> 1] & 0xffffu) | (d[3][m >> 1] << 16);
-      }
-      *(uint2 *)(dst + (hb * 8 + m) * (TB + 8) + 4 * rq2) = make_uint2(w0, w1);
-    }
-  }
-}
-
 __device__ __forceinline__ bf16x8_t pack8(const float *v) {
-  return as_bf8(make_uint4(pack2(f2bf(v[0]), f2bf(v[1])), pack2(f2bf(v[2]), f2bf(v[3])),
-                           pack2(f2bf(v[4]), f2bf(v[5])), pack2(f2bf(v[6]), f2bf(v[7]))));
+  return as_bf8(make_uint4(cvt_pk_bf16(v[0], v[1]), cvt_pk_bf16(v[2], v[3]), cvt_pk_bf16(v[4], v[5]), cvt_pk_bf16(v[6], v[7])));
 }
 
 // ------------------------------------------------------------------ D = rowsum(dO * O)
@@ -82,11 +45,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t *__restri
                                                           const float *__restrict__ lse, const float *__restrict__ dvec,
                                                           const int32_t *__restrict__ seg, int row_base, int Hq, int Hkv,
                                                           float *__restrict__ dq) {
-  constexpr int KP = HD + 8, TP = TB + 8, NKK = HD / 16, NOT = HD / 32;
+  constexpr int NKK = HD / 16, NOT = HD / 32;
+  using T = Tile<TB, HD, 256>;
+  constexpr int STAGE = 2 * T::ELEMS;       // K tile, V tile
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  bf16_t *Ks = (bf16_t *)smem_raw;          // [TB][KP]
-  bf16_t *Vs = Ks + TB * KP;                // [TB][KP]
-  bf16_t *Kt = Vs + TB * KP;                // [HD][TP]
+  bf16_t *lds = (bf16_t *)smem_raw;         // [2][STAGE]
   const int s = blockIdx.y, h = blockIdx.z, kvh = h / (Hq / Hkv);
   const int r0 = seg[s] - row_base, L = seg[s + 1] - seg[s];
   const int q0 = (gridDim.x - 1 - blockIdx.x) * 128;
@@ -94,6 +57,15 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t *__restri
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, j = lane & 31;
   const int qw0 = q0 + wave * 32, qi = qw0 + j;
   const size_t qld = (size_t)Hq * HD, kld = (size_t)Hkv * HD;
+  const bf16_t *kbase = k + (size_t)r0 * kld + (size_t)kvh * HD, *vbase = v + (size_t)r0 * kld + (size_t)kvh * HD;
+  const int kend = min(L, q0 + 128);
+  const int ntiles = (kend + TB - 1) / TB;
+  auto issue_tile = [&](int it) {
+    bf16_t *S = lds + (it & 1) * STAGE;
+    T::issue(kbase, kld, it * TB, L, S);
+    T::issue(vbase, kld, it * TB, L, S + T::ELEMS);
+  };
+  issue_tile(0);
 
   bf16x8_t qf[NKK], dof[NKK];
 #pragma unroll
@@ -113,21 +85,25 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t *__restri
     lse2 = lse[(size_t)(r0 + qi) * Hq + h] * 1.4426950408889634f;
     dv_ = dvec[(size_t)(r0 + qi) * Hq + h];
   }
+  // MFMA row j reads tile row swap23(j): register r = 8*mm + e then holds key 16*mm + 8*g + e
+  const typename T::FragK fk = T::frag_k_init(swap23(j));
+  typename T::FragT ft[NOT];
+#pragma unroll
+  for (int t = 0; t < NOT; ++t) ft[t] = T::frag_t_init(32 * t, lane);
   f32x16_t acc[NOT];
 #pragma unroll
   for (int t = 0; t < NOT; ++t)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
 
-  const int kend = min(L, q0 + 128);
-  const bf16_t *kbase = k + (size_t)r0 * kld + (size_t)kvh * HD, *vbase = v + (size_t)r0 * kld + (size_t)kvh * HD;
-  for (int kb = 0; kb < kend; kb += TB) {
-    __syncthreads();
-    stage_rows<HD>(Ks, kbase, kld, kb, L);
-    stage_rows<HD>(Vs, vbase, kld, kb, L);
-    stage_rows_t<HD>(Kt, kbase, kld, kb, L);
-    __syncthreads();
+  for (int it = 0; it < ntiles; ++it) {
+    wait_vmcnt<0>();
+    __syncthreads();                                     // tile it has landed; the other stage is free
+    if (it + 1 < ntiles) issue_tile(it + 1);
+    const int kb = it * TB;
     if (kb > qw0 + 31) continue;
+    const bf16_t *Ks = lds + (it & 1) * STAGE, *Vs = Ks + T::ELEMS;
+    const bool need_mask = kb + TB - 1 > qw0 || kb + TB > L;
 #pragma unroll
     for (int st = 0; st < 2; ++st) {
       f32x16_t sa, dp;
@@ -135,16 +111,19 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t *__restri
       for (int r = 0; r < 16; ++r) { sa[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
       for (int kk = 0; kk < NKK; ++kk) {
-        const bf16x8_t a = *(const bf16x8_t *)(Ks + (st * 32 + j) * KP + kk * 16 + g * 8);
+        const bf16x8_t a = T::frag_k(Ks + st * 32 * HD, fk, kk, g);
         sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], sa, 0, 0, 0);
-        const bf16x8_t b = *(const bf16x8_t *)(Vs + (st * 32 + j) * KP + kk * 16 + g * 8);
+        const bf16x8_t b = T::frag_k(Vs + st * 32 * HD, fk, kk, g);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, dof[kk], dp, 0, 0, 0);
       }
       float ds[16];
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int key = kb + st * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-        const float p = (key <= qi && key < L) ? exp2f(sa[r] * sc - lse2) : 0.f;
+        float p = __builtin_amdgcn_exp2f(fmaf(sa[r], sc, -lse2));
+        if (need_mask) {
+          const int key = kb + st * 32 + 16 * (r >> 3) + 8 * g + (r & 7);
+          if (!(key <= qi && key < L)) p = 0.f;
+        }
         ds[r] = p * (dp[r] - dv_) * rs;
       }
 #pragma unroll
@@ -152,7 +131,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t *__restri
         const bf16x8_t dsf = pack8(ds + 8 * mm);
 #pragma unroll
         for (int t = 0; t < NOT; ++t) {
-          const bf16x8_t a = *(const bf16x8_t *)(Kt + (t * 32 + j) * TP + st * 32 + mm * 16 + g * 8);
+          const bf16x8_t a = T::frag_t(Ks, ft[t], 2 * st + mm);
           acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, dsf, acc[t], 0, 0, 0);
         }
       }
@@ -175,14 +154,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(const bf16_t *__rest
                                                             const float *__restrict__ lse, const float *__restrict__ dvec,
                                                             const int32_t *__restrict__ seg, int row_base, int Hq,
                                                             int Hkv, float *__restrict__ dk, float *__restrict__ dv) {
-  constexpr int KP = HD + 8, TP = TB + 8, NKK = HD / 16, NOT = HD / 32;
+  constexpr int NKK = HD / 16, NOT = HD / 32;
+  using T = Tile<TB, HD, 256>;
+  constexpr int STAGE = 2 * T::ELEMS + 4 * TB;    // Q tile, dO tile, lse[TB] and D[TB] as fp32 (2 bf16 slots each)
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  bf16_t *Qs = (bf16_t *)smem_raw;          // [TB][KP]
-  bf16_t *Os = Qs + TB * KP;                // [TB][KP]   dO rows
-  bf16_t *Qt = Os + TB * KP;                // [HD][TP]
-  bf16_t *Ot = Qt + HD * TP;                // [HD][TP]   dO transposed
-  float *lse_s = (float *)(Ot + HD * TP);   // [TB]  lse * log2(e)
-  float *d_s = lse_s + TB;                  // [TB]
+  bf16_t *lds = (bf16_t *)smem_raw;               // [2][STAGE]
   const int s = blockIdx.y, kvh = blockIdx.z, grp = Hq / Hkv;
   const int r0 = seg[s] - row_base, L = seg[s + 1] - seg[s];
   const int k0 = blockIdx.x * 128;
@@ -190,6 +166,22 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(const bf16_t *__rest
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, j = lane & 31;
   const int kw0 = k0 + wave * 32, ki = kw0 + j;      // this lane's key
   const size_t qld = (size_t)Hq * HD, kld = (size_t)Hkv * HD;
+  const int nqt = (L - k0 + TB - 1) / TB;            // query tiles per head (k0 is a multiple of TB)
+  const int niter = grp * nqt;
+  auto issue_tile = [&](int it) {
+    const int gi = it / nqt, qb = k0 + (it % nqt) * TB;
+    const int h = kvh * grp + gi;
+    bf16_t *S = lds + (it & 1) * STAGE;
+    T::issue(q + (size_t)r0 * qld + (size_t)h * HD, qld, qb, L, S);
+    T::issue(d_o + (size_t)r0 * qld + (size_t)h * HD, qld, qb, L, S + T::ELEMS);
+    if (wave < 2) {                                  // one 4-byte element per lane: lane's value lands at base + 4*lane
+      const int qq = qb + lane;
+      const float *src = wave ? dvec : lse;
+      const float *p = qq < L ? src + (size_t)(r0 + qq) * Hq + h : (const float *)&zero16;
+      __builtin_amdgcn_global_load_lds((gbl_void_t *)p, (lds_void_t *)(S + 2 * T::ELEMS + wave * 2 * TB), 4, 0, 0);
+    }
+  };
+  issue_tile(0);
 
   bf16x8_t kf[NKK], vf[NKK];
 #pragma unroll
@@ -204,65 +196,67 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(const bf16_t *__rest
     vf[kk] = as_bf8(b);
   }
   const float sc = 1.4426950408889634f / sqrtf((float)HD), rs = 1.0f / sqrtf((float)HD);
+  // MFMA row j reads tile row swap23(j): register r = 8*mm + e then holds query 16*mm + 8*g + e
+  const typename T::FragK fk = T::frag_k_init(swap23(j));
+  typename T::FragT ft[NOT];
+#pragma unroll
+  for (int t = 0; t < NOT; ++t) ft[t] = T::frag_t_init(32 * t, lane);
   f32x16_t dka[NOT], dva[NOT];
 #pragma unroll
   for (int t = 0; t < NOT; ++t)
 #pragma unroll
     for (int r = 0; r < 16; ++r) { dka[t][r] = 0.f; dva[t][r] = 0.f; }
 
-  for (int gi = 0; gi < grp; ++gi) {
-    const int h = kvh * grp + gi;
-    const bf16_t *qbase = q + (size_t)r0 * qld + (size_t)h * HD, *obase = d_o + (size_t)r0 * qld + (size_t)h * HD;
-    for (int qb = k0; qb < L; qb += TB) {            // k0 is a multiple of 128, so of TB
-      __syncthreads();
-      stage_rows<HD>(Qs, qbase, qld, qb, L);
-      stage_rows<HD>(Os, obase, qld, qb, L);
-      stage_rows_t<HD>(Qt, qbase, qld, qb, L);
-      stage_rows_t<HD>(Ot, obase, qld, qb, L);
-      if (tid < TB) {
-        const int qq = qb + tid;
-        lse_s[tid] = qq < L ? lse[(size_t)(r0 + qq) * Hq + h] * 1.4426950408889634f : 0.f;
-        d_s[tid] = qq < L ? dvec[(size_t)(r0 + qq) * Hq + h] : 0.f;
+  for (int it = 0; it < niter; ++it) {
+    wait_vmcnt<0>();
+    __syncthreads();                                 // tile it has landed; the other stage is free
+    if (it + 1 < niter) issue_tile(it + 1);
+    const int qb = k0 + (it % nqt) * TB;
+    if (qb + TB - 1 < kw0) continue;                 // every query of the tile precedes this wave's keys
+    const bf16_t *Qs = lds + (it & 1) * STAGE, *Os = Qs + T::ELEMS;
+    const float *lse_s = (const float *)(Os + T::ELEMS), *d_s = lse_s + TB;
+    const bool need_mask = qb < kw0 + 31 || qb + TB > L || kw0 + 32 > L;
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+      f32x16_t sa, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sa[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+      for (int kk = 0; kk < NKK; ++kk) {
+        const bf16x8_t a = T::frag_k(Qs + st * 32 * HD, fk, kk, g);
+        sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[kk], sa, 0, 0, 0);
+        const bf16x8_t b = T::frag_k(Os + st * 32 * HD, fk, kk, g);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, vf[kk], dp, 0, 0, 0);
       }
-      __syncthreads();
-      if (qb + TB - 1 < kw0) continue;               // every query of the tile precedes this wave's keys
+      float pv[16], ds[16];
 #pragma unroll
-      for (int st = 0; st < 2; ++st) {
-        f32x16_t sa, dp;
+      for (int mm = 0; mm < 2; ++mm) {
+        const int qo = st * 32 + 16 * mm + 8 * g;    // first of the 8 queries in registers 8*mm .. 8*mm+7
+        const float4 la = *(const float4 *)(lse_s + qo), lb = *(const float4 *)(lse_s + qo + 4);
+        const float4 da = *(const float4 *)(d_s + qo), db = *(const float4 *)(d_s + qo + 4);
+        const float ll[8] = {la.x, la.y, la.z, la.w, lb.x, lb.y, lb.z, lb.w};
+        const float dd[8] = {da.x, da.y, da.z, da.w, db.x, db.y, db.z, db.w};
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { sa[r] = 0.f; dp[r] = 0.f; }
-#pragma unroll
-        for (int kk = 0; kk < NKK; ++kk) {
-          const bf16x8_t a = *(const bf16x8_t *)(Qs + (st * 32 + j) * KP + kk * 16 + g * 8);
-          sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[kk], sa, 0, 0, 0);
-          const bf16x8_t b = *(const bf16x8_t *)(Os + (st * 32 + j) * KP + kk * 16 + g * 8);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, vf[kk], dp, 0, 0, 0);
-        }
-        float pv[16], ds[16];
-#pragma unroll
-        for (int rq = 0; rq < 4; ++rq) {
-          const float4 l4 = *(const float4 *)(lse_s + st * 32 + 8 * rq + 4 * g);
-          const float4 d4 = *(const float4 *)(d_s + st * 32 + 8 * rq + 4 * g);
-          const float ll[4] = {l4.x, l4.y, l4.z, l4.w}, dd[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int r = 4 * rq + e;
-            const int qq = qb + st * 32 + 8 * rq + 4 * g + e;
-            const float p = (qq >= ki && qq < L && ki < L) ? exp2f(sa[r] * sc - ll[e]) : 0.f;
-            pv[r] = p;
-            ds[r] = p * (dp[r] - dd[e]) * rs;
+        for (int e = 0; e < 8; ++e) {
+          const int r = 8 * mm + e;
+          float p = __builtin_amdgcn_exp2f(fmaf(sa[r], sc, -1.4426950408889634f * ll[e]));
+          if (need_mask) {
+            const int qq = qb + qo + e;
+            if (!(qq >= ki && qq < L && ki < L)) p = 0.f;
           }
+          pv[r] = p;
+          ds[r] = p * (dp[r] - dd[e]) * rs;
         }
+      }
 #pragma unroll
-        for (int mm = 0; mm < 2; ++mm) {
-          const bf16x8_t pf = pack8(pv + 8 * mm), dsf = pack8(ds + 8 * mm);
+      for (int mm = 0; mm < 2; ++mm) {
+        const bf16x8_t pf = pack8(pv + 8 * mm), dsf = pack8(ds + 8 * mm);
 #pragma unroll
-          for (int t = 0; t < NOT; ++t) {
-            const bf16x8_t a = *(const bf16x8_t *)(Ot + (t * 32 + j) * TP + st * 32 + mm * 16 + g * 8);
-            dva[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf, dva[t], 0, 0, 0);
-            const bf16x8_t b = *(const bf16x8_t *)(Qt + (t * 32 + j) * TP + st * 32 + mm * 16 + g * 8);
-            dka[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, dsf, dka[t], 0, 0, 0);
-          }
+        for (int t = 0; t < NOT; ++t) {
+          const bf16x8_t a = T::frag_t(Os, ft[t], 2 * st + mm);
+          dva[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf, dva[t], 0, 0, 0);
+          const bf16x8_t b = T::frag_t(Qs, ft[t], 2 * st + mm);
+          dka[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, dsf, dka[t], 0, 0, 0);
         }
       }
     }
@@ -283,8 +277,8 @@ template <int HD>
 hipError_t launch_t(const bf16_t *q, const bf16_t *k, const bf16_t *v, const bf16_t *o, const bf16_t *d_o,
                     const float *lse, const int32_t *seg, int row_base, int n_seq, int max_len, int rows, int Hq,
                     int Hkv, float *dvec, float *dq, float *dk, float *dv, hipStream_t st) {
-  constexpr size_t lds_q = (size_t)(2 * TB * (HD + 8) + HD * (TB + 8)) * sizeof(bf16_t);
-  constexpr size_t lds_k = (size_t)(2 * TB * (HD + 8) + 2 * HD * (TB + 8)) * sizeof(bf16_t) + 2 * TB * sizeof(float);
+  constexpr size_t lds_q = (size_t)2 * (2 * TB * HD) * sizeof(bf16_t);
+  constexpr size_t lds_k = (size_t)2 * (2 * TB * HD + 4 * TB) * sizeof(bf16_t);
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute((const void *)attn_bwd_dq_kernel<HD>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_q);
