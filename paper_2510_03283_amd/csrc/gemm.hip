@@ -9,6 +9,7 @@
 #include "gemm.h"
 
 #include <cmath>
+#include <utility>
 
 namespace {
 
@@ -44,7 +45,10 @@ struct DirectStage {
   static constexpr int RPB = LAYOUT == 0 ? 16 / CPR : 1;         // LDS rows per 256 bytes (LAYOUT 0)
 
   // LAYOUT 0: LDS [row][BKT], chunk position pos holds logical k-chunk pos ^ ((row / RPB) % CPR)
-  // LAYOUT 1: LDS [k][ROWS],  chunk position pos holds logical row-chunk pos ^ ((k & 3) << 2)
+  // LAYOUT 1: LDS [k][ROWS],  logical row-chunk c sits at position c ^ ((k & 3) << 2) when CPR is a
+  //           power of two, else at (c + 4 * (k & 3)) % CPR (same bank spread, any CPR % 4 == 0)
+  static constexpr bool POW2 = (CPR & (CPR - 1)) == 0;
+  static_assert(LAYOUT == 0 || CPR % 4 == 0, "row-contiguous tiles need a multiple of 32 rows");
   static __device__ __forceinline__ void issue(const bf16_t *base, long long ld, int row0, int rows, int k0, int K, bf16_t *S) {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
 #pragma unroll
@@ -60,7 +64,7 @@ struct DirectStage {
         ok = gr < rows;
         src = base + (long long)gr * ld + k0 + kc * 8;
       } else {
-        const int c = pos ^ ((lr & 3) << 2);
+        const int c = POW2 ? pos ^ ((lr & 3) << 2) : (pos + CPR - 4 * (lr & 3)) % CPR;
         const int k = k0 + lr, gr = row0 + 8 * c;
         ok = k < K && gr < rows;
         src = base + (long long)k * ld + gr;
@@ -79,7 +83,8 @@ struct DirectStage {
       f.sw = (row / RPB) % CPR;
     } else {
       const int grp = lane >> 4, j = lane & 15;
-      const int chunk = ((r0 >> 3) + 2 * (grp & 1) + ((j & 3) >> 1)) ^ ((j >> 2) << 2);
+      const int cl = (r0 >> 3) + 2 * (grp & 1) + ((j & 3) >> 1);
+      const int chunk = POW2 ? cl ^ ((j >> 2) << 2) : (cl + 4 * (j >> 2)) % CPR;
       f.base = (8 * (grp >> 1) + (j >> 2)) * ROWS + chunk * 8 + 4 * (j & 1);
       f.sw = 0;
     }
@@ -114,23 +119,36 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(const Gemm
   extern __shared__ __align__(16) unsigned char smem_raw[];
   bf16_t *lds = (bf16_t *)smem_raw;
 
-  const int total_mt = p.mt_start[p.n_mg], total_nt = p.nt_start[p.n_ns];
-  const int total = total_mt * total_nt;
-  int v;
+  // Block -> tile.  Row groups are laid out one after the other in block-id order (the launcher
+  // sorts the multi-pass groups first, so the long tiles start first).  Inside a group, the blocks
+  // that land on XCD x (block id % 8) take a contiguous chunk of the group's tile list, ordered in
+  // bands of GROUP_M m-tiles, so the tiles resident on one XCD share A and B panels in its L2 and
+  // every XCD gets the same mix of long and short tiles.
+  const int total_nt = p.nt_start[p.n_ns];
+  int g = 0, first_blk = 0;
+  while (g + 1 < p.n_mg && (int)blockIdx.x >= first_blk + (p.mt_start[g + 1] - p.mt_start[g]) * total_nt) {
+    first_blk += (p.mt_start[g + 1] - p.mt_start[g]) * total_nt;
+    ++g;
+  }
+  const int mtc = p.mt_start[g + 1] - p.mt_start[g], T = mtc * total_nt;
+  int v = 0;
   {
-    const int per = total >> 3, rem = total & 7, xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
-    v = xcd < rem ? xcd * (per + 1) + idx : rem * (per + 1) + (xcd - rem) * per + idx;
+    const int x = blockIdx.x & 7;
+    for (int y = 0; y < x; ++y) {
+      const int fy = (y - first_blk) & 7;            // first block of the group on XCD y (group-local id)
+      v += fy < T ? (T - 1 - fy) / 8 + 1 : 0;
+    }
+    v += ((int)blockIdx.x - first_blk - ((x - first_blk) & 7)) >> 3;
   }
   const int grp_sz = GROUP_M * total_nt;
   const int first_m = (v / grp_sz) * GROUP_M;
-  const int gm = min(total_mt - first_m, GROUP_M);
-  const int mt_g = first_m + (v % grp_sz) % gm, nt_g = (v % grp_sz) / gm;
-  int g = 0, s = 0;
-  while (g + 1 < p.n_mg && mt_g >= p.mt_start[g + 1]) ++g;
+  const int gm = min(mtc - first_m, GROUP_M);
+  const int mt_l = first_m + (v % grp_sz) % gm, nt_g = (v % grp_sz) / gm;
+  int s = 0;
   while (s + 1 < p.n_ns && nt_g >= p.nt_start[s + 1]) ++s;
   const GemmMGroup &G = p.mg[g];
   const GemmNSeg &S = p.ns[s];
-  const int m0 = (mt_g - p.mt_start[g]) * BM, n0 = (nt_g - p.nt_start[s]) * BN;
+  const int m0 = mt_l * BM, n0 = (nt_g - p.nt_start[s]) * BN;
   const int M = G.M, N = S.N, K = p.K;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
@@ -262,25 +280,36 @@ int g_force_tile = -1;
 
 // Tile choice.  256x256 tiles (8 waves, one block per CU) do 0.75 LDS fragment reads per MFMA and
 // half the L2 traffic of 128x128 tiles (4 waves, two blocks per CU), but quantise worse on small
-// problems: compare the fraction of (CU x round) slots each choice keeps busy, with a 15 %
-// handicap for the small tile's lower efficiency.
+// problems; 192x256 (8 waves) sits between.  Each candidate is priced as
+//   rounds over its (CU x resident block) slots  x  tile area  /  measured relative efficiency,
+// a tile of a row group with p passes counting p times, and the cheapest is launched.
+template <int BM, int BN>
+double tile_cost(const GemmParams &p, int slots, double slot_share, double eff) {
+  double w = 0;
+  const int ks = p.k_splits > 1 ? p.k_splits : 1;
+  int nt = 0;
+  for (int s = 0; s < p.n_ns; ++s) nt += cdiv(p.ns[s].N, BN);
+  for (int g = 0; g < p.n_mg; ++g) w += (double)cdiv(p.mg[g].M, BM) * nt * p.mg[g].npass * ks;
+  return std::ceil(w / slots) * BM * BN * slot_share / eff;
+}
+
 template <int LA, int LB>
 hipError_t launch_layout(GemmParams &p, hipStream_t stream) {
   int tile = g_force_tile;
   if (tile < 0) {
-    GemmParams q = p;
-    const int ks = p.k_splits > 1 ? p.k_splits : 1;
-    const double t256 = (double)count_tiles<256, 256>(q) * ks, t128 = (double)count_tiles<128, 128>(q) * ks;
-    const double e256 = t256 / (std::ceil(t256 / 256.0) * 256.0), e128 = t128 / (std::ceil(t128 / 512.0) * 512.0);
-    tile = e256 * 1.15 >= e128 ? 1 : 0;
+    const double c256 = tile_cost<256, 256>(p, 256, 1.0, 1.0);
+    const double c192 = tile_cost<192, 256>(p, 256, 1.0, 0.92);
+    const double c128 = tile_cost<128, 128>(p, 512, 2.0, 0.83);
+    tile = c256 <= c192 && c256 <= c128 ? 1 : (c192 <= c128 ? 2 : 0);
   }
   if (tile == 1) return launch_dl<256, 256, 2, 4, LA, LB, BK, NSTAGES>(p, stream);
+  if (tile == 2) return launch_dl<192, 256, 2, 4, LA, LB, BK, NSTAGES>(p, stream);
   return launch_dl<128, 128, 2, 2, LA, LB, BK, NSTAGES>(p, stream);
 }
 
 }  // namespace
 
-// development hook: pin the tile configuration (0 = 128x128, 1 = 256x256, -1 = automatic)
+// development hook: pin the tile configuration (0 = 128x128, 1 = 256x256, 2 = 192x256, -1 = automatic)
 void gemm_force_tile(int id) { g_force_tile = id; }
 
 hipError_t gemm_launch(int LA, int LB, GemmParams &p, hipStream_t stream, const char **why) {
@@ -306,6 +335,9 @@ hipError_t gemm_launch(int LA, int LB, GemmParams &p, hipStream_t stream, const 
     if (S.N <= 0 || !S.b[0] || !aligned16(S.b[0]) || (S.b[1] && !aligned16(S.b[1]))) { *why = "gemm: bad column segment"; return hipErrorInvalidValue; }
     if (LB == 1 && S.N % 8) { *why = "gemm: N of an n-contiguous operand must be a multiple of 8"; return hipErrorInvalidValue; }
   }
+  // multi-pass row groups first (stable): their tiles take longest and should start first
+  for (int i = 1; i < p.n_mg; ++i)
+    for (int j = i; j > 0 && p.mg[j].npass > p.mg[j - 1].npass; --j) std::swap(p.mg[j], p.mg[j - 1]);
   if (LA == 0 && LB == 0) return launch_layout<0, 0>(p, stream);
   if (LA == 0 && LB == 1) return launch_layout<0, 1>(p, stream);
   if (LA == 1 && LB == 1) return launch_layout<1, 1>(p, stream);
