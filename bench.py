@@ -78,8 +78,18 @@ def main():
     for _ in range(args.warmup):
         it.step()
     torch.cuda.synchronize()
+    # Pass 1 (untimed): every launch bracketed by events -> per-class table and the dominant class.
+    # Pass 2 (the timed region): only the dominant class is bracketed, so `value` carries the cost of
+    # a handful of event records per step instead of one per launch.
+    prof_all, dom = {}, None
     if not args.no_profile:
         B.mace_profile_enable(it.h, True)
+        for _ in range(args.steps):
+            it.step()
+        torch.cuda.synchronize()
+        prof_all = B.mace_profile_collect(it.h)
+        dom = max((k for k in prof_all if prof_all[k]["launches"]), key=lambda k: prof_all[k]["ms"])
+        B.mace_profile_enable(it.h, [dom])
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -101,7 +111,6 @@ def main():
                    "decode_context_tokens": int(wl.batch.decode_ctx.sum()), "n_pairs": it.n_pairs},
     }
     if prof:
-        dom = max((k for k in prof if prof[k]["launches"]), key=lambda k: prof[k]["ms"])
         e = prof[dom]
         avg_ms = e["ms"] / e["launches"]
         hbm_classes = ("attn_decode", "logsoftmax", "dlogits")      # streamed once from HBM; the rest are contractions
@@ -116,9 +125,10 @@ def main():
                     "frac": ach / PEAK_HBM_GBS, "traffic": TRAFFIC_BYTES_PER_LAUNCH.get((args.workload, dom)),
                     "avg_launch_ms": avg_ms, "launches_per_step": e["launches"] / args.steps}
         out["roofline"] = roof
-        out["kernel_ms_per_step"] = {k: round(v["ms"] / args.steps, 4) for k, v in prof.items() if v["launches"]}
-        out["kernel_tflops"] = {k: round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 1) for k, v in prof.items() if v["launches"] and v["flops"] > 0}
-        out["kernel_gbps"] = {k: round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) for k, v in prof.items() if v["launches"] and v["bytes"] > 0}
+        # per-class figures of the untimed all-classes pass (side-stream classes overlap the main chain)
+        out["kernel_ms_per_step"] = {k: round(v["ms"] / args.steps, 4) for k, v in prof_all.items() if v["launches"]}
+        out["kernel_tflops"] = {k: round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 1) for k, v in prof_all.items() if v["launches"] and v["flops"] > 0}
+        out["kernel_gbps"] = {k: round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) for k, v in prof_all.items() if v["launches"] and v["bytes"] > 0}
     if not args.no_cpu_baseline and not big_cache:
         out["cpu_baseline"] = cpu_baseline(wl)
     it.close()

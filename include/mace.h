@@ -173,7 +173,13 @@ int mace_dpo_logprob_loss(mace_handle_t h, const float *h_ft, const void *g_fina
  * and each call ends with one more, so launch i lasts event[i+1] - event[i] on that stream.
  * mace_profile_collect waits for the last event (host-synchronising), sums launches, milliseconds
  * and algorithmic flops per kernel class into out[0 .. *n_out) (max_entries >= 16), and clears
- * the record.  At most 32768 launches are recorded between two collects; later ones are not timed. */
+ * the record.  At most 32768 launches are recorded between two collects; later ones are not timed.
+ * on = 0: off; on = 1: every kernel class; any other value: bit (i + 1) selects class i of the
+ * order in which mace_profile_collect reports them, and only launches of the selected classes are
+ * bracketed (an event before the launch, one before whatever is launched next), which keeps the
+ * cost of the events out of a timed region that needs one class only.  Launches that the
+ * library puts on its internal side stream (the weight-gradient GEMMs) are timed on that stream;
+ * they overlap with the main chain, so class times can add up to more than the wall time. */
 typedef struct {
   char name[48];      /* kernel class: gemm_nt, gemm_nn, gemm_tn, attn_fwd_prefill, attn_fwd_ft, attn_decode, ... */
   int64_t launches;

@@ -209,7 +209,17 @@ def mace_dpo_logprob_loss(h, h_ft, g_final, w_lm, token_ids, ft_seq_offsets, ft_
                                         workspace.numel() * workspace.element_size(), _stream(stream)), "mace_dpo_logprob_loss")
 
 
-def mace_profile_enable(h, on: bool):
+PROFILE_CLASSES = ["gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd_prefill", "attn_fwd_ft", "attn_decode", "attn_bwd",
+                   "rmsnorm", "rope", "swiglu", "logsoftmax", "dlogits", "misc"]
+
+
+def mace_profile_enable(h, on):
+    """on: False/0 off, True/1 all kernel classes, or a list of class names to time only those."""
+    if isinstance(on, (list, tuple, set)):
+        mask = 0
+        for name in on:
+            mask |= 1 << (PROFILE_CLASSES.index(name) + 1)
+        on = mask
     _check(load().mace_profile_enable(h, int(on)), "mace_profile_enable")
 
 

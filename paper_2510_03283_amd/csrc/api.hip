@@ -1,6 +1,7 @@
 // C ABI of the hybrid-iteration library: argument validation, workspace layout, launch sequences.
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -12,13 +13,25 @@
 // Optional in-stream timing: one event before every launch and one at the end of a call, so the
 // time of launch i is event[i+1] - event[i] on the stream the kernels run on.
 struct ProfMark {
-  int tag;         // index into PROF_TAGS, or -1 for the closing event of a call
+  int tag;         // index into PROF_TAGS, or -1 for a closing event
+  int chain;       // 0 = the caller's stream, 1 = the side stream
   double flops, bytes;
 };
+// The weight-gradient GEMMs of the backward pass depend on nothing that follows them, so they run
+// on a side stream of the context (same priority, non-blocking) forked from and joined back into
+// the caller's stream with events inside each call: they fill the CUs that the small dX GEMMs and
+// the elementwise kernels of the main chain leave idle.  MACE_SINGLE_STREAM=1 in the environment
+// keeps everything on the caller's stream.
+constexpr int N_FORK_EVENTS = 8;
 struct mace_ctx {
   mace_model_t m;
   double *inv_freq;   // device [head_dim/2]
+  hipStream_t side = nullptr;
+  hipEvent_t ev_fork[N_FORK_EVENTS] = {}, ev_join = nullptr;
+  int n_fork = 0;          // forks issued in the current call
   bool prof_on = false;
+  unsigned prof_mask = ~0u;        // kernel classes that are timed
+  bool prof_open[2] = {false, false};   // per chain: the last mark opened an interval
   std::vector<hipEvent_t> prof_events;
   std::vector<ProfMark> prof_marks;
 };
@@ -33,8 +46,30 @@ constexpr size_t PROF_MAX_MARKS = 1 << 15;
 
 void prof_mark(mace_ctx *h, hipStream_t st, int tag, double flops = 0.0, double bytes = 0.0) {
   if (!h->prof_on || h->prof_marks.size() >= h->prof_events.size()) return;
+  const int c = h->side && st == h->side ? 1 : 0;
+  const bool want = tag >= 0 && ((h->prof_mask >> tag) & 1u);
+  if (!want && !h->prof_open[c]) return;           // nothing to open and nothing to close
   if (hipEventRecord(h->prof_events[h->prof_marks.size()], st) != hipSuccess) return;
-  h->prof_marks.push_back({tag, flops, bytes});
+  h->prof_marks.push_back({want ? tag : -1, c, flops, bytes});
+  h->prof_open[c] = want;
+}
+
+// Side stream on which work may start once everything issued so far on `st` is done; returns `st`
+// itself when the context has no side stream.
+hipStream_t side_fork(mace_ctx *h, hipStream_t st) {
+  if (!h->side || h->n_fork >= N_FORK_EVENTS) return st;
+  hipEvent_t ev = h->ev_fork[h->n_fork];
+  if (hipEventRecord(ev, st) != hipSuccess || hipStreamWaitEvent(h->side, ev, 0) != hipSuccess) return st;
+  ++h->n_fork;
+  return h->side;
+}
+// Makes `st` wait for everything issued on the side stream in this call.
+hipError_t side_join(mace_ctx *h, hipStream_t st) {
+  if (!h->side || h->n_fork == 0) return hipSuccess;
+  h->n_fork = 0;
+  hipError_t e = hipEventRecord(h->ev_join, h->side);
+  if (e != hipSuccess) return e;
+  return hipStreamWaitEvent(st, h->ev_join, 0);
 }
 
 thread_local std::string g_err;
@@ -235,6 +270,13 @@ int run_gemm(mace_ctx *h, int LA, int LB, GemmParams &p, hipStream_t st, const c
   if (e != hipSuccess) return fail(why ? MACE_BAD_SHAPE : MACE_HIP_ERROR, std::string(where) + ": " + (why ? why : hipGetErrorString(e)));
   return MACE_OK;
 }
+// A GEMM nothing later in the call depends on: issued on the side stream (see mace_ctx).
+int run_gemm_side(mace_ctx *h, int LA, int LB, GemmParams &p, hipStream_t st, const char *where) {
+  hipStream_t s2 = side_fork(h, st);
+  const int rc = run_gemm(h, LA, LB, p, s2, where);
+  if (rc == MACE_OK && s2 != st) prof_mark(h, s2, -1);
+  return rc;
+}
 #define TRY(expr)                 \
   do {                            \
     int rc__ = (expr);            \
@@ -328,6 +370,16 @@ int mace_create(mace_handle_t *out, const mace_model_t *model) {
     delete c;
     return hip_fail(e, "mace_create");
   }
+  const char *single = getenv("MACE_SINGLE_STREAM");
+  if (!(single && single[0] == '1')) {
+    e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
+    for (int i = 0; i < N_FORK_EVENTS && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&c->ev_fork[i], hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming);
+    if (e != hipSuccess) {
+      mace_destroy(c);
+      return hip_fail(e, "mace_create: side stream");
+    }
+  }
   *out = c;
   return MACE_OK;
 }
@@ -335,6 +387,13 @@ int mace_create(mace_handle_t *out, const mace_model_t *model) {
 void mace_destroy(mace_handle_t h) {
   if (!h) return;
   if (h->inv_freq) (void)hipFree(h->inv_freq);
+  if (h->side) {
+    (void)hipStreamSynchronize(h->side);
+    (void)hipStreamDestroy(h->side);
+  }
+  for (hipEvent_t e : h->ev_fork)
+    if (e) (void)hipEventDestroy(e);
+  if (h->ev_join) (void)hipEventDestroy(h->ev_join);
   for (hipEvent_t e : h->prof_events) (void)hipEventDestroy(e);
   delete h;
 }
@@ -342,6 +401,8 @@ void mace_destroy(mace_handle_t h) {
 int mace_profile_enable(mace_handle_t h, int on) {
   if (!h) return fail(MACE_INVALID_ARG, "handle is null");
   h->prof_marks.clear();
+  h->prof_open[0] = h->prof_open[1] = false;
+  h->prof_mask = on == 1 ? ~0u : (unsigned)on >> 1;
   if (on && h->prof_events.empty()) {
     h->prof_events.reserve(PROF_MAX_MARKS);
     for (size_t i = 0; i < PROF_MAX_MARKS; ++i) {
@@ -362,18 +423,24 @@ int mace_profile_collect(mace_handle_t h, mace_profile_entry_t *out, int32_t max
     memset(&out[t], 0, sizeof(out[t]));
     snprintf(out[t].name, sizeof(out[t].name), "%s", PROF_TAGS[t]);
   }
-  for (size_t i = 0; i + 1 < n; ++i) {
-    const ProfMark &m = h->prof_marks[i];
-    if (m.tag < 0) continue;
-    float ms = 0.f;
-    HIP_TRY(hipEventElapsedTime(&ms, h->prof_events[i], h->prof_events[i + 1]), "hipEventElapsedTime");
-    out[m.tag].launches += 1;
-    out[m.tag].ms += ms;
-    out[m.tag].flops += m.flops;
-    out[m.tag].bytes += m.bytes;
+  if (h->side) HIP_TRY(hipStreamSynchronize(h->side), "hipStreamSynchronize");
+  long prev[2] = {-1, -1};                       // previous mark of each chain
+  for (size_t i = 0; i < n; ++i) {
+    const int c = h->prof_marks[i].chain;
+    if (prev[c] >= 0 && h->prof_marks[prev[c]].tag >= 0) {
+      const ProfMark &m = h->prof_marks[prev[c]];
+      float ms = 0.f;
+      HIP_TRY(hipEventElapsedTime(&ms, h->prof_events[prev[c]], h->prof_events[i]), "hipEventElapsedTime");
+      out[m.tag].launches += 1;
+      out[m.tag].ms += ms;
+      out[m.tag].flops += m.flops;
+      out[m.tag].bytes += m.bytes;
+    }
+    prev[c] = (long)i;
   }
   *n_out = T_COUNT;
   h->prof_marks.clear();
+  h->prof_open[0] = h->prof_open[1] = false;
   return MACE_OK;
 }
 
@@ -588,6 +655,7 @@ int mace_hybrid_layer_bwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
   const int acc = accumulate ? 1 : 0;
   const int n_part = Tf < DG_PARTS ? Tf : DG_PARTS;
 
+  HIP_TRY(side_join(h, st), "join side stream");      // no-op unless an earlier call failed between fork and join
   prof_mark(h, st, T_MISC);
   HIP_TRY(launch_split_f32(dy_ft, (size_t)Tf * D.d, B.dy_bf, nullptr, st), "cast dy");
   // MLP: dHm = dY Wd ; SwiGLU backward ; dWd = dY^T Hm
@@ -605,7 +673,7 @@ int mace_hybrid_layer_bwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
     p.resid_kind = acc;
     gp_group(p, B.dy_bf, nullptr, grads->w_down, grads->w_down, D.d, 1);
     gp_seg(p, B.hm, nullptr, D.F, 0);
-    TRY(run_gemm(h, 1, 1, p, st, "dWd gemm"));
+    TRY(run_gemm_side(h, 1, 1, p, st, "dWd gemm"));
   }
   // db = dG Wg + dU Wu ; dWg = dG^T b ; dWu = dU^T b
   {
@@ -625,7 +693,7 @@ int mace_hybrid_layer_bwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
     if (grads->w_gate) gp_group(p, B.dgu, nullptr, grads->w_gate, grads->w_gate, D.F, 1);
     if (grads->w_up) gp_group(p, B.dgu + D.F, nullptr, grads->w_up, grads->w_up, D.F, 1);
     gp_seg(p, S.b, nullptr, D.d, 0);
-    TRY(run_gemm(h, 1, 1, p, st, "dWg/dWu gemm"));
+    TRY(run_gemm_side(h, 1, 1, p, st, "dWg/dWu gemm"));
   }
   // RMSNorm (MLP) backward: dx1 = dy + ...
   prof_mark(h, st, T_RMSNORM);
@@ -645,7 +713,7 @@ int mace_hybrid_layer_bwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
     p.resid_kind = acc;
     gp_group(p, B.dx1_bf, nullptr, grads->wo, grads->wo, D.d, 1);
     gp_seg(p, S.o, nullptr, D.qd, 0);
-    TRY(run_gemm(h, 1, 1, p, st, "dWo gemm"));
+    TRY(run_gemm_side(h, 1, 1, p, st, "dWo gemm"));
   }
   // attention backward, RoPE backward
   prof_mark(h, st, T_ATTN_BWD, 10.0 * D.hd * D.Hq * I.pairs_ft);
@@ -672,7 +740,7 @@ int mace_hybrid_layer_bwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
       if (grads->wk) gp_group(p, as[1], nullptr, grads->wk, grads->wk, D.kd, 1);
       if (grads->wv) gp_group(p, as[2], nullptr, grads->wv, grads->wv, D.kd, 1);
       gp_seg(p, S.a, nullptr, D.d, 0);
-      TRY(run_gemm(h, 1, 1, p, st, "dWqkv gemm"));
+      TRY(run_gemm_side(h, 1, 1, p, st, "dWqkv gemm"));
     }
   }
   // RMSNorm (attention) backward: dx = dx1 + ...
@@ -681,6 +749,7 @@ int mace_hybrid_layer_bwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
   if (grads->g_attn) { prof_mark(h, st, T_MISC); HIP_TRY(launch_colsum(B.dg_part, n_part, D.d, grads->g_attn, acc, st), "dg1");
   }
   prof_mark(h, st, -1);
+  HIP_TRY(side_join(h, st), "join side stream");
   return MACE_OK;
 }
 
@@ -751,6 +820,8 @@ int mace_dpo_logprob_loss(mace_handle_t h, const float *h_ft, const void *g_fina
     prof_mark(h, st, -1);
     return MACE_OK;
   }
+  if (dg_final && !dh_ft && (size_t)Tf * D.d > (size_t)Ri * D.V) return fail(MACE_INVALID_ARG, "dg_final without dh_ft needs T_f*d <= R*V");
+  HIP_TRY(side_join(h, st), "join side stream");      // no-op unless an earlier call failed between fork and join
   prof_mark(h, st, T_DLOGITS, 0.0, (double)Ri * D.V * 6.0);
   HIP_TRY(launch_dlogits(P.logits, Ri, D.V, P.label, P.seq_id, P.lse, P.dlogp, P.dl, st), "dlogits");
   if (dw_lm) {
@@ -758,7 +829,7 @@ int mace_dpo_logprob_loss(mace_handle_t h, const float *h_ft, const void *g_fina
     p.resid_kind = acc;
     gp_group(p, P.dl, nullptr, dw_lm, dw_lm, D.V, 1);
     gp_seg(p, P.n_hi, nullptr, D.d, 0);
-    TRY(run_gemm(h, 1, 1, p, st, "dE gemm"));
+    TRY(run_gemm_side(h, 1, 1, p, st, "dE gemm"));
   }
   if (dh_ft || dg_final) {
     // small output, reduction over the whole vocabulary: slice k so that every CU has work
@@ -772,13 +843,13 @@ int mace_dpo_logprob_loss(mace_handle_t h, const float *h_ft, const void *g_fina
     const int n_part = Ri < DG_PARTS ? Ri : DG_PARTS;
     // without dh_ft the row gradients still have to land somewhere: reuse the logits buffer
     float *dx_dst = dh_ft ? dh_ft : P.logits;
-    if (!dh_ft && (size_t)Tf * D.d > (size_t)Ri * D.V) return fail(MACE_INVALID_ARG, "dg_final without dh_ft needs T_f*d <= R*V");
     prof_mark(h, st, T_RMSNORM);
     HIP_TRY(launch_rmsnorm_bwd(P.dn, h_ft, false, P.row_idx, g_final, D.bf, P.rstd, nullptr, Ri, D.d, dx_dst, nullptr, P.dg_part, n_part, st), "final rmsnorm bwd");
     if (dg_final) { prof_mark(h, st, T_MISC); HIP_TRY(launch_colsum(P.dg_part, n_part, D.d, dg_final, acc, st), "dg_final");
     }
   }
   prof_mark(h, st, -1);
+  HIP_TRY(side_join(h, st), "join side stream");
   return MACE_OK;
 }
 
