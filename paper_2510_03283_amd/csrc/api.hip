@@ -677,15 +677,14 @@ int mace_hybrid_layer_bwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
   }
   // db = dG Wg + dU Wu ; dWg = dG^T b ; dWu = dU^T b
   {
-    GemmParams p = gp_init(D.F, 2 * D.F, D.d, D.d);
+    // one product over the stacked reduction [dG | dU] x [Wg ; Wu]
+    GemmParams p = gp_init(2 * D.F, 2 * D.F, D.d, D.d);
     gp_group(p, B.dgu, nullptr, B.db, nullptr, Tf, 1);
     gp_seg(p, W.hi[W_G], nullptr, D.d, 0);
-    TRY(run_gemm(h, 0, 1, p, st, "db gemm (gate)"));
-    GemmParams p2 = gp_init(D.F, 2 * D.F, D.d, D.d);
-    p2.resid_kind = 1;
-    gp_group(p2, B.dgu + D.F, nullptr, B.db, B.db, Tf, 1);
-    gp_seg(p2, W.hi[W_U], nullptr, D.d, 0);
-    TRY(run_gemm(h, 0, 1, p2, st, "db gemm (up)"));
+    p.n_kseg = 2;
+    p.kseg_b[0] = W.hi[W_G]; p.kseg_b[1] = W.hi[W_U];
+    p.kseg_start[0] = 0; p.kseg_start[1] = D.F; p.kseg_start[2] = 2 * D.F;
+    TRY(run_gemm(h, 0, 1, p, st, "db gemm"));
   }
   if (grads->w_gate || grads->w_up) {
     GemmParams p = gp_init(Tf, 2 * D.F, D.d, D.d);
@@ -726,11 +725,14 @@ int mace_hybrid_layer_bwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
     const bf16_t *as[3] = {B.dqkv, B.dqkv + D.qd, B.dqkv + D.qd + D.kd};
     const int ks[3] = {D.qd, D.kd, D.kd};
     const int wi[3] = {W_Q, W_K, W_V};
-    for (int i = 0; i < 3; ++i) {
-      GemmParams p = gp_init(ks[i], D.nqkv, D.d, D.d);
-      p.resid_kind = i ? 1 : 0;
-      gp_group(p, as[i], nullptr, B.da, B.da, Tf, 1);
-      gp_seg(p, W.hi[wi[i]], nullptr, D.d, 0);
+    {
+      // one product over the stacked reduction [dQ | dK | dV] x [Wq ; Wk ; Wv]
+      GemmParams p = gp_init(D.nqkv, D.nqkv, D.d, D.d);
+      gp_group(p, B.dqkv, nullptr, B.da, nullptr, Tf, 1);
+      gp_seg(p, W.hi[W_Q], nullptr, D.d, 0);
+      p.n_kseg = 3;
+      for (int i = 0; i < 3; ++i) p.kseg_b[i] = W.hi[wi[i]];
+      p.kseg_start[0] = 0; p.kseg_start[1] = ks[0]; p.kseg_start[2] = ks[0] + ks[1]; p.kseg_start[3] = ks[0] + ks[1] + ks[2];
       TRY(run_gemm(h, 0, 1, p, st, "da gemm"));
     }
     if (grads->wq || grads->wk || grads->wv) {

@@ -33,6 +33,13 @@ struct GemmParams {
   long long lda, ldb, ldc, ldr;
   int out_bf16;     // 0: C is fp32, 1: C is bf16
   int resid_kind;   // 0 none, 1 fp32, 2 bf16 ; C = acc + resid
+  // K segments (optional, n_kseg > 1; needs n_ns == 1 and one pass): the k range is a concatenation
+  // and segment s (k in [kseg_start[s], kseg_start[s+1]), boundaries multiples of 64) takes its B
+  // rows from kseg_b[s] instead of ns[0].b[0] - several weight matrices stacked along the reduction
+  // (dX = dQ Wq + dK Wk + dV Wv as one product).
+  int n_kseg;
+  const bf16_t *kseg_b[3];
+  int kseg_start[4];
   int k_splits;     // > 1: grid.y slices of the k range; slice z writes fp32 partial sums at C + z * c_split_stride
   long long c_split_stride;   // elements
   int mt_start[4];  // filled by gemm_launch
@@ -40,7 +47,8 @@ struct GemmParams {
 };
 
 // Number of k slices worth using for a single-group, single-segment problem (1 = none): small
-// outputs with a long reduction leave most CUs idle otherwise.
+// outputs with a long reduction leave most CUs idle otherwise.  Priced with the launcher's tile
+// cost model plus the traffic of writing and summing the partial results.
 int gemm_suggest_k_splits(int M, int N, int K);
 
 // Returns hipSuccess or the launch error; a non-null *why is set on a rejected shape.

@@ -8,7 +8,9 @@
 // and no in-register shuffles.
 #include "gemm.h"
 
+#include <algorithm>
 #include <cmath>
+#include <cstring>
 #include <utility>
 
 namespace {
@@ -171,7 +173,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(const Gemm
     const int pass = it / nk, kt = kt0 + it - pass * nk;
     bf16_t *st = lds + stage * STAGE;
     SA::issue(G.a[pass == 1 ? 1 : 0], p.lda, m0, M, kt * BKT, K, st);
-    SB::issue(S.b[pass == 2 ? 1 : 0], p.ldb, n0, N, kt * BKT, K, st + SA::ELEMS);
+    if (p.n_kseg > 1) {
+      int ks = 0;
+      while (ks + 1 < p.n_kseg && kt * BKT >= p.kseg_start[ks + 1]) ++ks;
+      SB::issue(p.kseg_b[ks], p.ldb, n0, N, kt * BKT - p.kseg_start[ks], p.kseg_start[ks + 1] - p.kseg_start[ks], st + SA::ELEMS);
+    } else {
+      SB::issue(S.b[pass == 2 ? 1 : 0], p.ldb, n0, N, kt * BKT, K, st + SA::ELEMS);
+    }
   };
   typename SA::Frag fa[TM];
   typename SB::Frag fb[TN];
@@ -335,6 +343,13 @@ hipError_t gemm_launch(int LA, int LB, GemmParams &p, hipStream_t stream, const 
     if (S.N <= 0 || !S.b[0] || !aligned16(S.b[0]) || (S.b[1] && !aligned16(S.b[1]))) { *why = "gemm: bad column segment"; return hipErrorInvalidValue; }
     if (LB == 1 && S.N % 8) { *why = "gemm: N of an n-contiguous operand must be a multiple of 8"; return hipErrorInvalidValue; }
   }
+  if (p.n_kseg > 1) {
+    if (p.n_kseg > 3 || p.n_ns != 1 || p.kseg_start[0] != 0 || p.kseg_start[p.n_kseg] != p.K) { *why = "gemm: bad k segments"; return hipErrorInvalidValue; }
+    for (int g = 0; g < p.n_mg; ++g)
+      if (p.mg[g].npass != 1) { *why = "gemm: k segments need single-pass row groups"; return hipErrorInvalidValue; }
+    for (int s = 0; s < p.n_kseg; ++s)
+      if (!p.kseg_b[s] || !aligned16(p.kseg_b[s]) || p.kseg_start[s] % BK || p.kseg_start[s + 1] <= p.kseg_start[s]) { *why = "gemm: bad k segment"; return hipErrorInvalidValue; }
+  }
   // multi-pass row groups first (stable): their tiles take longest and should start first
   for (int i = 1; i < p.n_mg; ++i)
     for (int j = i; j > 0 && p.mg[j].npass > p.mg[j - 1].npass; --j) std::swap(p.mg[j], p.mg[j - 1]);
@@ -346,11 +361,24 @@ hipError_t gemm_launch(int LA, int LB, GemmParams &p, hipStream_t stream, const 
 }
 
 int gemm_suggest_k_splits(int M, int N, int K) {
-  const long long tiles = (long long)cdiv(M, 128) * cdiv(N, 128);
   const int nk = cdiv(K, BK);
-  if (tiles >= 256 || nk < 32) return 1;
-  long long sp = 512 / tiles;
-  if (sp > nk / 16) sp = nk / 16;
-  if (sp > 8) sp = 8;
-  return sp < 2 ? 1 : (int)sp;
+  if (nk < 32) return 1;
+  GemmParams p;
+  memset(&p, 0, sizeof(p));
+  p.n_mg = p.n_ns = 1;
+  p.mg[0].M = M; p.mg[0].npass = 1;
+  p.ns[0].N = N;
+  // seconds: a CU does about 3.5 TFLOP/s on a 256x256 tile; partial sums move at about 3 TB/s
+  double best = 0;
+  int best_ks = 1;
+  for (int ks = 1; ks <= 8; ++ks) {
+    if (nk / ks < 16) break;
+    p.k_splits = ks;
+    const double c = std::min(std::min(tile_cost<256, 256>(p, 256, 1.0, 1.0), tile_cost<192, 256>(p, 256, 1.0, 0.92)),
+                              tile_cost<128, 128>(p, 512, 2.0, 0.83));
+    double t = c * 2.0 * ((double)K / ks) / 3.5e12;
+    if (ks > 1) t += 4e-6 + (double)(ks + 1) * M * N * 4.0 / 3e12;
+    if (ks == 1 || t < best * 0.95) { best = t; best_ks = ks; }
+  }
+  return best_ks;
 }
