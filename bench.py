@@ -22,7 +22,7 @@ PEAK_HBM_GBS = 8000.0
 # rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, scaled by a plain copy, bytes per launch averaged over one step's
 # launches of the class: (workload, kernel class) -> bytes.  Source: profiles/bench_edge_gemm_nt_hbm_traffic.md
 # and profiles/bench_7b_decode_attn_decode_hbm_traffic.md.  Not measured -> null.
-TRAFFIC_BYTES_PER_LAUNCH = {("edge", "gemm_nt"): 5.996e8, ("7b_decode", "attn_decode"): 2.2127e10}
+TRAFFIC_BYTES_PER_LAUNCH = {("edge", "gemm_nt"): 6.561e8, ("7b_decode", "attn_decode"): 2.2127e10}
 
 
 def cpu_baseline(wl):
@@ -88,7 +88,10 @@ def main():
             it.step()
         torch.cuda.synchronize()
         prof_all = B.mace_profile_collect(it.h)
-        dom = max((k for k in prof_all if prof_all[k]["launches"]), key=lambda k: prof_all[k]["ms"])
+        # classes the library runs on its side stream overlap the main chain: their event times are not
+        # the kernel's own speed, so the roofline class is the largest one that runs alone
+        dom = max((k for k in prof_all if prof_all[k]["launches"] and not prof_all[k]["side_launches"]),
+                  key=lambda k: prof_all[k]["ms"])
         B.mace_profile_enable(it.h, [dom])
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -129,6 +132,7 @@ def main():
         out["kernel_ms_per_step"] = {k: round(v["ms"] / args.steps, 4) for k, v in prof_all.items() if v["launches"]}
         out["kernel_tflops"] = {k: round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 1) for k, v in prof_all.items() if v["launches"] and v["flops"] > 0}
         out["kernel_gbps"] = {k: round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) for k, v in prof_all.items() if v["launches"] and v["bytes"] > 0}
+        out["overlapped_classes"] = [k for k, v in prof_all.items() if v["side_launches"]]
     if not args.no_cpu_baseline and not big_cache:
         out["cpu_baseline"] = cpu_baseline(wl)
     it.close()

@@ -183,6 +183,7 @@ int mace_dpo_logprob_loss(mace_handle_t h, const float *h_ft, const void *g_fina
 typedef struct {
   char name[48];      /* kernel class: gemm_nt, gemm_nn, gemm_tn, attn_fwd_prefill, attn_fwd_ft, attn_decode, ... */
   int64_t launches;
+  int64_t side_launches;  /* how many of them ran on the library's side stream, overlapping the main chain */
   double ms;          /* summed duration */
   double flops;       /* summed algorithmic flops (GEMM classes: 2*M*N*K once per launch, extra operand passes not counted) */
   double bytes;       /* summed algorithmic bytes where the class is HBM-bound, else 0 */

@@ -52,7 +52,7 @@ class BatchT(C.Structure):
 
 
 class ProfileEntryT(C.Structure):
-    _fields_ = [("name", C.c_char * 48), ("launches", C.c_int64), ("ms", C.c_double), ("flops", C.c_double),
+    _fields_ = [("name", C.c_char * 48), ("launches", C.c_int64), ("side_launches", C.c_int64), ("ms", C.c_double), ("flops", C.c_double),
                 ("bytes", C.c_double)]
 
 
@@ -228,5 +228,5 @@ def mace_profile_collect(h) -> dict:
     arr = (ProfileEntryT * 16)()
     n = C.c_int32(0)
     _check(load().mace_profile_collect(h, arr, 16, C.byref(n)), "mace_profile_collect")
-    return {arr[i].name.decode(): dict(launches=int(arr[i].launches), ms=float(arr[i].ms), flops=float(arr[i].flops),
+    return {arr[i].name.decode(): dict(launches=int(arr[i].launches), side_launches=int(arr[i].side_launches), ms=float(arr[i].ms), flops=float(arr[i].flops),
                                        bytes=float(arr[i].bytes)) for i in range(n.value)}

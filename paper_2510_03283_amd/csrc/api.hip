@@ -432,6 +432,7 @@ int mace_profile_collect(mace_handle_t h, mace_profile_entry_t *out, int32_t max
       float ms = 0.f;
       HIP_TRY(hipEventElapsedTime(&ms, h->prof_events[prev[c]], h->prof_events[i]), "hipEventElapsedTime");
       out[m.tag].launches += 1;
+      out[m.tag].side_launches += c;
       out[m.tag].ms += ms;
       out[m.tag].flops += m.flops;
       out[m.tag].bytes += m.bytes;
