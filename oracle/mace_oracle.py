@@ -20,7 +20,10 @@ tiling, fusion or reordering.  Backward formulas are written out by hand (no aut
 Pins (tests/test_oracle_*.py): brute-force soft-max attention, decode == last row of causal
 attention, GQA == MHA with repeated KV heads, RoPE identities, RMSNorm scale invariance,
 closed forms of the DPO loss, uniform-logit closed form of the LM head, central finite
-differences for every gradient, batch-composition invariance, cache round trips.  The paper
+differences for every gradient, batch-composition invariance, cache round trips; for the
+adapter path: zero B == base model, equality with the merged weight W + scale*B*A in the forward
+and in dx, dA = scale*B^T dW and dB = scale*dW A^T against the full-weight gradient, and
+central finite differences on adapter entries.  The paper
 prints no worked numerical example for this path, so absolute values of the benchmark
 configurations are pinned by these invariants only.
 """
@@ -175,21 +178,45 @@ def _w(W, name):
     return np.asarray(W[name], F64)
 
 
-def project_qkv(dims, W, x, pos):
+def adapted_linear(u, W, lora, p):
+    """u W^T, plus the low-rank adapter term scale * (u A^T) B^T when `lora` holds a_p / b_p
+    (Section 5: a frozen base model shared by all requests with a trainable LoRA adapter on the
+    attention layers).  A is [rank, in], B is [out, rank]."""
+    y = u @ W.T
+    if lora is not None:
+        A, B = np.asarray(lora["a_" + p], F64), np.asarray(lora["b_" + p], F64)
+        y = y + F64(lora["scale"]) * ((u @ A.T) @ B.T)
+    return y
+
+
+def adapted_linear_bwd(dy, u, W, lora, p):
+    """Backward of adapted_linear with the base weight frozen: returns du, dA, dB.
+    t = u A^T ; dB = scale * dy^T t ; dt = scale * dy B ; dA = dt^T u ; du = dy W + dt A."""
+    A, B = np.asarray(lora["a_" + p], F64), np.asarray(lora["b_" + p], F64)
+    s = F64(lora["scale"])
+    t = u @ A.T
+    dB = s * (dy.T @ t)
+    dt = s * (dy @ B)
+    dA = dt.T @ u
+    du = dy @ W + dt @ A
+    return du, dA, dB
+
+
+def project_qkv(dims, W, x, pos, lora=None):
     """Steps 1-3 of the forward: RMSNorm, Q/K/V projections, RoPE on q and k."""
     a, r1 = rmsnorm(x, _w(W, "g1"), dims.rms_eps)
     T = a.shape[0]
-    q = (a @ _w(W, "wq").T).reshape(T, dims.n_q_heads, dims.head_dim)
-    k = (a @ _w(W, "wk").T).reshape(T, dims.n_kv_heads, dims.head_dim)
-    v = (a @ _w(W, "wv").T).reshape(T, dims.n_kv_heads, dims.head_dim)
+    q = adapted_linear(a, _w(W, "wq"), lora, "q").reshape(T, dims.n_q_heads, dims.head_dim)
+    k = adapted_linear(a, _w(W, "wk"), lora, "k").reshape(T, dims.n_kv_heads, dims.head_dim)
+    v = adapted_linear(a, _w(W, "wv"), lora, "v").reshape(T, dims.n_kv_heads, dims.head_dim)
     q = rope(q, pos, dims.rope_theta)
     k = rope(k, pos, dims.rope_theta)
     return a, r1, q, k, v
 
 
-def mlp_block(dims, W, x, attn):
+def mlp_block(dims, W, x, attn, lora=None):
     """Steps 6-7: x1 = x + Wo attn ; y = x1 + Wd (silu(Wg b) * (Wu b)), b = RMSNorm(x1)."""
-    x1 = np.asarray(x, F64) + attn @ _w(W, "wo").T
+    x1 = np.asarray(x, F64) + adapted_linear(attn, _w(W, "wo"), lora, "o")
     b, r2 = rmsnorm(x1, _w(W, "g2"), dims.rms_eps)
     G = b @ _w(W, "wg").T
     U = b @ _w(W, "wu").T
@@ -198,13 +225,15 @@ def mlp_block(dims, W, x, attn):
     return y, dict(x1=x1, b=b, r2=r2, G=G, U=U, Hm=Hm)
 
 
-def layer_forward(dims, W, batch, x, cache_k, cache_v):
+def layer_forward(dims, W, batch, x, cache_k, cache_v, lora=None):
     """One hybrid iteration of the layer, request by request.
 
     batch: object with prefill_lens, decode_ctx, ft_lens, seg_offsets, positions, block_size,
     prefill_block_tables, decode_block_tables.  x[T, d] rows ordered prefill | decode | ft.
     cache_k / cache_v: [blocks, Hkv, B, hd] float64, updated in place with the post-RoPE keys
     and the values of the prefill and decode rows.
+    lora (optional): adapter on the attention projections; every row of the iteration sees the
+    same model, base plus adapter.
     Returns y[T, d], the slot mapping of the inference rows (int64), and per ft sequence the
     intermediates the backward pass needs."""
     x = np.asarray(x, F64)
@@ -218,18 +247,18 @@ def layer_forward(dims, W, batch, x, cache_k, cache_v):
     for i in range(npf):
         o0, o1 = seg[i], seg[i + 1]
         pos = np.asarray(batch.positions[o0:o1])
-        a, r1, q, k, v = project_qkv(dims, W, x[o0:o1], pos)
+        a, r1, q, k, v = project_qkv(dims, W, x[o0:o1], pos, lora)
         slots = slot_mapping(batch.prefill_block_tables[i], B, 0, o1 - o0)
         kv_append(cache_k, k, slots)
         kv_append(cache_v, v, slots)
         slots_all.append(slots)
         o, _, _ = causal_attention(q, k, v)
-        y[o0:o1], _ = mlp_block(dims, W, x[o0:o1], o.reshape(o1 - o0, -1))
+        y[o0:o1], _ = mlp_block(dims, W, x[o0:o1], o.reshape(o1 - o0, -1), lora)
     # decode requests: one new token at position n, appended, attends to n+1 keys
     for j in range(nd):
         t = seg[npf + j]
         n = int(batch.decode_ctx[j])
-        a, r1, q, k, v = project_qkv(dims, W, x[t:t + 1], np.array([n]))
+        a, r1, q, k, v = project_qkv(dims, W, x[t:t + 1], np.array([n]), lora)
         slots = slot_mapping(batch.decode_block_tables[j], B, n, 1)
         kv_append(cache_k, k, slots)
         kv_append(cache_v, v, slots)
@@ -237,15 +266,15 @@ def layer_forward(dims, W, batch, x, cache_k, cache_v):
         K, _ = kv_gather(cache_k, batch.decode_block_tables[j], n + 1)
         V, _ = kv_gather(cache_v, batch.decode_block_tables[j], n + 1)
         o = decode_attention(q[0], np.asarray(K, F64), np.asarray(V, F64))
-        y[t:t + 1], _ = mlp_block(dims, W, x[t:t + 1], o.reshape(1, -1))
+        y[t:t + 1], _ = mlp_block(dims, W, x[t:t + 1], o.reshape(1, -1), lora)
     # fine-tune sequences: causal attention, nothing cached, intermediates kept
     saved = []
     for s in range(len(batch.ft_lens)):
         o0, o1 = seg[npf + nd + s], seg[npf + nd + s + 1]
         pos = np.asarray(batch.positions[o0:o1])
-        a, r1, q, k, v = project_qkv(dims, W, x[o0:o1], pos)
+        a, r1, q, k, v = project_qkv(dims, W, x[o0:o1], pos, lora)
         o, lse, P = causal_attention(q, k, v)
-        y[o0:o1], sv = mlp_block(dims, W, x[o0:o1], o.reshape(o1 - o0, -1))
+        y[o0:o1], sv = mlp_block(dims, W, x[o0:o1], o.reshape(o1 - o0, -1), lora)
         sv.update(x=x[o0:o1], a=a, r1=r1, q=q, k=k, v=v, o=o, lse=lse, P=P, pos=pos)
         saved.append(sv)
     slots_cat = np.concatenate(slots_all) if slots_all else np.zeros(0, np.int64)
@@ -379,12 +408,56 @@ def dpo_head_backward(dims, W, head):
     return dys, dE, dgf
 
 
+def layer_backward_lora(dims, W, lora, saved, dy_list):
+    """Backward of the layer over the fine-tune sequences when only the adapter is trained: the
+    base weights and gains are frozen, so the pass produces dx per sequence and the summed
+    gradients of a_p, b_p for p in q, k, v, o - no base-weight gradient is formed."""
+    grads = {}
+    for p in ("q", "k", "v", "o"):
+        grads["a_" + p] = np.zeros_like(np.asarray(lora["a_" + p], F64))
+        grads["b_" + p] = np.zeros_like(np.asarray(lora["b_" + p], F64))
+
+    def acc(p, dA, dB):
+        grads["a_" + p] += dA
+        grads["b_" + p] += dB
+
+    dxs = []
+    for sv, dy in zip(saved, dy_list):
+        dy = np.asarray(dy, F64)
+        L = dy.shape[0]
+        dHm = dy @ _w(W, "wd")
+        dx1 = dy.copy()
+        sg = sigmoid(sv["G"])
+        dU = dHm * (sv["G"] * sg)
+        dG = dHm * sv["U"] * sg * (1.0 + sv["G"] * (1.0 - sg))
+        db = dG @ _w(W, "wg") + dU @ _w(W, "wu")
+        dxa, _ = rmsnorm_bwd(db, sv["x1"], _w(W, "g2"), sv["r2"])
+        dx1 += dxa
+        attn = sv["o"].reshape(L, -1)
+        dattn, dA, dB = adapted_linear_bwd(dx1, attn, _w(W, "wo"), lora, "o")
+        acc("o", dA, dB)
+        dx = dx1.copy()
+        dq, dk, dv = causal_attention_bwd(dattn.reshape(sv["o"].shape), sv["q"], sv["k"], sv["v"], sv["o"], sv["P"])
+        dq = rope(dq, sv["pos"], dims.rope_theta, sign=-1.0)
+        dk = rope(dk, sv["pos"], dims.rope_theta, sign=-1.0)
+        da = np.zeros_like(sv["a"])
+        for p, g, wn in (("q", dq.reshape(L, -1), "wq"), ("k", dk.reshape(L, -1), "wk"), ("v", dv.reshape(L, -1), "wv")):
+            du, dA, dB = adapted_linear_bwd(g, sv["a"], _w(W, wn), lora, p)
+            da += du
+            acc(p, dA, dB)
+        dxa, _ = rmsnorm_bwd(da, sv["x"], _w(W, "g1"), sv["r1"])
+        dx += dxa
+        dxs.append(dx)
+    return dxs, grads
+
+
 # --------------------------------------------------------------------------- whole iteration
 
-def hybrid_iteration(dims, W, batch, x, cache_k, cache_v, ref_logp, beta, backward=True):
+def hybrid_iteration(dims, W, batch, x, cache_k, cache_v, ref_logp, beta, backward=True, lora=None):
     """Forward of all rows, DPO head over the ft sequences, and the backward pass of the ft
-    sequences.  Returns a dict with y, slots, the head outputs, and the gradients."""
-    y, slots, saved = layer_forward(dims, W, batch, x, cache_k, cache_v)
+    sequences.  Returns a dict with y, slots, the head outputs, and the gradients (with `lora`:
+    the adapter gradients only, the base model being frozen)."""
+    y, slots, saved = layer_forward(dims, W, batch, x, cache_k, cache_v, lora)
     seg = np.asarray(batch.seg_offsets, dtype=np.int64)
     base = len(batch.prefill_lens) + len(batch.decode_ctx)
     y_ft = [y[seg[base + s]:seg[base + s + 1]] for s in range(len(batch.ft_lens))]
@@ -392,9 +465,12 @@ def hybrid_iteration(dims, W, batch, x, cache_k, cache_v, ref_logp, beta, backwa
     out = dict(y=y, slots=slots, head=head, saved=saved)
     if backward:
         dys, dE, dgf = dpo_head_backward(dims, W, head)
-        dxs, grads = layer_backward(dims, W, saved, dys)
-        grads["E"] = dE
-        grads["gf"] = dgf
+        if lora is not None:
+            dxs, grads = layer_backward_lora(dims, W, lora, saved, dys)
+        else:
+            dxs, grads = layer_backward(dims, W, saved, dys)
+            grads["E"] = dE
+            grads["gf"] = dgf
         out.update(dy_ft=np.concatenate(dys), dx_ft=np.concatenate(dxs), grads=grads)
     return out
 

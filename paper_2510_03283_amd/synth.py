@@ -30,6 +30,8 @@ STREAMS = {
     "wd": 9, "gf": 10, "prefill_len": 11, "decode_ctx": 12, "resp_len": 13,
     "token_ids": 14, "cache_k": 15, "cache_v": 16, "ref_logp": 17, "block_perm": 18,
     "dy": 19,
+    "lora_a_q": 20, "lora_b_q": 21, "lora_a_k": 22, "lora_b_k": 23, "lora_a_v": 24, "lora_b_v": 25,
+    "lora_a_o": 26, "lora_b_o": 27,
 }
 
 
@@ -199,6 +201,20 @@ def make_weights(spec: ConfigSpec) -> Dict[str, np.ndarray]:
     for name in ("g1", "g2", "gf"):
         w[name] = _maybe_bf16(1.0 + 0.02 * normal(s, STREAMS[name], 0, m.d_model), m.io_bf16)
     return w
+
+
+def make_lora(spec: ConfigSpec, rank: int = 16, scale: float = 2.0) -> Dict[str, object]:
+    """Low-rank adapters on the four attention projections: for projection p with weight
+    [out, in], a_p [rank, in] and b_p [out, rank], both N(0, 0.02) (b is non-zero on purpose so
+    that every term of the adapter arithmetic is exercised), stored in the io dtype."""
+    m, s = spec.dims, spec.seed
+    qd, kvd = m.n_q_heads * m.head_dim, m.n_kv_heads * m.head_dim
+    io = {"q": (qd, m.d_model), "k": (kvd, m.d_model), "v": (kvd, m.d_model), "o": (m.d_model, qd)}
+    lora: Dict[str, object] = {"rank": int(rank), "scale": float(scale)}
+    for pn, (n_out, n_in) in io.items():
+        lora["a_" + pn] = _maybe_bf16(0.02 * normal(s, STREAMS["lora_a_" + pn], 0, rank * n_in).reshape(rank, n_in), m.io_bf16)
+        lora["b_" + pn] = _maybe_bf16(0.02 * normal(s, STREAMS["lora_b_" + pn], 0, n_out * rank).reshape(n_out, rank), m.io_bf16)
+    return lora
 
 
 def make_batch(spec: ConfigSpec, n_prefill=None, n_decode=None, n_pairs=None) -> Batch:
