@@ -25,7 +25,7 @@ PEAK_HBM_GBS = 8000.0
 TRAFFIC_BYTES_PER_LAUNCH = {("edge", "gemm_nt"): 6.561e8, ("7b_decode", "attn_decode"): 2.2127e10}
 
 
-def cpu_baseline(wl):
+def cpu_baseline(wl, lora=None):
     """The oracle as it stands, timed once on the whole workload on the host cores."""
     sys.path.insert(0, os.path.join(ROOT, "tests"))
     from helpers import run_oracle
@@ -35,7 +35,7 @@ def cpu_baseline(wl):
     except Exception:
         cores = os.cpu_count() or 1
     t0 = time.time()
-    run_oracle(wl, backward=True)
+    run_oracle(wl, backward=True, lora=lora)
     dt = time.time() - t0
     return {"value": wl.batch.n_tokens / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
             "sample": f"whole workload, 1 pass ({wl.batch.n_tokens} rows, {dt:.1f} s)"}
@@ -47,6 +47,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="edge", help="synthetic configuration (default: the one the metric is quoted on)")
+    ap.add_argument("--variant", default="full", choices=["full", "lora"],
+                    help="full: all seven weight gradients (the headline metric); lora: frozen base model, rank-16 "
+                         "adapters on the attention projections, adapter gradients only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket launches with events")
     ap.add_argument("--calib-copy", action="store_true",
@@ -67,7 +70,8 @@ def main():
     B.load()   # fails loudly when the HIP library is not built
     big_cache = args.workload in ("7b", "7b_decode", "7b_ft")     # cached contexts drawn on the GPU
     wl = synth.make_workload(args.workload, with_cache=not big_cache)
-    it = DeviceIteration(wl, device_cache_seed=wl.spec.seed if big_cache else None)
+    lora = synth.make_lora(wl.spec, rank=16, scale=2.0) if args.variant == "lora" else None
+    it = DeviceIteration(wl, device_cache_seed=wl.spec.seed if big_cache else None, lora=lora)
     if args.calib_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB read + 1 GiB written per copy
         dst = torch.empty_like(src)
@@ -111,7 +115,8 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload} (BASELINE.json configs[{synth.CONFIG_ORDER.index(args.workload)}])",
                    "rows": T, "prefill_rows": it.Tp, "decode_rows": it.Td, "ft_rows": it.Tf, "loss_rows": it.R,
-                   "decode_context_tokens": int(wl.batch.decode_ctx.sum()), "n_pairs": it.n_pairs},
+                   "decode_context_tokens": int(wl.batch.decode_ctx.sum()), "n_pairs": it.n_pairs,
+                   "variant": "full fine-tune (7 weight gradients + head)" if lora is None else "LoRA rank 16 on q,k,v,o (adapter gradients only)"},
     }
     if prof:
         e = prof[dom]
@@ -134,7 +139,7 @@ def main():
         out["kernel_gbps"] = {k: round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) for k, v in prof_all.items() if v["launches"] and v["bytes"] > 0}
         out["overlapped_classes"] = [k for k, v in prof_all.items() if v["side_launches"]]
     if not args.no_cpu_baseline and not big_cache:
-        out["cpu_baseline"] = cpu_baseline(wl)
+        out["cpu_baseline"] = cpu_baseline(wl, lora)
     it.close()
     print(json.dumps(out))
 

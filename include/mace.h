@@ -142,6 +142,30 @@ int mace_hybrid_layer_bwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
                           const mace_layer_grads_t *grads, int accumulate,
                           void *workspace, size_t workspace_bytes, void *stream);
 
+/* Adapter (LoRA) variant of the two layer calls (Section 5, fine-tune worker: every user or domain
+ * owns a low-rank adapter while the base model stays frozen and shared by all requests).  The
+ * four attention projections become  u W^T + scale * (u A^T) B^T  with A [rank, in] and
+ * B [out, rank] (device, io_dtype, row-major; in/out as for wq, wk, wv, wo), 1 <= rank <= 64.
+ * Every row of the iteration sees base + adapter.  The backward forms no base-weight gradient:
+ * it returns dx_ft and the fp32 gradients of the eight adapter matrices (same shapes; a NULL
+ * pointer skips that one; overwritten, or added to when accumulate != 0).  Workspace and saved
+ * sizes are those of mace_workspace_bytes / mace_fwd_saved_bytes. */
+typedef struct {
+  const void *a_q, *b_q, *a_k, *b_k, *a_v, *b_v, *a_o, *b_o;
+  int32_t rank;
+  float scale;
+} mace_lora_t;
+typedef struct {
+  float *a_q, *b_q, *a_k, *b_k, *a_v, *b_v, *a_o, *b_o;
+} mace_lora_grads_t;
+int mace_hybrid_layer_fwd_lora(mace_handle_t h, const mace_layer_w_t *w, const mace_lora_t *lora,
+                               const mace_batch_t *batch, mace_kv_cache_t *cache, const void *x, float *y,
+                               void *saved, void *workspace, size_t workspace_bytes, void *stream);
+int mace_hybrid_layer_bwd_lora(mace_handle_t h, const mace_layer_w_t *w, const mace_lora_t *lora,
+                               const mace_batch_t *batch, const void *x, const float *dy_ft,
+                               const void *saved, float *dx_ft, const mace_lora_grads_t *grads,
+                               int accumulate, void *workspace, size_t workspace_bytes, void *stream);
+
 /* DPO head over the fine-tune rows (Section 3.1).  For sequence s with prompt length P_s and
  * length L_s, rows t = P_s-1 .. L_s-2 predict token t+1 through a final RMSNorm (gain g_final)
  * and the tied head w_lm [vocab, d_model]; log pi(y|x) is the sum of those log-probabilities.

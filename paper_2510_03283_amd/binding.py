@@ -18,7 +18,8 @@ MACE_F32, MACE_BF16 = 0, 1
 EXPORTS = [
     "mace_create", "mace_destroy", "mace_last_error", "mace_fwd_saved_bytes", "mace_workspace_bytes",
     "mace_kv_slot_mapping", "mace_kv_cache_append", "mace_kv_cache_gather", "mace_hybrid_layer_fwd",
-    "mace_hybrid_layer_bwd", "mace_dpo_logprob_loss", "mace_profile_enable", "mace_profile_collect",
+    "mace_hybrid_layer_bwd", "mace_hybrid_layer_fwd_lora", "mace_hybrid_layer_bwd_lora", "mace_dpo_logprob_loss",
+    "mace_profile_enable", "mace_profile_collect",
 ]
 
 
@@ -38,6 +39,17 @@ class LayerWT(C.Structure):
 
 class LayerGradsT(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("g_attn", "wq", "wk", "wv", "wo", "g_mlp", "w_gate", "w_up", "w_down")]
+
+
+_LORA_NAMES = ("a_q", "b_q", "a_k", "b_k", "a_v", "b_v", "a_o", "b_o")
+
+
+class LoraT(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _LORA_NAMES] + [("rank", C.c_int32), ("scale", C.c_float)]
+
+
+class LoraGradsT(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _LORA_NAMES]
 
 
 class KvCacheT(C.Structure):
@@ -89,6 +101,10 @@ def load():
     lib.mace_hybrid_layer_fwd.restype = C.c_int
     lib.mace_hybrid_layer_bwd.argtypes = [vp, C.POINTER(LayerWT), C.POINTER(BatchT), vp, vp, vp, vp, C.POINTER(LayerGradsT), C.c_int, vp, sz, vp]
     lib.mace_hybrid_layer_bwd.restype = C.c_int
+    lib.mace_hybrid_layer_fwd_lora.argtypes = [vp, C.POINTER(LayerWT), C.POINTER(LoraT), C.POINTER(BatchT), C.POINTER(KvCacheT), vp, vp, vp, vp, sz, vp]
+    lib.mace_hybrid_layer_fwd_lora.restype = C.c_int
+    lib.mace_hybrid_layer_bwd_lora.argtypes = [vp, C.POINTER(LayerWT), C.POINTER(LoraT), C.POINTER(BatchT), vp, vp, vp, vp, C.POINTER(LoraGradsT), C.c_int, vp, sz, vp]
+    lib.mace_hybrid_layer_bwd_lora.restype = C.c_int
     lib.mace_dpo_logprob_loss.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, f32, vp, vp, vp, vp, vp, vp, vp, vp, C.c_int, vp, sz, vp]
     lib.mace_dpo_logprob_loss.restype = C.c_int
     lib.mace_profile_enable.argtypes = [vp, C.c_int]
@@ -195,6 +211,30 @@ def mace_hybrid_layer_bwd(h, w: LayerWT, batch: BatchDesc, x, dy_ft, saved, dx_f
     _check(load().mace_hybrid_layer_bwd(h, C.byref(w), C.byref(batch.struct), _dev(x), _dev(dy_ft), _dev(saved), _dev(dx_ft),
                                         C.byref(grads), int(accumulate), _dev(workspace), workspace.numel() * workspace.element_size(),
                                         _stream(stream)), "mace_hybrid_layer_bwd")
+
+
+def lora_struct(l: dict, rank: int, scale: float) -> LoraT:
+    """l: dict of device tensors keyed a_q, b_q, ..., b_o (io dtype)."""
+    return LoraT(*[l[k].data_ptr() for k in _LORA_NAMES], int(rank), float(scale))
+
+
+def lora_grads_struct(g: dict) -> LoraGradsT:
+    return LoraGradsT(*[(g[k].data_ptr() if g.get(k) is not None else None) for k in _LORA_NAMES])
+
+
+def mace_hybrid_layer_fwd_lora(h, w: LayerWT, lora: LoraT, batch: BatchDesc, cache: Optional[KvCacheT], x, y, saved, workspace, stream=None):
+    _check(load().mace_hybrid_layer_fwd_lora(h, C.byref(w), C.byref(lora), C.byref(batch.struct),
+                                             C.byref(cache) if cache is not None else None, _dev(x), _dev(y), _dev(saved),
+                                             _dev(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
+           "mace_hybrid_layer_fwd_lora")
+
+
+def mace_hybrid_layer_bwd_lora(h, w: LayerWT, lora: LoraT, batch: BatchDesc, x, dy_ft, saved, dx_ft, grads: LoraGradsT, accumulate,
+                               workspace, stream=None):
+    _check(load().mace_hybrid_layer_bwd_lora(h, C.byref(w), C.byref(lora), C.byref(batch.struct), _dev(x), _dev(dy_ft), _dev(saved),
+                                             _dev(dx_ft), C.byref(grads), int(accumulate), _dev(workspace),
+                                             workspace.numel() * workspace.element_size(), _stream(stream)),
+           "mace_hybrid_layer_bwd_lora")
 
 
 def mace_dpo_logprob_loss(h, h_ft, g_final, w_lm, token_ids, ft_seq_offsets, ft_seq_offsets_host, prompt_lens, prompt_lens_host,

@@ -227,6 +227,86 @@ BwdWs plan_bwd(const Dims &D, size_t Tf, Bump &w) {
   return B;
 }
 
+// ---------------------------------------------------------------- adapter (LoRA) scratch
+constexpr int LR = 64;   // adapter rank as the GEMM sees it (zero-padded)
+
+struct LoraWs {
+  bf16_t *aqkv_hi, *aqkv_lo;   // [3*LR, d]   rows: A_q | A_k | A_v, each padded to LR rows
+  bf16_t *ao_hi, *ao_lo;       // [LR, qd]
+  bf16_t *bblk_hi, *bblk_lo;   // [nqkv, 3*LR] block diagonal: B_q | B_k | B_v
+  bf16_t *bo_hi, *bo_lo;       // [d, LR]
+  float *t_qkv, *t_o;          // forward: u A^T of every row, [rows, 3*LR] and [rows, LR]
+  bf16_t *tq_hi, *tq_lo, *to_hi, *to_lo;
+  bf16_t *dtq, *dto;           // backward: dy B
+  float *dbblk, *dbo, *daqkv, *dao;
+};
+LoraWs plan_lora(const Dims &D, size_t rows, bool bwd, Bump &w) {
+  LoraWs L;
+  memset(&L, 0, sizeof(L));
+  const bool lo = !D.bf && !bwd;
+  L.aqkv_hi = w.take<bf16_t>((size_t)3 * LR * D.d);
+  L.ao_hi = w.take<bf16_t>((size_t)LR * D.qd);
+  L.bblk_hi = w.take<bf16_t>((size_t)D.nqkv * 3 * LR);
+  L.bo_hi = w.take<bf16_t>((size_t)D.d * LR);
+  if (lo) {
+    L.aqkv_lo = w.take<bf16_t>((size_t)3 * LR * D.d);
+    L.ao_lo = w.take<bf16_t>((size_t)LR * D.qd);
+    L.bblk_lo = w.take<bf16_t>((size_t)D.nqkv * 3 * LR);
+    L.bo_lo = w.take<bf16_t>((size_t)D.d * LR);
+  }
+  L.tq_hi = w.take<bf16_t>(rows * 3 * LR);
+  L.to_hi = w.take<bf16_t>(rows * LR);
+  if (!bwd) {
+    L.t_qkv = w.take<float>(rows * 3 * LR);
+    L.t_o = w.take<float>(rows * LR);
+    L.tq_lo = w.take<bf16_t>(rows * 3 * LR);
+    L.to_lo = w.take<bf16_t>(rows * LR);
+  } else {
+    L.dtq = w.take<bf16_t>(rows * 3 * LR);
+    L.dto = w.take<bf16_t>(rows * LR);
+    L.dbblk = w.take<float>((size_t)D.nqkv * 3 * LR);
+    L.dbo = w.take<float>((size_t)D.d * LR);
+    L.daqkv = w.take<float>((size_t)3 * LR * D.d);
+    L.dao = w.take<float>((size_t)LR * D.qd);
+  }
+  return L;
+}
+
+int check_lora(const mace_lora_t *l) {
+  if (!l) return fail(MACE_INVALID_ARG, "lora is null");
+  if (!l->a_q || !l->b_q || !l->a_k || !l->b_k || !l->a_v || !l->b_v || !l->a_o || !l->b_o) return fail(MACE_INVALID_ARG, "null adapter pointer");
+  if (l->rank < 1 || l->rank > LR) return fail(MACE_BAD_SHAPE, "adapter rank must be in 1..64");
+  if (!std::isfinite(l->scale)) return fail(MACE_INVALID_ARG, "adapter scale");
+  return MACE_OK;
+}
+
+// Pack the caller's adapters into the padded operands.  b_scale multiplies the B matrices (the
+// backward folds the adapter scale into them).
+int prepare_lora(const Dims &D, const mace_lora_t *l, const LoraWs &L, float b_scale, hipStream_t st) {
+  const int r = l->rank;
+  {
+    const void *src[3] = {l->a_q, l->a_k, l->a_v};
+    const int rows[3] = {r, r, r}, cols[3] = {D.d, D.d, D.d}, r0[3] = {0, LR, 2 * LR}, c0[3] = {0, 0, 0};
+    HIP_TRY(launch_lora_pack(src, rows, cols, r0, c0, 3, D.bf, 3 * LR, D.d, 1.0f, L.aqkv_hi, L.aqkv_lo, st), "pack A_qkv");
+  }
+  {
+    const void *src[1] = {l->a_o};
+    const int rows[1] = {r}, cols[1] = {D.qd}, z[1] = {0};
+    HIP_TRY(launch_lora_pack(src, rows, cols, z, z, 1, D.bf, LR, D.qd, 1.0f, L.ao_hi, L.ao_lo, st), "pack A_o");
+  }
+  {
+    const void *src[3] = {l->b_q, l->b_k, l->b_v};
+    const int rows[3] = {D.qd, D.kd, D.kd}, cols[3] = {r, r, r}, r0[3] = {0, D.qd, D.qd + D.kd}, c0[3] = {0, LR, 2 * LR};
+    HIP_TRY(launch_lora_pack(src, rows, cols, r0, c0, 3, D.bf, D.nqkv, 3 * LR, b_scale, L.bblk_hi, L.bblk_lo, st), "pack B_qkv");
+  }
+  {
+    const void *src[1] = {l->b_o};
+    const int rows[1] = {D.d}, cols[1] = {r}, z[1] = {0};
+    HIP_TRY(launch_lora_pack(src, rows, cols, z, z, 1, D.bf, D.d, LR, b_scale, L.bo_hi, L.bo_lo, st), "pack B_o");
+  }
+  return MACE_OK;
+}
+
 // ---------------------------------------------------------------- DPO head scratch
 struct DpoWs {
   int32_t *row_idx, *label, *seq_id;
@@ -460,8 +540,10 @@ size_t mace_workspace_bytes(mace_handle_t h, int32_t n_tokens, int32_t n_ft_toke
   Bump f(nullptr), b(nullptr), p(nullptr);
   prepare_weights(D, nullptr, f, true, false, nullptr, ws);
   plan_fwd(D, (size_t)(n_tokens - n_ft_tokens), (size_t)n_ft_tokens, n_decode, max_context, f);
+  plan_lora(D, (size_t)n_tokens, false, f);
   prepare_weights(D, nullptr, b, false, false, nullptr, ws);
   plan_bwd(D, (size_t)n_ft_tokens, b);
+  plan_lora(D, (size_t)n_ft_tokens, true, b);
   plan_dpo(D, (size_t)n_loss_rows, 1u << 16, p);
   size_t m = f.off > b.off ? f.off : b.off;
   m = m > p.off ? m : p.off;
@@ -514,9 +596,11 @@ int mace_kv_cache_gather(mace_handle_t h, const mace_kv_cache_t *cache, const in
   return MACE_OK;
 }
 
-int mace_hybrid_layer_fwd(mace_handle_t h, const mace_layer_w_t *w, const mace_batch_t *batch, mace_kv_cache_t *cache,
-                          const void *x, float *y, void *saved, void *workspace, size_t workspace_bytes, void *stream) {
+static int layer_fwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_lora_t *lora, const mace_batch_t *batch,
+                          mace_kv_cache_t *cache, const void *x, float *y, void *saved, void *workspace,
+                          size_t workspace_bytes, void *stream) {
   if (!h || !w || !x || !y) return fail(MACE_INVALID_ARG, "mace_hybrid_layer_fwd: null argument");
+  if (lora) TRY(check_lora(lora));
   if (!w->g_attn || !w->wq || !w->wk || !w->wv || !w->wo || !w->g_mlp || !w->w_gate || !w->w_up || !w->w_down) return fail(MACE_INVALID_ARG, "null weight pointer");
   BatchInfo I;
   TRY(check_batch(batch, I));
@@ -542,11 +626,18 @@ int mace_hybrid_layer_fwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
     WSplit tmp;
     prepare_weights(D, w, m, true, false, st, tmp);
     plan_fwd(D, I.Ti, I.Tf, I.Td, I.max_ctx, m);
+    if (lora) plan_lora(D, (size_t)I.T, false, m);
     if (m.off > workspace_bytes) return fail(MACE_WORKSPACE_TOO_SMALL, "forward workspace too small");
   }
   Bump wsb(workspace), svb(saved);
   TRY(prepare_weights(D, w, wsb, true, true, st, W));
   FwdWs F = plan_fwd(D, I.Ti, I.Tf, I.Td, I.max_ctx, wsb);
+  LoraWs L;
+  if (lora) {
+    L = plan_lora(D, (size_t)I.T, false, wsb);
+    prof_mark(h, st, T_MISC);
+    TRY(prepare_lora(D, lora, L, 1.0f, st));
+  }
   Saved S = plan_saved(D, I.Tf, svb);
   const int np_ft = D.bf ? 2 : 3;
   const size_t es = D.bf ? 2 : 4;
@@ -567,6 +658,22 @@ int mace_hybrid_layer_fwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
     gp_seg(p, W.hi[W_K], W.lo[W_K], D.kd, D.qd);
     gp_seg(p, W.hi[W_V], W.lo[W_V], D.kd, D.qd + D.kd);
     TRY(run_gemm(h, 0, 0, p, st, "qkv gemm"));
+  }
+  if (lora) {
+    // adapter term of the three projections: t = a [A_q; A_k; A_v]^T, qkv += (scale t) blockdiag(B_q, B_k, B_v)^T
+    GemmParams p = gp_init(D.d, D.d, D.d, 3 * LR);
+    gp_group(p, S.a, F.a_lo, L.t_qkv + (size_t)I.Ti * 3 * LR, nullptr, I.Tf, np_ft);
+    gp_group(p, F.a_i, nullptr, L.t_qkv, nullptr, I.Ti, 1);
+    gp_seg(p, L.aqkv_hi, L.aqkv_lo, 3 * LR, 0);
+    TRY(run_gemm(h, 0, 0, p, st, "lora t_qkv gemm"));
+    prof_mark(h, st, T_MISC);
+    HIP_TRY(launch_scale_split(L.t_qkv, (size_t)I.T * 3 * LR, lora->scale, L.tq_hi, L.tq_lo, st), "lora t_qkv split");
+    GemmParams p2 = gp_init(3 * LR, 3 * LR, 3 * LR, D.nqkv);
+    p2.resid_kind = 1; p2.ldr = D.nqkv;
+    gp_group(p2, L.tq_hi + (size_t)I.Ti * 3 * LR, L.tq_lo + (size_t)I.Ti * 3 * LR, F.qkv_f, F.qkv_f, I.Tf, np_ft);
+    gp_group(p2, L.tq_hi, nullptr, F.qkv_i, F.qkv_i, I.Ti, 1);
+    gp_seg(p2, L.bblk_hi, L.bblk_lo, D.nqkv, 0);
+    TRY(run_gemm(h, 0, 0, p2, st, "lora qkv gemm"));
   }
   // 3. RoPE, operand split, KV append of the inference rows
   if (I.Ti > 0) {
@@ -598,6 +705,21 @@ int mace_hybrid_layer_fwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
     gp_seg(p, W.hi[W_O], W.lo[W_O], D.d, 0);
     TRY(run_gemm(h, 0, 0, p, st, "o gemm"));
   }
+  if (lora) {
+    GemmParams p = gp_init(D.qd, D.qd, D.qd, LR);
+    gp_group(p, S.o, F.o_lo, L.t_o + (size_t)I.Ti * LR, nullptr, I.Tf, np_ft);
+    gp_group(p, F.o_i, nullptr, L.t_o, nullptr, I.Ti, 1);
+    gp_seg(p, L.ao_hi, L.ao_lo, LR, 0);
+    TRY(run_gemm(h, 0, 0, p, st, "lora t_o gemm"));
+    prof_mark(h, st, T_MISC);
+    HIP_TRY(launch_scale_split(L.t_o, (size_t)I.T * LR, lora->scale, L.to_hi, L.to_lo, st), "lora t_o split");
+    GemmParams p2 = gp_init(LR, LR, LR, D.d);
+    p2.resid_kind = 1; p2.ldr = D.d;
+    gp_group(p2, L.to_hi + (size_t)I.Ti * LR, L.to_lo + (size_t)I.Ti * LR, S.x1, S.x1, I.Tf, np_ft);
+    gp_group(p2, L.to_hi, nullptr, F.x1_i, F.x1_i, I.Ti, 1);
+    gp_seg(p2, L.bo_hi, L.bo_lo, D.d, 0);
+    TRY(run_gemm(h, 0, 0, p2, st, "lora o gemm"));
+  }
   // 6. RMSNorm (MLP), gate/up projection, SwiGLU, down projection + residual
   prof_mark(h, st, T_RMSNORM);
   HIP_TRY(launch_rmsnorm_fwd(F.x1_i, false, nullptr, w->g_mlp, D.bf, I.Ti, D.d, h->m.rms_eps, F.b_i, nullptr, nullptr, st), "rmsnorm2");
@@ -627,10 +749,26 @@ int mace_hybrid_layer_fwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
   return MACE_OK;
 }
 
-int mace_hybrid_layer_bwd(mace_handle_t h, const mace_layer_w_t *w, const mace_batch_t *batch, const void *x,
-                          const float *dy_ft, const void *saved, float *dx_ft, const mace_layer_grads_t *grads,
-                          int accumulate, void *workspace, size_t workspace_bytes, void *stream) {
-  if (!h || !w || !x || !dy_ft || !saved || !dx_ft || !grads) return fail(MACE_INVALID_ARG, "mace_hybrid_layer_bwd: null argument");
+int mace_hybrid_layer_fwd(mace_handle_t h, const mace_layer_w_t *w, const mace_batch_t *batch, mace_kv_cache_t *cache,
+                          const void *x, float *y, void *saved, void *workspace, size_t workspace_bytes, void *stream) {
+  return layer_fwd_impl(h, w, nullptr, batch, cache, x, y, saved, workspace, workspace_bytes, stream);
+}
+
+int mace_hybrid_layer_fwd_lora(mace_handle_t h, const mace_layer_w_t *w, const mace_lora_t *lora, const mace_batch_t *batch,
+                               mace_kv_cache_t *cache, const void *x, float *y, void *saved, void *workspace,
+                               size_t workspace_bytes, void *stream) {
+  if (!lora) return fail(MACE_INVALID_ARG, "lora is null");
+  return layer_fwd_impl(h, w, lora, batch, cache, x, y, saved, workspace, workspace_bytes, stream);
+}
+
+static int layer_bwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_lora_t *lora, const mace_batch_t *batch,
+                          const void *x, const float *dy_ft, const void *saved, float *dx_ft,
+                          const mace_layer_grads_t *grads, const mace_lora_grads_t *lgrads, int accumulate,
+                          void *workspace, size_t workspace_bytes, void *stream) {
+  if (!h || !w || !x || !dy_ft || !saved || !dx_ft || (!grads && !lgrads)) return fail(MACE_INVALID_ARG, "mace_hybrid_layer_bwd: null argument");
+  if (lora) TRY(check_lora(lora));
+  static const mace_layer_grads_t no_grads = {};
+  if (!grads) grads = &no_grads;
   if (!w->g_attn || !w->wq || !w->wk || !w->wv || !w->wo || !w->g_mlp || !w->w_gate || !w->w_up || !w->w_down) return fail(MACE_INVALID_ARG, "null weight pointer");
   BatchInfo I;
   TRY(check_batch(batch, I));
@@ -644,12 +782,19 @@ int mace_hybrid_layer_bwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
     WSplit tmp;
     prepare_weights(D, w, m, false, false, st, tmp);
     plan_bwd(D, I.Tf, m);
+    if (lora) plan_lora(D, (size_t)I.Tf, true, m);
     if (m.off > workspace_bytes) return fail(MACE_WORKSPACE_TOO_SMALL, "backward workspace too small");
   }
   Bump wsb(workspace), svb((void *)saved);
   WSplit W;
   TRY(prepare_weights(D, w, wsb, false, true, st, W));
   BwdWs B = plan_bwd(D, I.Tf, wsb);
+  LoraWs L;
+  if (lora) {
+    L = plan_lora(D, (size_t)I.Tf, true, wsb);
+    prof_mark(h, st, T_MISC);
+    TRY(prepare_lora(D, lora, L, lora->scale, st));     // B matrices carry the adapter scale here
+  }
   const Saved S = plan_saved(D, I.Tf, svb);
   const int Tf = I.Tf;
   const size_t es = D.bf ? 2 : 4;
@@ -708,6 +853,50 @@ int mace_hybrid_layer_bwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
     gp_seg(p, W.hi[W_O], nullptr, D.qd, 0);
     TRY(run_gemm(h, 0, 1, p, st, "dattn gemm"));
   }
+  if (lora) {
+    // output projection adapter: t = o A_o^T ; dB_o = s dx1^T t ; dt = dx1 (s B_o) ; dA_o = dt^T o ; dattn += dt A_o
+    {
+      GemmParams p = gp_init(D.qd, D.qd, D.qd, LR);
+      p.out_bf16 = 1;
+      gp_group(p, S.o, nullptr, L.to_hi, nullptr, Tf, 1);
+      gp_seg(p, L.ao_hi, nullptr, LR, 0);
+      TRY(run_gemm(h, 0, 0, p, st, "lora t_o gemm"));
+    }
+    {
+      GemmParams p = gp_init(D.d, D.d, LR, LR);
+      p.out_bf16 = 1;
+      gp_group(p, B.dx1_bf, nullptr, L.dto, nullptr, Tf, 1);
+      gp_seg(p, L.bo_hi, nullptr, LR, 0);
+      TRY(run_gemm(h, 0, 1, p, st, "lora dt_o gemm"));
+    }
+    {
+      GemmParams p = gp_init(LR, LR, D.qd, D.qd);
+      p.out_bf16 = 1; p.resid_kind = 2;
+      gp_group(p, L.dto, nullptr, B.dattn, B.dattn, Tf, 1);
+      gp_seg(p, L.ao_hi, nullptr, D.qd, 0);
+      TRY(run_gemm(h, 0, 1, p, st, "lora dattn gemm"));
+    }
+    if (lgrads->b_o) {
+      hipStream_t s2 = side_fork(h, st);
+      GemmParams p = gp_init(Tf, D.d, LR, LR);
+      gp_group(p, B.dx1_bf, nullptr, L.dbo, nullptr, D.d, 1);
+      gp_seg(p, L.to_hi, nullptr, LR, 0);
+      TRY(run_gemm(h, 1, 1, p, s2, "lora dB_o gemm"));
+      prof_mark(h, s2, T_MISC);
+      HIP_TRY(launch_extract(L.dbo, LR, 0, 0, D.d, lora->rank, lora->scale, lgrads->b_o, acc, s2), "lora dB_o");
+      if (s2 != st) prof_mark(h, s2, -1);
+    }
+    if (lgrads->a_o) {
+      hipStream_t s2 = side_fork(h, st);
+      GemmParams p = gp_init(Tf, LR, D.qd, D.qd);
+      gp_group(p, L.dto, nullptr, L.dao, nullptr, LR, 1);
+      gp_seg(p, S.o, nullptr, D.qd, 0);
+      TRY(run_gemm(h, 1, 1, p, s2, "lora dA_o gemm"));
+      prof_mark(h, s2, T_MISC);
+      HIP_TRY(launch_extract(L.dao, D.qd, 0, 0, lora->rank, D.qd, 1.0f, lgrads->a_o, acc, s2), "lora dA_o");
+      if (s2 != st) prof_mark(h, s2, -1);
+    }
+  }
   if (grads->wo) {
     GemmParams p = gp_init(Tf, D.d, D.qd, D.qd);
     p.resid_kind = acc;
@@ -736,6 +925,59 @@ int mace_hybrid_layer_bwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
       p.kseg_start[0] = 0; p.kseg_start[1] = ks[0]; p.kseg_start[2] = ks[0] + ks[1]; p.kseg_start[3] = ks[0] + ks[1] + ks[2];
       TRY(run_gemm(h, 0, 1, p, st, "da gemm"));
     }
+    if (lora) {
+      // q/k/v adapters at once through the stacked A and the block-diagonal (scaled) B
+      {
+        GemmParams p = gp_init(D.d, D.d, D.d, 3 * LR);
+        p.out_bf16 = 1;
+        gp_group(p, S.a, nullptr, L.tq_hi, nullptr, Tf, 1);
+        gp_seg(p, L.aqkv_hi, nullptr, 3 * LR, 0);
+        TRY(run_gemm(h, 0, 0, p, st, "lora t_qkv gemm"));
+      }
+      {
+        GemmParams p = gp_init(D.nqkv, D.nqkv, 3 * LR, 3 * LR);
+        p.out_bf16 = 1;
+        gp_group(p, B.dqkv, nullptr, L.dtq, nullptr, Tf, 1);
+        gp_seg(p, L.bblk_hi, nullptr, 3 * LR, 0);
+        TRY(run_gemm(h, 0, 1, p, st, "lora dt_qkv gemm"));
+      }
+      {
+        GemmParams p = gp_init(3 * LR, 3 * LR, D.d, D.d);
+        p.resid_kind = 1;
+        gp_group(p, L.dtq, nullptr, B.da, B.da, Tf, 1);
+        gp_seg(p, L.aqkv_hi, nullptr, D.d, 0);
+        TRY(run_gemm(h, 0, 1, p, st, "lora da gemm"));
+      }
+      if (lgrads->b_q || lgrads->b_k || lgrads->b_v) {
+        hipStream_t s2 = side_fork(h, st);
+        GemmParams p = gp_init(Tf, D.nqkv, 3 * LR, 3 * LR);
+        gp_group(p, B.dqkv, nullptr, L.dbblk, nullptr, D.nqkv, 1);
+        gp_seg(p, L.tq_hi, nullptr, 3 * LR, 0);
+        TRY(run_gemm(h, 1, 1, p, s2, "lora dB_qkv gemm"));
+        float *dst[3] = {lgrads->b_q, lgrads->b_k, lgrads->b_v};
+        const int r0[3] = {0, D.qd, D.qd + D.kd}, nr[3] = {D.qd, D.kd, D.kd};
+        for (int i = 0; i < 3; ++i)
+          if (dst[i]) {
+            prof_mark(h, s2, T_MISC);
+            HIP_TRY(launch_extract(L.dbblk, 3 * LR, r0[i], i * LR, nr[i], lora->rank, lora->scale, dst[i], acc, s2), "lora dB_qkv");
+          }
+        if (s2 != st) prof_mark(h, s2, -1);
+      }
+      if (lgrads->a_q || lgrads->a_k || lgrads->a_v) {
+        hipStream_t s2 = side_fork(h, st);
+        GemmParams p = gp_init(Tf, 3 * LR, D.d, D.d);
+        gp_group(p, L.dtq, nullptr, L.daqkv, nullptr, 3 * LR, 1);
+        gp_seg(p, S.a, nullptr, D.d, 0);
+        TRY(run_gemm(h, 1, 1, p, s2, "lora dA_qkv gemm"));
+        float *dst[3] = {lgrads->a_q, lgrads->a_k, lgrads->a_v};
+        for (int i = 0; i < 3; ++i)
+          if (dst[i]) {
+            prof_mark(h, s2, T_MISC);
+            HIP_TRY(launch_extract(L.daqkv, D.d, i * LR, 0, lora->rank, D.d, 1.0f, dst[i], acc, s2), "lora dA_qkv");
+          }
+        if (s2 != st) prof_mark(h, s2, -1);
+      }
+    }
     if (grads->wq || grads->wk || grads->wv) {
       GemmParams p = gp_init(Tf, D.nqkv, D.d, D.d);
       p.resid_kind = acc;
@@ -754,6 +996,21 @@ int mace_hybrid_layer_bwd(mace_handle_t h, const mace_layer_w_t *w, const mace_b
   prof_mark(h, st, -1);
   HIP_TRY(side_join(h, st), "join side stream");
   return MACE_OK;
+}
+
+int mace_hybrid_layer_bwd(mace_handle_t h, const mace_layer_w_t *w, const mace_batch_t *batch, const void *x,
+                          const float *dy_ft, const void *saved, float *dx_ft, const mace_layer_grads_t *grads,
+                          int accumulate, void *workspace, size_t workspace_bytes, void *stream) {
+  if (!grads) return fail(MACE_INVALID_ARG, "mace_hybrid_layer_bwd: null argument");
+  return layer_bwd_impl(h, w, nullptr, batch, x, dy_ft, saved, dx_ft, grads, nullptr, accumulate, workspace, workspace_bytes, stream);
+}
+
+int mace_hybrid_layer_bwd_lora(mace_handle_t h, const mace_layer_w_t *w, const mace_lora_t *lora, const mace_batch_t *batch,
+                               const void *x, const float *dy_ft, const void *saved, float *dx_ft,
+                               const mace_lora_grads_t *grads, int accumulate, void *workspace, size_t workspace_bytes,
+                               void *stream) {
+  if (!lora || !grads) return fail(MACE_INVALID_ARG, "mace_hybrid_layer_bwd_lora: null argument");
+  return layer_bwd_impl(h, w, lora, batch, x, dy_ft, saved, dx_ft, nullptr, grads, accumulate, workspace, workspace_bytes, stream);
 }
 
 int mace_dpo_logprob_loss(mace_handle_t h, const float *h_ft, const void *g_final, const void *w_lm,

@@ -40,6 +40,16 @@ hipError_t launch_fill_f32(float *dst, size_t n, float v, hipStream_t st);
 // out[i] = sum_s part[s * n + i], n % 4 == 0 (partial sums of a split-K GEMM, fixed order).
 hipError_t launch_sum_partials(const float *part, int n_part, size_t n, float *out, hipStream_t st);
 
+// ---- lora.hip ---------------------------------------------------------------------------------
+// dst[dst_rows, dst_cols] as bf16 (hi, nullable lo) = zeros with up to three source matrices
+// (fp32 or bf16, [rows, cols] row-major), multiplied by scale, placed at (r0, c0).
+hipError_t launch_lora_pack(const void *const *src, const int *rows, const int *cols, const int *r0, const int *c0, int n_src,
+                            bool src_bf16, int dst_rows, int dst_cols, float scale, bf16_t *hi, bf16_t *lo, hipStream_t st);
+// (hi, lo) = two-term bf16 form of scale * src.
+hipError_t launch_scale_split(const float *src, size_t n, float scale, bf16_t *hi, bf16_t *lo, hipStream_t st);
+// dst[rows, cols] (+)= scale * the window of src (row pitch src_ld) that starts at (r0, c0).
+hipError_t launch_extract(const float *src, int src_ld, int r0, int c0, int rows, int cols, float scale, float *dst, int accumulate, hipStream_t st);
+
 // ---- kv_cache.hip ----------------------------------------------------------------------------
 hipError_t launch_kv_append(void *cache_k, void *cache_v, bool bf16, long long num_slots, int block_size, int Hkv,
                             int hd, const void *k_new, const void *v_new, const int32_t *slot_mapping, int n,

@@ -15,8 +15,10 @@ _WNAMES = ("g1", "wq", "wk", "wv", "wo", "g2", "wg", "wu", "wd")
 
 
 class DeviceIteration:
-    def __init__(self, wl: Workload, device: str = "cuda:0", load_cache: bool = True, device_cache_seed=None):
-        """device_cache_seed: fill the cached contexts with N(0,1) values drawn on the GPU (torch
+    def __init__(self, wl: Workload, device: str = "cuda:0", load_cache: bool = True, device_cache_seed=None, lora=None):
+        """lora: adapter dict of synth.make_lora - the iteration then runs the adapter variant (base
+        model frozen, adapter gradients only).
+        device_cache_seed: fill the cached contexts with N(0,1) values drawn on the GPU (torch
         generator) instead of uploading wl.ctx_k / ctx_v - for benchmark workloads whose cache
         (tens of GB) is too large to generate on the host.  Not used by parity tests."""
         self.wl = wl
@@ -32,6 +34,10 @@ class DeviceIteration:
         self.gf = upio(wl.weights["gf"])
         self.w_struct = B.layer_weights_struct(self.w)
         self.x = upio(wl.x)
+        self.lora = None
+        if lora is not None:
+            self.lora_dev = {k: upio(lora[k]) for k in B._LORA_NAMES}
+            self.lora = B.lora_struct(self.lora_dev, lora["rank"], lora["scale"])
 
         # descriptor arrays
         self.T, self.Tp, self.Td, self.Tf = b.n_tokens, b.t_prefill, b.t_decode, b.t_ft
@@ -94,6 +100,9 @@ class DeviceIteration:
         self.dx = torch.empty((self.Tf, m.d_model), **f32)
         self.grads = {k: torch.empty(self.w[k].shape, **f32) for k in _WNAMES}
         self.g_struct = B.layer_grads_struct(self.grads)
+        if self.lora is not None:
+            self.lora_grads = {k: torch.empty(self.lora_dev[k].shape, **f32) for k in B._LORA_NAMES}
+            self.lg_struct = B.lora_grads_struct(self.lora_grads)
 
     def load_context(self, ctx_k, ctx_v):
         """Place the already-cached rows of every decode request through mace_kv_cache_append."""
@@ -114,11 +123,20 @@ class DeviceIteration:
         B.mace_kv_cache_append(self.h, self.cache, k, v, sl, int(sl.numel()))
 
     def forward(self):
+        if self.lora is not None:
+            B.mace_hybrid_layer_fwd_lora(self.h, self.w_struct, self.lora, self.batch, self.cache if self.Ti else None,
+                                         self.x, self.y, self.saved, self.ws)
+            return
         B.mace_hybrid_layer_fwd(self.h, self.w_struct, self.batch, self.cache if self.Ti else None, self.x, self.y,
                                 self.saved, self.ws)
 
     def dpo(self, backward: bool = True):
         y_ft = self.y[self.Ti:]
+        if self.lora is not None and backward:      # frozen base model: only the row gradients are needed
+            B.mace_dpo_logprob_loss(self.h, y_ft, self.gf, self.E, self.tok_ft, self.ft_off_dev, self.ft_off_host,
+                                    self.prompt_dev, self.prompt_host, self.n_pairs, self.ref_dev, self.wl.beta, self.logp,
+                                    self.loss_pair, self.loss_mean, self.clpd, self.win, self.dh, None, None, 0, self.ws)
+            return
         B.mace_dpo_logprob_loss(self.h, y_ft, self.gf, self.E, self.tok_ft, self.ft_off_dev, self.ft_off_host,
                                 self.prompt_dev, self.prompt_host, self.n_pairs, self.ref_dev, self.wl.beta, self.logp,
                                 self.loss_pair, self.loss_mean, self.clpd, self.win,
@@ -126,6 +144,10 @@ class DeviceIteration:
                                 self.dgf if backward else None, 0, self.ws)
 
     def backward(self, dy=None):
+        if self.lora is not None:
+            B.mace_hybrid_layer_bwd_lora(self.h, self.w_struct, self.lora, self.batch, self.x, self.dh if dy is None else dy,
+                                         self.saved, self.dx, self.lg_struct, 0, self.ws)
+            return
         B.mace_hybrid_layer_bwd(self.h, self.w_struct, self.batch, self.x, self.dh if dy is None else dy, self.saved,
                                 self.dx, self.g_struct, 0, self.ws)
 

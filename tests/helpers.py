@@ -4,7 +4,7 @@ import numpy as np
 from oracle import mace_oracle as O
 
 
-def run_oracle(wl, backward=True):
+def run_oracle(wl, backward=True, lora=None):
     m, b = wl.dims, wl.batch
     ck = O.new_cache(b.num_blocks, m.n_kv_heads, b.block_size, m.head_dim)
     cv = O.new_cache(b.num_blocks, m.n_kv_heads, b.block_size, m.head_dim)
@@ -12,10 +12,10 @@ def run_oracle(wl, backward=True):
         O.load_context(ck, b.decode_block_tables, b.block_size, wl.ctx_k)
         O.load_context(cv, b.decode_block_tables, b.block_size, wl.ctx_v)
     if len(b.ft_lens) == 0:       # inference-only batch: there is no DPO head to run
-        y, slots, saved = O.layer_forward(m, wl.weights, b, wl.x, ck, cv)
+        y, slots, saved = O.layer_forward(m, wl.weights, b, wl.x, ck, cv, lora)
         out = dict(y=y, slots=slots, saved=saved)
     else:
-        out = O.hybrid_iteration(m, wl.weights, b, wl.x, ck, cv, wl.ref_logp, wl.beta, backward=backward)
+        out = O.hybrid_iteration(m, wl.weights, b, wl.x, ck, cv, wl.ref_logp, wl.beta, backward=backward, lora=lora)
     out["cache_k"], out["cache_v"] = ck, cv
     return out
 

@@ -22,11 +22,12 @@ def torch_mod():
     return torch
 
 
-def check_iteration(torch, wl, label, check_grads=True):
-    """Run forward + DPO head + backward on the GPU and compare everything with the oracle."""
+def check_iteration(torch, wl, label, check_grads=True, lora=None):
+    """Run forward + DPO head + backward on the GPU and compare everything with the oracle.
+    lora: adapter dict - both sides then run the adapter variant (frozen base, adapter gradients)."""
     from paper_2510_03283_amd.harness import DeviceIteration
-    ref = run_oracle(wl, backward=check_grads)
-    it = DeviceIteration(wl)
+    ref = run_oracle(wl, backward=check_grads, lora=lora)
+    it = DeviceIteration(wl, lora=lora)
     try:
         print(f"[{label}] T={it.T} (prefill {it.Tp}, decode {it.Td}, ft {it.Tf}), loss rows {it.R}", flush=True)
         it.forward()
@@ -59,7 +60,10 @@ def check_iteration(torch, wl, label, check_grads=True):
         assert np.array_equal(it.win.cpu().numpy()[:it.n_pairs], head["win"])
         if not check_grads:
             return
-        for nm, a, b in (("dh", it.dh, ref["dy_ft"]), ("dE", it.dE, ref["grads"]["E"]), ("dgf", it.dgf, ref["grads"]["gf"])):
+        head_grads = [("dh", it.dh, ref["dy_ft"])]
+        if lora is None:
+            head_grads += [("dE", it.dE, ref["grads"]["E"]), ("dgf", it.dgf, ref["grads"]["gf"])]
+        for nm, a, b in head_grads:
             e = rel_fro_err(a.cpu().numpy(), b)
             print(f"[{label}] {nm}: {e:.2e}", flush=True)
             assert e <= TOL_GRAD, (label, nm, e)
@@ -71,8 +75,10 @@ def check_iteration(torch, wl, label, check_grads=True):
         e = rel_fro_err(it.dx.cpu().numpy(), ref["dx_ft"])
         print(f"[{label}] dx: {e:.2e}", flush=True)
         assert e <= TOL_GRAD
-        for k in it.grads:
-            e = rel_fro_err(it.grads[k].cpu().numpy(), ref["grads"][k])
+        got = it.grads if lora is None else it.lora_grads
+        assert set(got) == set(ref["grads"]) - {"E", "gf"}
+        for k in got:
+            e = rel_fro_err(got[k].cpu().numpy(), ref["grads"][k])
             print(f"[{label}] d{k}: {e:.2e}", flush=True)
             assert e <= TOL_GRAD, (label, k, e)
     finally:
