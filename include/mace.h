@@ -202,8 +202,10 @@ int mace_dpo_logprob_loss(mace_handle_t h, const float *h_ft, const void *g_fina
  * order in which mace_profile_collect reports them, and only launches of the selected classes are
  * bracketed (an event before the launch, one before whatever is launched next), which keeps the
  * cost of the events out of a timed region that needs one class only.  Launches that the
- * library puts on its internal side stream (the weight-gradient GEMMs) are timed on that stream;
- * they overlap with the main chain, so class times can add up to more than the wall time. */
+ * library puts on its internal side stream (weight-gradient and adapter GEMMs) are timed on that
+ * stream and reported as classes of their own ("gemm_tn@side", ...; selected by the bit of the
+ * plain class); they overlap with the main chain, so class times can add up to more than the
+ * wall time and a side class does not show the speed of a kernel that has the chip to itself. */
 typedef struct {
   char name[48];      /* kernel class: gemm_nt, gemm_nn, gemm_tn, attn_fwd_prefill, attn_fwd_ft, attn_decode, ... */
   int64_t launches;

@@ -39,9 +39,10 @@ struct mace_ctx {
 namespace {
 
 const char *const PROF_TAGS[] = {"gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd_prefill", "attn_fwd_ft", "attn_decode",
-                                 "attn_bwd", "rmsnorm", "rope", "swiglu", "logsoftmax", "dlogits", "misc"};
+                                 "attn_bwd", "rmsnorm", "rope", "swiglu", "logsoftmax", "dlogits", "misc",
+                                 "gemm_nt@side", "gemm_nn@side", "gemm_tn@side"};   // GEMM launches on the side stream
 enum { T_GEMM_NT, T_GEMM_NN, T_GEMM_TN, T_ATTN_PREFILL, T_ATTN_FT, T_ATTN_DECODE, T_ATTN_BWD, T_RMSNORM, T_ROPE,
-       T_SWIGLU, T_LOGSOFTMAX, T_DLOGITS, T_MISC, T_COUNT };
+       T_SWIGLU, T_LOGSOFTMAX, T_DLOGITS, T_MISC, T_SIDE0, T_COUNT = T_SIDE0 + 3 };
 constexpr size_t PROF_MAX_MARKS = 1 << 15;
 
 void prof_mark(mace_ctx *h, hipStream_t st, int tag, double flops = 0.0, double bytes = 0.0) {
@@ -151,7 +152,9 @@ int prepare_weights(const Dims &D, const mace_layer_w_t *w, Bump &ws, bool need_
 struct Saved {
   float *rstd1, *rstd2, *lse, *x1, *gu;
   bf16_t *a, *q, *k, *v, *o, *b;
+  bf16_t *tq, *to;   // adapter variant: scale * (a [A_q;A_k;A_v]^T) [Tf, 3*64] and scale * (o A_o^T) [Tf, 64]
 };
+constexpr int LR = 64;   // adapter rank as the GEMM sees it (zero-padded)
 Saved plan_saved(const Dims &D, size_t Tf, Bump &s) {
   Saved S;
   S.rstd1 = s.take<float>(Tf);
@@ -165,6 +168,8 @@ Saved plan_saved(const Dims &D, size_t Tf, Bump &s) {
   S.v = s.take<bf16_t>(Tf * D.kd);
   S.o = s.take<bf16_t>(Tf * D.qd);
   S.b = s.take<bf16_t>(Tf * D.d);
+  S.tq = s.take<bf16_t>(Tf * 3 * LR);
+  S.to = s.take<bf16_t>(Tf * LR);
   return S;
 }
 
@@ -228,7 +233,6 @@ BwdWs plan_bwd(const Dims &D, size_t Tf, Bump &w) {
 }
 
 // ---------------------------------------------------------------- adapter (LoRA) scratch
-constexpr int LR = 64;   // adapter rank as the GEMM sees it (zero-padded)
 
 struct LoraWs {
   bf16_t *aqkv_hi, *aqkv_lo;   // [3*LR, d]   rows: A_q | A_k | A_v, each padded to LR rows
@@ -511,11 +515,12 @@ int mace_profile_collect(mace_handle_t h, mace_profile_entry_t *out, int32_t max
       const ProfMark &m = h->prof_marks[prev[c]];
       float ms = 0.f;
       HIP_TRY(hipEventElapsedTime(&ms, h->prof_events[prev[c]], h->prof_events[i]), "hipEventElapsedTime");
-      out[m.tag].launches += 1;
-      out[m.tag].side_launches += c;
-      out[m.tag].ms += ms;
-      out[m.tag].flops += m.flops;
-      out[m.tag].bytes += m.bytes;
+      const int tg = c == 1 && m.tag <= T_GEMM_TN ? T_SIDE0 + m.tag : m.tag;   // side-stream GEMMs are classes of their own
+      out[tg].launches += 1;
+      out[tg].side_launches += c;
+      out[tg].ms += ms;
+      out[tg].flops += m.flops;
+      out[tg].bytes += m.bytes;
     }
     prev[c] = (long)i;
   }
@@ -649,7 +654,20 @@ static int layer_fwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
   HIP_TRY(launch_rmsnorm_fwd(x, D.bf, nullptr, w->g_attn, D.bf, I.Ti, D.d, h->m.rms_eps, F.a_i, nullptr, nullptr, st), "rmsnorm1");
   prof_mark(h, st, T_RMSNORM);
   HIP_TRY(launch_rmsnorm_fwd(xb + (size_t)I.Ti * D.d * es, D.bf, nullptr, w->g_attn, D.bf, I.Tf, D.d, h->m.rms_eps, S.a, F.a_lo, S.rstd1, st), "rmsnorm1 ft");
-  // 2. QKV projection, all rows in one launch
+  // 2. QKV projection, all rows in one launch.  Adapter variant: t = a [A_q; A_k; A_v]^T is a skinny
+  // product that runs beside the main one on the side stream; then qkv += (scale t) blockdiag(B)^T.
+  if (lora) {
+    hipStream_t s2 = side_fork(h, st);
+    GemmParams p = gp_init(D.d, D.d, D.d, 3 * LR);
+    gp_group(p, S.a, F.a_lo, L.t_qkv + (size_t)I.Ti * 3 * LR, nullptr, I.Tf, np_ft);
+    gp_group(p, F.a_i, nullptr, L.t_qkv, nullptr, I.Ti, 1);
+    gp_seg(p, L.aqkv_hi, L.aqkv_lo, 3 * LR, 0);
+    TRY(run_gemm(h, 0, 0, p, s2, "lora t_qkv gemm"));
+    prof_mark(h, s2, T_MISC);
+    HIP_TRY(launch_scale_split(L.t_qkv, (size_t)I.Ti * 3 * LR, lora->scale, L.tq_hi, nullptr, s2), "lora t_qkv split");
+    HIP_TRY(launch_scale_split(L.t_qkv + (size_t)I.Ti * 3 * LR, (size_t)I.Tf * 3 * LR, lora->scale, S.tq, L.tq_lo, s2), "lora t_qkv split ft");
+    if (s2 != st) prof_mark(h, s2, -1);
+  }
   {
     GemmParams p = gp_init(D.d, D.d, D.d, D.nqkv);
     gp_group(p, S.a, F.a_lo, F.qkv_f, nullptr, I.Tf, np_ft);
@@ -660,17 +678,10 @@ static int layer_fwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
     TRY(run_gemm(h, 0, 0, p, st, "qkv gemm"));
   }
   if (lora) {
-    // adapter term of the three projections: t = a [A_q; A_k; A_v]^T, qkv += (scale t) blockdiag(B_q, B_k, B_v)^T
-    GemmParams p = gp_init(D.d, D.d, D.d, 3 * LR);
-    gp_group(p, S.a, F.a_lo, L.t_qkv + (size_t)I.Ti * 3 * LR, nullptr, I.Tf, np_ft);
-    gp_group(p, F.a_i, nullptr, L.t_qkv, nullptr, I.Ti, 1);
-    gp_seg(p, L.aqkv_hi, L.aqkv_lo, 3 * LR, 0);
-    TRY(run_gemm(h, 0, 0, p, st, "lora t_qkv gemm"));
-    prof_mark(h, st, T_MISC);
-    HIP_TRY(launch_scale_split(L.t_qkv, (size_t)I.T * 3 * LR, lora->scale, L.tq_hi, L.tq_lo, st), "lora t_qkv split");
+    HIP_TRY(side_join(h, st), "join side stream");
     GemmParams p2 = gp_init(3 * LR, 3 * LR, 3 * LR, D.nqkv);
     p2.resid_kind = 1; p2.ldr = D.nqkv;
-    gp_group(p2, L.tq_hi + (size_t)I.Ti * 3 * LR, L.tq_lo + (size_t)I.Ti * 3 * LR, F.qkv_f, F.qkv_f, I.Tf, np_ft);
+    gp_group(p2, S.tq, L.tq_lo, F.qkv_f, F.qkv_f, I.Tf, np_ft);
     gp_group(p2, L.tq_hi, nullptr, F.qkv_i, F.qkv_i, I.Ti, 1);
     gp_seg(p2, L.bblk_hi, L.bblk_lo, D.nqkv, 0);
     TRY(run_gemm(h, 0, 0, p2, st, "lora qkv gemm"));
@@ -696,7 +707,19 @@ static int layer_fwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
   }
   prof_mark(h, st, T_ATTN_FT, 4.0 * D.hd * D.Hq * I.pairs_ft);
   HIP_TRY(launch_attn_fwd(S.q, S.k, S.v, F.q_lo, F.k_lo, F.v_lo, batch->seg_offsets + batch->n_prefill + batch->n_decode, I.Ti, batch->n_ft_seq, I.max_ft, D.Hq, D.Hkv, D.hd, S.o, F.o_lo, S.lse, st), "ft attention");
-  // 5. output projection + residual
+  // 5. output projection + residual (adapter variant: t = o A_o^T beside it, then x1 += (scale t) B_o^T)
+  if (lora) {
+    hipStream_t s2 = side_fork(h, st);
+    GemmParams p = gp_init(D.qd, D.qd, D.qd, LR);
+    gp_group(p, S.o, F.o_lo, L.t_o + (size_t)I.Ti * LR, nullptr, I.Tf, np_ft);
+    gp_group(p, F.o_i, nullptr, L.t_o, nullptr, I.Ti, 1);
+    gp_seg(p, L.ao_hi, L.ao_lo, LR, 0);
+    TRY(run_gemm(h, 0, 0, p, s2, "lora t_o gemm"));
+    prof_mark(h, s2, T_MISC);
+    HIP_TRY(launch_scale_split(L.t_o, (size_t)I.Ti * LR, lora->scale, L.to_hi, nullptr, s2), "lora t_o split");
+    HIP_TRY(launch_scale_split(L.t_o + (size_t)I.Ti * LR, (size_t)I.Tf * LR, lora->scale, S.to, L.to_lo, s2), "lora t_o split ft");
+    if (s2 != st) prof_mark(h, s2, -1);
+  }
   {
     GemmParams p = gp_init(D.qd, D.qd, D.qd, D.d);
     p.resid_kind = resid_x; p.ldr = D.d;
@@ -706,16 +729,10 @@ static int layer_fwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
     TRY(run_gemm(h, 0, 0, p, st, "o gemm"));
   }
   if (lora) {
-    GemmParams p = gp_init(D.qd, D.qd, D.qd, LR);
-    gp_group(p, S.o, F.o_lo, L.t_o + (size_t)I.Ti * LR, nullptr, I.Tf, np_ft);
-    gp_group(p, F.o_i, nullptr, L.t_o, nullptr, I.Ti, 1);
-    gp_seg(p, L.ao_hi, L.ao_lo, LR, 0);
-    TRY(run_gemm(h, 0, 0, p, st, "lora t_o gemm"));
-    prof_mark(h, st, T_MISC);
-    HIP_TRY(launch_scale_split(L.t_o, (size_t)I.T * LR, lora->scale, L.to_hi, L.to_lo, st), "lora t_o split");
+    HIP_TRY(side_join(h, st), "join side stream");
     GemmParams p2 = gp_init(LR, LR, LR, D.d);
     p2.resid_kind = 1; p2.ldr = D.d;
-    gp_group(p2, L.to_hi + (size_t)I.Ti * LR, L.to_lo + (size_t)I.Ti * LR, S.x1, S.x1, I.Tf, np_ft);
+    gp_group(p2, S.to, L.to_lo, S.x1, S.x1, I.Tf, np_ft);
     gp_group(p2, L.to_hi, nullptr, F.x1_i, F.x1_i, I.Ti, 1);
     gp_seg(p2, L.bo_hi, L.bo_lo, D.d, 0);
     TRY(run_gemm(h, 0, 0, p2, st, "lora o gemm"));
@@ -845,7 +862,17 @@ static int layer_bwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
   HIP_TRY(launch_rmsnorm_bwd(B.db, S.x1, false, nullptr, w->g_mlp, D.bf, S.rstd2, dy_ft, Tf, D.d, B.dx1, B.dx1_bf, B.dg_part, n_part, st), "rmsnorm2 bwd");
   if (grads->g_mlp) { prof_mark(h, st, T_MISC); HIP_TRY(launch_colsum(B.dg_part, n_part, D.d, grads->g_mlp, acc, st), "dg2");
   }
-  // attention output projection
+  // attention output projection.  Adapter variant: dt = dx1 (s B_o) is a skinny product that runs
+  // beside the main one; then dattn += dt A_o ; dB_o = dx1^T (s t) with the saved s t ; dA_o = dt^T o.
+  if (lora) {
+    hipStream_t s2 = side_fork(h, st);
+    GemmParams p = gp_init(D.d, D.d, LR, LR);
+    p.out_bf16 = 1;
+    gp_group(p, B.dx1_bf, nullptr, L.dto, nullptr, Tf, 1);
+    gp_seg(p, L.bo_hi, nullptr, LR, 0);
+    TRY(run_gemm(h, 0, 1, p, s2, "lora dt_o gemm"));
+    if (s2 != st) prof_mark(h, s2, -1);
+  }
   {
     GemmParams p = gp_init(D.d, D.d, D.qd, D.qd);
     p.out_bf16 = 1;
@@ -853,22 +880,15 @@ static int layer_bwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
     gp_seg(p, W.hi[W_O], nullptr, D.qd, 0);
     TRY(run_gemm(h, 0, 1, p, st, "dattn gemm"));
   }
+  if (grads->wo) {
+    GemmParams p = gp_init(Tf, D.d, D.qd, D.qd);
+    p.resid_kind = acc;
+    gp_group(p, B.dx1_bf, nullptr, grads->wo, grads->wo, D.d, 1);
+    gp_seg(p, S.o, nullptr, D.qd, 0);
+    TRY(run_gemm_side(h, 1, 1, p, st, "dWo gemm"));
+  }
   if (lora) {
-    // output projection adapter: t = o A_o^T ; dB_o = s dx1^T t ; dt = dx1 (s B_o) ; dA_o = dt^T o ; dattn += dt A_o
-    {
-      GemmParams p = gp_init(D.qd, D.qd, D.qd, LR);
-      p.out_bf16 = 1;
-      gp_group(p, S.o, nullptr, L.to_hi, nullptr, Tf, 1);
-      gp_seg(p, L.ao_hi, nullptr, LR, 0);
-      TRY(run_gemm(h, 0, 0, p, st, "lora t_o gemm"));
-    }
-    {
-      GemmParams p = gp_init(D.d, D.d, LR, LR);
-      p.out_bf16 = 1;
-      gp_group(p, B.dx1_bf, nullptr, L.dto, nullptr, Tf, 1);
-      gp_seg(p, L.bo_hi, nullptr, LR, 0);
-      TRY(run_gemm(h, 0, 1, p, st, "lora dt_o gemm"));
-    }
+    HIP_TRY(side_join(h, st), "join side stream");
     {
       GemmParams p = gp_init(LR, LR, D.qd, D.qd);
       p.out_bf16 = 1; p.resid_kind = 2;
@@ -880,10 +900,10 @@ static int layer_bwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
       hipStream_t s2 = side_fork(h, st);
       GemmParams p = gp_init(Tf, D.d, LR, LR);
       gp_group(p, B.dx1_bf, nullptr, L.dbo, nullptr, D.d, 1);
-      gp_seg(p, L.to_hi, nullptr, LR, 0);
+      gp_seg(p, S.to, nullptr, LR, 0);
       TRY(run_gemm(h, 1, 1, p, s2, "lora dB_o gemm"));
       prof_mark(h, s2, T_MISC);
-      HIP_TRY(launch_extract(L.dbo, LR, 0, 0, D.d, lora->rank, lora->scale, lgrads->b_o, acc, s2), "lora dB_o");
+      HIP_TRY(launch_extract(L.dbo, LR, 0, 0, D.d, lora->rank, 1.0f, lgrads->b_o, acc, s2), "lora dB_o");
       if (s2 != st) prof_mark(h, s2, -1);
     }
     if (lgrads->a_o) {
@@ -897,13 +917,6 @@ static int layer_bwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
       if (s2 != st) prof_mark(h, s2, -1);
     }
   }
-  if (grads->wo) {
-    GemmParams p = gp_init(Tf, D.d, D.qd, D.qd);
-    p.resid_kind = acc;
-    gp_group(p, B.dx1_bf, nullptr, grads->wo, grads->wo, D.d, 1);
-    gp_seg(p, S.o, nullptr, D.qd, 0);
-    TRY(run_gemm_side(h, 1, 1, p, st, "dWo gemm"));
-  }
   // attention backward, RoPE backward
   prof_mark(h, st, T_ATTN_BWD, 10.0 * D.hd * D.Hq * I.pairs_ft);
   HIP_TRY(launch_attn_bwd(S.q, S.k, S.v, S.o, B.dattn, S.lse, batch->seg_offsets + batch->n_prefill + batch->n_decode, I.Ti, batch->n_ft_seq, I.max_ft, Tf,
@@ -915,6 +928,16 @@ static int layer_bwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
     const bf16_t *as[3] = {B.dqkv, B.dqkv + D.qd, B.dqkv + D.qd + D.kd};
     const int ks[3] = {D.qd, D.kd, D.kd};
     const int wi[3] = {W_Q, W_K, W_V};
+    if (lora) {
+      // q/k/v adapters at once through the stacked A and the block-diagonal (scaled) B: dt beside the main product
+      hipStream_t s2 = side_fork(h, st);
+      GemmParams p = gp_init(D.nqkv, D.nqkv, 3 * LR, 3 * LR);
+      p.out_bf16 = 1;
+      gp_group(p, B.dqkv, nullptr, L.dtq, nullptr, Tf, 1);
+      gp_seg(p, L.bblk_hi, nullptr, 3 * LR, 0);
+      TRY(run_gemm(h, 0, 1, p, s2, "lora dt_qkv gemm"));
+      if (s2 != st) prof_mark(h, s2, -1);
+    }
     {
       // one product over the stacked reduction [dQ | dK | dV] x [Wq ; Wk ; Wv]
       GemmParams p = gp_init(D.nqkv, D.nqkv, D.d, D.d);
@@ -926,21 +949,7 @@ static int layer_bwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
       TRY(run_gemm(h, 0, 1, p, st, "da gemm"));
     }
     if (lora) {
-      // q/k/v adapters at once through the stacked A and the block-diagonal (scaled) B
-      {
-        GemmParams p = gp_init(D.d, D.d, D.d, 3 * LR);
-        p.out_bf16 = 1;
-        gp_group(p, S.a, nullptr, L.tq_hi, nullptr, Tf, 1);
-        gp_seg(p, L.aqkv_hi, nullptr, 3 * LR, 0);
-        TRY(run_gemm(h, 0, 0, p, st, "lora t_qkv gemm"));
-      }
-      {
-        GemmParams p = gp_init(D.nqkv, D.nqkv, 3 * LR, 3 * LR);
-        p.out_bf16 = 1;
-        gp_group(p, B.dqkv, nullptr, L.dtq, nullptr, Tf, 1);
-        gp_seg(p, L.bblk_hi, nullptr, 3 * LR, 0);
-        TRY(run_gemm(h, 0, 1, p, st, "lora dt_qkv gemm"));
-      }
+      HIP_TRY(side_join(h, st), "join side stream");
       {
         GemmParams p = gp_init(3 * LR, 3 * LR, D.d, D.d);
         p.resid_kind = 1;
@@ -952,14 +961,14 @@ static int layer_bwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
         hipStream_t s2 = side_fork(h, st);
         GemmParams p = gp_init(Tf, D.nqkv, 3 * LR, 3 * LR);
         gp_group(p, B.dqkv, nullptr, L.dbblk, nullptr, D.nqkv, 1);
-        gp_seg(p, L.tq_hi, nullptr, 3 * LR, 0);
+        gp_seg(p, S.tq, nullptr, 3 * LR, 0);
         TRY(run_gemm(h, 1, 1, p, s2, "lora dB_qkv gemm"));
         float *dst[3] = {lgrads->b_q, lgrads->b_k, lgrads->b_v};
         const int r0[3] = {0, D.qd, D.qd + D.kd}, nr[3] = {D.qd, D.kd, D.kd};
         for (int i = 0; i < 3; ++i)
           if (dst[i]) {
             prof_mark(h, s2, T_MISC);
-            HIP_TRY(launch_extract(L.dbblk, 3 * LR, r0[i], i * LR, nr[i], lora->rank, lora->scale, dst[i], acc, s2), "lora dB_qkv");
+            HIP_TRY(launch_extract(L.dbblk, 3 * LR, r0[i], i * LR, nr[i], lora->rank, 1.0f, dst[i], acc, s2), "lora dB_qkv");
           }
         if (s2 != st) prof_mark(h, s2, -1);
       }
