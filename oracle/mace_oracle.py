@@ -23,7 +23,9 @@ closed forms of the DPO loss, uniform-logit closed form of the LM head, central 
 differences for every gradient, batch-composition invariance, cache round trips; for the
 adapter path: zero B == base model, equality with the merged weight W + scale*B*A in the forward
 and in dx, dA = scale*B^T dW and dB = scale*dW A^T against the full-weight gradient, and
-central finite differences on adapter entries.  The paper
+central finite differences on adapter entries; for the pruning statistics: a one-key context
+(the head norm is the norm of that value row), the running mean against the arithmetic mean,
+hand-worked capacity splits and their invariants.  The paper
 prints no worked numerical example for this path, so absolute values of the benchmark
 configurations are pinned by these invariants only.
 """
@@ -225,7 +227,7 @@ def mlp_block(dims, W, x, attn, lora=None):
     return y, dict(x1=x1, b=b, r2=r2, G=G, U=U, Hm=Hm)
 
 
-def layer_forward(dims, W, batch, x, cache_k, cache_v, lora=None):
+def layer_forward(dims, W, batch, x, cache_k, cache_v, lora=None, extras=None):
     """One hybrid iteration of the layer, request by request.
 
     batch: object with prefill_lens, decode_ctx, ft_lens, seg_offsets, positions, block_size,
@@ -234,6 +236,8 @@ def layer_forward(dims, W, batch, x, cache_k, cache_v, lora=None):
     and the values of the prefill and decode rows.
     lora (optional): adapter on the attention projections; every row of the iteration sees the
     same model, base plus adapter.
+    extras (optional dict): receives "head_norms" [n_decode, Hq], the L2 norm of every head's
+    attention output vector of each decode row (the signal of the cache-pruning policy, Section 4.3).
     Returns y[T, d], the slot mapping of the inference rows (int64), and per ft sequence the
     intermediates the backward pass needs."""
     x = np.asarray(x, F64)
@@ -266,6 +270,8 @@ def layer_forward(dims, W, batch, x, cache_k, cache_v, lora=None):
         K, _ = kv_gather(cache_k, batch.decode_block_tables[j], n + 1)
         V, _ = kv_gather(cache_v, batch.decode_block_tables[j], n + 1)
         o = decode_attention(q[0], np.asarray(K, F64), np.asarray(V, F64))
+        if extras is not None:
+            extras.setdefault("head_norms", []).append(np.sqrt(np.sum(o * o, axis=-1)))
         y[t:t + 1], _ = mlp_block(dims, W, x[t:t + 1], o.reshape(1, -1), lora)
     # fine-tune sequences: causal attention, nothing cached, intermediates kept
     saved = []
@@ -278,6 +284,8 @@ def layer_forward(dims, W, batch, x, cache_k, cache_v, lora=None):
         sv.update(x=x[o0:o1], a=a, r1=r1, q=q, k=k, v=v, o=o, lse=lse, P=P, pos=pos)
         saved.append(sv)
     slots_cat = np.concatenate(slots_all) if slots_all else np.zeros(0, np.int64)
+    if extras is not None:
+        extras["head_norms"] = np.array(extras.get("head_norms", [])).reshape(nd, dims.n_q_heads)
     return y, slots_cat, saved
 
 
@@ -451,13 +459,49 @@ def layer_backward_lora(dims, W, lora, saved, dy_list):
     return dxs, grads
 
 
+# --------------------------------------------------------------------------- cache-pruning statistics
+
+def rolling_mean_update(abar, norms, t_count):
+    """Running mean of the head norms (Section 4.3): after the update abar is the mean of the
+    t_count norms seen so far, abar <- abar + (norm - abar) / t_count.  abar, norms [n, H];
+    t_count [n] = number of decode iterations of each request including this one."""
+    abar, norms = np.asarray(abar, F64), np.asarray(norms, F64)
+    return abar + (norms - abar) / np.asarray(t_count, F64)[:, None]
+
+
+def head_budget(abar, c_total):
+    """Per-head cache capacity (Section 4.3): w_h = abar_h / sum_j abar_j, C_h = floor(w_h C_total),
+    and the capacity the floors leave over goes, one unit each, to the heads with the largest
+    weights (ties: the lower head index first).  Returns int64 [H] with sum == c_total."""
+    abar = np.asarray(abar, F64)
+    w = abar / np.sum(abar)
+    c = np.floor(w * F64(c_total)).astype(np.int64)
+    left = int(c_total) - int(c.sum())
+    order = sorted(range(len(w)), key=lambda h: (-w[h], h))
+    for h in order[:left]:
+        c[h] += 1
+    return c
+
+
+def prune_flags(norms, t_now, t_last_used, window, tau):
+    """Prune predicate of Section 4.3 per (request, head): t - t_last_used > W  or  norm < tau.
+    Reading: t_last_used is the last iteration at which that head's norm reached tau; it is
+    returned updated (t_now where norm >= tau).  t_now [n], t_last_used [n, H] integers."""
+    norms = np.asarray(norms, F64)
+    t_now = np.asarray(t_now, np.int64)[:, None]
+    last = np.asarray(t_last_used, np.int64)
+    low = norms < tau
+    flags = ((t_now - last) > window) | low
+    return flags, np.where(low, last, t_now)
+
+
 # --------------------------------------------------------------------------- whole iteration
 
-def hybrid_iteration(dims, W, batch, x, cache_k, cache_v, ref_logp, beta, backward=True, lora=None):
+def hybrid_iteration(dims, W, batch, x, cache_k, cache_v, ref_logp, beta, backward=True, lora=None, extras=None):
     """Forward of all rows, DPO head over the ft sequences, and the backward pass of the ft
     sequences.  Returns a dict with y, slots, the head outputs, and the gradients (with `lora`:
     the adapter gradients only, the base model being frozen)."""
-    y, slots, saved = layer_forward(dims, W, batch, x, cache_k, cache_v, lora)
+    y, slots, saved = layer_forward(dims, W, batch, x, cache_k, cache_v, lora, extras)
     seg = np.asarray(batch.seg_offsets, dtype=np.int64)
     base = len(batch.prefill_lens) + len(batch.decode_ctx)
     y_ft = [y[seg[base + s]:seg[base + s + 1]] for s in range(len(batch.ft_lens))]
