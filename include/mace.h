@@ -85,6 +85,9 @@ typedef struct {
   const int32_t *context_lens_host;/* host   [n_decode] tokens already cached (the new token is not counted) */
   const int32_t *context_lens;     /* device copy of the same array */
   int32_t max_blocks_per_req;
+  float *decode_head_norms;        /* optional OUTPUT, device fp32 [n_decode, n_q_heads]: L2 norm of every head's attention
+                                      output vector of each decode row (before the output projection) - the signal of the
+                                      norm-based cache pruning of Section 4.3; NULL = not wanted */
 } mace_batch_t;
 
 /* Create / destroy a handle.  The handle owns a few KB of device tables (rotary frequencies). */
@@ -191,6 +194,23 @@ int mace_dpo_logprob_loss(mace_handle_t h, const float *h_ft, const void *g_fina
                           float *clpd_out, int32_t *win_out, float *dh_ft, float *dw_lm,
                           float *dg_final, int accumulate, void *workspace, size_t workspace_bytes,
                           void *stream);
+
+/* Cache-pruning statistics of Section 4.3 ("Decode KV cache pruning").
+ * mace_head_norm_stats (device, elementwise over n requests x n_heads heads), given the norms of
+ * this iteration (decode_head_norms of the forward):
+ *   abar[r,h]  <-  abar[r,h] + (norm[r,h] - abar[r,h]) / t_count[r]     running mean over the t_count[r] decode
+ *                                                                       iterations request r has had, this one included
+ *   prune[r,h]  =  (t_count[r] - last_used[r,h] > window)  or  (norm[r,h] < tau)
+ *   last_used[r,h]  <-  t_count[r] where norm[r,h] >= tau                (reading: "last used" = last iteration at
+ *                                                                       which the head's norm reached tau)
+ * abar fp32 in/out, t_count int32, last_used int32 in/out and prune int32 out (0/1) are device
+ * arrays; last_used and prune may both be NULL (running mean only).
+ * mace_kv_head_budget (host, pure): w_h = abar_h / sum_j abar_j, C_h = floor(w_h * c_total) in
+ * double precision, and what the floors leave over goes one unit each to the heads of largest w_h
+ * (ties: lower index first); sum_h c_out[h] == c_total.  abar must be positive and finite. */
+int mace_head_norm_stats(mace_handle_t h, const float *norms, const int32_t *t_count, int32_t n, int32_t n_heads,
+                         float *abar, int32_t *last_used, int32_t window, float tau, int32_t *prune, void *stream);
+int mace_kv_head_budget(const double *abar, int32_t n_heads, int64_t c_total, int64_t *c_out);
 
 /* Instrumentation for benchmarks (not part of the paper's method).  When enabled, every kernel
  * launch of the three iteration calls is preceded by a HIP event recorded on the call's stream

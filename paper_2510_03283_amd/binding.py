@@ -19,7 +19,7 @@ EXPORTS = [
     "mace_create", "mace_destroy", "mace_last_error", "mace_fwd_saved_bytes", "mace_workspace_bytes",
     "mace_kv_slot_mapping", "mace_kv_cache_append", "mace_kv_cache_gather", "mace_hybrid_layer_fwd",
     "mace_hybrid_layer_bwd", "mace_hybrid_layer_fwd_lora", "mace_hybrid_layer_bwd_lora", "mace_dpo_logprob_loss",
-    "mace_profile_enable", "mace_profile_collect",
+    "mace_head_norm_stats", "mace_kv_head_budget", "mace_profile_enable", "mace_profile_collect",
 ]
 
 
@@ -60,7 +60,7 @@ class BatchT(C.Structure):
     _fields_ = [("n_prefill", C.c_int32), ("n_decode", C.c_int32), ("n_ft_seq", C.c_int32), ("n_tokens", C.c_int32),
                 ("seg_offsets_host", C.c_void_p), ("seg_offsets", C.c_void_p), ("positions", C.c_void_p),
                 ("slot_mapping", C.c_void_p), ("block_tables", C.c_void_p), ("context_lens_host", C.c_void_p),
-                ("context_lens", C.c_void_p), ("max_blocks_per_req", C.c_int32)]
+                ("context_lens", C.c_void_p), ("max_blocks_per_req", C.c_int32), ("decode_head_norms", C.c_void_p)]
 
 
 class ProfileEntryT(C.Structure):
@@ -107,6 +107,10 @@ def load():
     lib.mace_hybrid_layer_bwd_lora.restype = C.c_int
     lib.mace_dpo_logprob_loss.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, f32, vp, vp, vp, vp, vp, vp, vp, vp, C.c_int, vp, sz, vp]
     lib.mace_dpo_logprob_loss.restype = C.c_int
+    lib.mace_head_norm_stats.argtypes = [vp, vp, vp, i32, i32, vp, vp, i32, f32, vp, vp]
+    lib.mace_head_norm_stats.restype = C.c_int
+    lib.mace_kv_head_budget.argtypes = [vp, i32, i64, vp]
+    lib.mace_kv_head_budget.restype = C.c_int
     lib.mace_profile_enable.argtypes = [vp, C.c_int]
     lib.mace_profile_enable.restype = C.c_int
     lib.mace_profile_collect.argtypes = [vp, C.POINTER(ProfileEntryT), i32, C.POINTER(i32)]
@@ -192,13 +196,13 @@ class BatchDesc:
     """Owns the host arrays a mace_batch_t points to, next to the struct itself."""
 
     def __init__(self, n_prefill, n_decode, n_ft_seq, n_tokens, seg_offsets_host, seg_offsets, positions,
-                 slot_mapping, block_tables, context_lens_host, context_lens, max_blocks_per_req):
+                 slot_mapping, block_tables, context_lens_host, context_lens, max_blocks_per_req, decode_head_norms=None):
         self._seg, segp = _host_i32(seg_offsets_host)
         self._ctx, ctxp = _host_i32(context_lens_host)
-        self._keep = (seg_offsets, positions, slot_mapping, block_tables, context_lens)
+        self._keep = (seg_offsets, positions, slot_mapping, block_tables, context_lens, decode_head_norms)
         self.struct = BatchT(n_prefill, n_decode, n_ft_seq, n_tokens, segp, _dev(seg_offsets), _dev(positions),
                              _dev(slot_mapping), _dev(block_tables), ctxp if n_decode else None,
-                             _dev(context_lens), max_blocks_per_req)
+                             _dev(context_lens), max_blocks_per_req, _dev(decode_head_norms))
 
 
 def mace_hybrid_layer_fwd(h, w: LayerWT, batch: BatchDesc, cache: Optional[KvCacheT], x, y, saved, workspace, stream=None):
@@ -247,6 +251,21 @@ def mace_dpo_logprob_loss(h, h_ft, g_final, w_lm, token_ids, ft_seq_offsets, ft_
                                         _dev(loss_per_pair), _dev(loss_mean), _dev(clpd_out), _dev(win_out), _dev(dh_ft),
                                         _dev(dw_lm), _dev(dg_final), int(accumulate), _dev(workspace),
                                         workspace.numel() * workspace.element_size(), _stream(stream)), "mace_dpo_logprob_loss")
+
+
+def mace_head_norm_stats(h, norms, t_count, abar, last_used=None, window=0, tau=0.0, prune=None, stream=None):
+    n, H = norms.shape
+    _check(load().mace_head_norm_stats(h, _dev(norms), _dev(t_count), n, H, _dev(abar), _dev(last_used), int(window), float(tau),
+                                       _dev(prune), _stream(stream)), "mace_head_norm_stats")
+
+
+def mace_kv_head_budget(abar, c_total: int):
+    """Host-side capacity split; abar: sequence of positive floats.  Returns a numpy int64 array."""
+    import numpy as np
+    a = np.ascontiguousarray(abar, dtype=np.float64)
+    out = np.empty(len(a), dtype=np.int64)
+    _check(load().mace_kv_head_budget(C.c_void_p(a.ctypes.data), len(a), int(c_total), C.c_void_p(out.ctypes.data)), "mace_kv_head_budget")
+    return out
 
 
 PROFILE_CLASSES = ["gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd_prefill", "attn_fwd_ft", "attn_decode", "attn_bwd",

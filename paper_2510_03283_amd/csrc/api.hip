@@ -2,6 +2,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
+#include <algorithm>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -555,6 +556,38 @@ size_t mace_workspace_bytes(mace_handle_t h, int32_t n_tokens, int32_t n_ft_toke
   return align_up(m, 256) + 256;
 }
 
+int mace_head_norm_stats(mace_handle_t h, const float *norms, const int32_t *t_count, int32_t n, int32_t n_heads, float *abar,
+                         int32_t *last_used, int32_t window, float tau, int32_t *prune, void *stream) {
+  if (!h || !norms || !t_count || !abar || n < 0 || n_heads <= 0) return fail(MACE_INVALID_ARG, "mace_head_norm_stats: bad argument");
+  if ((last_used == nullptr) != (prune == nullptr)) return fail(MACE_INVALID_ARG, "last_used and prune go together");
+  if ((long long)n * n_heads > (1ll << 30)) return fail(MACE_BAD_SHAPE, "too many (request, head) pairs");
+  if (prune && (window < 0 || !(tau >= 0.f))) return fail(MACE_INVALID_ARG, "window / tau");
+  HIP_TRY(launch_head_norm_stats(norms, t_count, n, n_heads, abar, last_used, window, tau, prune, (hipStream_t)stream), "head norm stats");
+  return MACE_OK;
+}
+
+int mace_kv_head_budget(const double *abar, int32_t n_heads, int64_t c_total, int64_t *c_out) {
+  if (!abar || !c_out || n_heads <= 0 || c_total < 0) return fail(MACE_INVALID_ARG, "mace_kv_head_budget: bad argument");
+  double sum = 0.0;
+  for (int i = 0; i < n_heads; ++i) {
+    if (!(abar[i] > 0.0) || !std::isfinite(abar[i])) return fail(MACE_INVALID_ARG, "head norms must be positive and finite");
+    sum += abar[i];
+  }
+  std::vector<double> w(n_heads);
+  int64_t used = 0;
+  for (int i = 0; i < n_heads; ++i) {
+    w[i] = abar[i] / sum;
+    c_out[i] = (int64_t)std::floor(w[i] * (double)c_total);
+    used += c_out[i];
+  }
+  std::vector<int> order(n_heads);
+  for (int i = 0; i < n_heads; ++i) order[i] = i;
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return w[a] > w[b]; });
+  int64_t left = c_total - used;
+  for (int i = 0; i < n_heads && left > 0; ++i, --left) c_out[order[i]] += 1;
+  return MACE_OK;
+}
+
 int mace_kv_slot_mapping(const int32_t *block_table, int32_t table_len, int32_t block_size, int32_t start_pos, int32_t n,
                          int32_t *slots_out) {
   if (!block_table || !slots_out || table_len < 0 || start_pos < 0 || n < 0) return fail(MACE_INVALID_ARG, "mace_kv_slot_mapping: bad argument");
@@ -703,7 +736,7 @@ static int layer_fwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
     for (int i = 0; i < I.Td; ++i) kv_tokens += (double)batch->context_lens_host[i] + 1.0;
     prof_mark(h, st, T_ATTN_DECODE, 4.0 * kv_tokens * D.Hq * D.hd, kv_tokens * 2.0 * D.Hkv * D.hd * (D.bf ? 2.0 : 4.0));
     HIP_TRY(launch_attn_decode(F.q_i + (size_t)I.Tp * D.qd, cache->k, cache->v, D.bf, cache->num_blocks, cache->block_size, batch->block_tables, batch->max_blocks_per_req,
-                               batch->context_lens, I.Td, I.max_ctx, D.Hq, D.Hkv, D.hd, F.dec_partial, F.o_i + (size_t)I.Tp * D.qd, st), "decode attention");
+                               batch->context_lens, I.Td, I.max_ctx, D.Hq, D.Hkv, D.hd, F.dec_partial, F.o_i + (size_t)I.Tp * D.qd, batch->decode_head_norms, st), "decode attention");
   }
   prof_mark(h, st, T_ATTN_FT, 4.0 * D.hd * D.Hq * I.pairs_ft);
   HIP_TRY(launch_attn_fwd(S.q, S.k, S.v, F.q_lo, F.k_lo, F.v_lo, batch->seg_offsets + batch->n_prefill + batch->n_decode, I.Ti, batch->n_ft_seq, I.max_ft, D.Hq, D.Hkv, D.hd, S.o, F.o_lo, S.lse, st), "ft attention");

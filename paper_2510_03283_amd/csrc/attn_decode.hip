@@ -205,7 +205,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(const bf16_t *__restri
 template <int HD>
 __global__ __launch_bounds__(HD) void attn_decode_combine_kernel(const float *__restrict__ partial,
                                                                  const int32_t *__restrict__ ctx_lens, int Hq, int nsplit,
-                                                                 bf16_t *__restrict__ out) {
+                                                                 bf16_t *__restrict__ out, float *__restrict__ norms) {
   const int req = blockIdx.x, h = blockIdx.y, e = threadIdx.x;
   const int ns = min(nsplit, (ctx_lens[req] + 1 + CHUNK - 1) / CHUNK);
   const float *src = partial + ((size_t)req * Hq + h) * nsplit * (HD + 2);
@@ -217,7 +217,18 @@ __global__ __launch_bounds__(HD) void attn_decode_combine_kernel(const float *__
     lo += src[s * (HD + 2) + HD + 1] * a;
     ao += src[s * (HD + 2) + e] * a;
   }
-  out[((size_t)req * Hq + h) * HD + e] = f2bf(lo > 0.f ? ao / lo : 0.f);
+  const float v = lo > 0.f ? ao / lo : 0.f;
+  out[((size_t)req * Hq + h) * HD + e] = f2bf(v);
+  if (norms) {                                   // L2 norm of the head's output vector (fp32 values)
+    __shared__ float red[2];
+    float s = wave_sum(v * v);
+    if constexpr (HD > 64) {
+      if ((e & 63) == 0) red[e >> 6] = s;
+      __syncthreads();
+      s = red[0] + red[1];
+    }
+    if (e == 0) norms[(size_t)req * Hq + h] = sqrtf(s);
+  }
 }
 
 template <int HD, int GRP, bool CBF>
@@ -253,7 +264,7 @@ size_t decode_partial_floats(int n_decode, int Hq, int hd, int max_context) {
 hipError_t launch_attn_decode(const bf16_t *q, const void *cache_k, const void *cache_v, bool cache_bf16,
                               long long num_blocks, int block_size, const int32_t *block_tables, int max_blocks_per_req,
                               const int32_t *ctx_lens, int n_decode, int max_context, int Hq, int Hkv, int hd,
-                              float *partial, bf16_t *out, hipStream_t st) {
+                              float *partial, bf16_t *out, float *norms, hipStream_t st) {
   if (n_decode <= 0) return hipSuccess;
   if (n_decode > 65535 || Hkv > 65535 || Hq > 65535) return hipErrorInvalidValue;
   int bshift = 0;
@@ -269,7 +280,7 @@ hipError_t launch_attn_decode(const bf16_t *q, const void *cache_k, const void *
   if (!ok) return hipErrorInvalidValue;
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (hd == 64) hipLaunchKernelGGL((attn_decode_combine_kernel<64>), dim3(n_decode, Hq), dim3(64), 0, st, partial, ctx_lens, Hq, nsplit, out);
-  else hipLaunchKernelGGL((attn_decode_combine_kernel<128>), dim3(n_decode, Hq), dim3(128), 0, st, partial, ctx_lens, Hq, nsplit, out);
+  if (hd == 64) hipLaunchKernelGGL((attn_decode_combine_kernel<64>), dim3(n_decode, Hq), dim3(64), 0, st, partial, ctx_lens, Hq, nsplit, out, norms);
+  else hipLaunchKernelGGL((attn_decode_combine_kernel<128>), dim3(n_decode, Hq), dim3(128), 0, st, partial, ctx_lens, Hq, nsplit, out, norms);
   return hipGetLastError();
 }

@@ -345,6 +345,30 @@ hipError_t launch_split_f32(const float *src, size_t n, bf16_t *hi, bf16_t *lo, 
   return hipGetLastError();
 }
 
+namespace {
+__global__ __launch_bounds__(256) void head_norm_stats_kernel(const float *__restrict__ norms, const int32_t *__restrict__ t_count,
+                                                              int n, int H, float *__restrict__ abar, int32_t *__restrict__ last_used,
+                                                              int window, float tau, int32_t *__restrict__ prune) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= n * H) return;
+  const int t = t_count[i / H];
+  const float v = norms[i], a = abar[i];
+  abar[i] = a + (v - a) / (float)t;
+  if (prune) {
+    const bool low = v < tau;
+    prune[i] = (t - last_used[i] > window || low) ? 1 : 0;
+    if (!low) last_used[i] = t;
+  }
+}
+}  // namespace
+
+hipError_t launch_head_norm_stats(const float *norms, const int32_t *t_count, int n, int H, float *abar, int32_t *last_used,
+                                  int window, float tau, int32_t *prune, hipStream_t st) {
+  if (n <= 0 || H <= 0) return hipSuccess;
+  hipLaunchKernelGGL(head_norm_stats_kernel, dim3((unsigned)cdiv(n * H, 256)), dim3(256), 0, st, norms, t_count, n, H, abar, last_used, window, tau, prune);
+  return hipGetLastError();
+}
+
 hipError_t launch_fill_f32(float *dst, size_t n, float v, hipStream_t st) {
   if (n == 0) return hipSuccess;
   const unsigned blocks = (unsigned)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);

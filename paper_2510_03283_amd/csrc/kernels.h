@@ -69,12 +69,15 @@ hipError_t launch_attn_fwd(const bf16_t *q_hi, const bf16_t *k_hi, const bf16_t 
 // ---- attn_decode.hip -------------------------------------------------------------------------
 // One query row per request against its paged context of ctx_len[r]+1 tokens.  q bf16
 // [n_decode, Hq*hd] (rows of the decode class), out bf16 same shape.  partial: fp32 scratch of
-// decode_partial_floats() floats.
+// decode_partial_floats() floats.  norms (nullable): fp32 [n_decode, Hq], L2 norm of each head's output.
 size_t decode_partial_floats(int n_decode, int Hq, int hd, int max_context);
 hipError_t launch_attn_decode(const bf16_t *q, const void *cache_k, const void *cache_v, bool cache_bf16,
                               long long num_blocks, int block_size, const int32_t *block_tables, int max_blocks_per_req,
                               const int32_t *ctx_lens, int n_decode, int max_context, int Hq, int Hkv, int hd,
-                              float *partial, bf16_t *out, hipStream_t st);
+                              float *partial, bf16_t *out, float *norms, hipStream_t st);
+// Running mean of the head norms, prune predicate and last-used bookkeeping (elementwise, n x H).
+hipError_t launch_head_norm_stats(const float *norms, const int32_t *t_count, int n, int H, float *abar, int32_t *last_used,
+                                  int window, float tau, int32_t *prune, hipStream_t st);
 // ---- attn_bwd.hip ----------------------------------------------------------------------------
 // Backward of the varlen causal attention of the fine-tune sequences (bf16 operands, fp32 out).
 // dvec: fp32 scratch [rows, Hq].

@@ -56,9 +56,10 @@ class DeviceIteration:
         self.slot_dev = up(self.slot_mapping_host) if self.Ti else None
         self.bt_dev = up(np.ascontiguousarray(np.maximum(b.decode_block_tables, 0), dtype=np.int32)) if self.Td else None
         self.ctx_dev = up(np.asarray(b.decode_ctx, dtype=np.int32)) if self.Td else None
+        self.head_norms = torch.zeros((self.Td, m.n_q_heads), dtype=torch.float32, device=self.dev) if self.Td else None
         self.batch = B.BatchDesc(b.n_prefill, b.n_decode, b.n_ft_seq, self.T, seg, self.seg_dev, self.pos_dev,
                                  self.slot_dev, self.bt_dev, np.asarray(b.decode_ctx, dtype=np.int32), self.ctx_dev,
-                                 b.max_blocks_per_req)
+                                 b.max_blocks_per_req, self.head_norms)
         self.tok_ft = up(np.asarray(b.token_ids[self.Ti:], dtype=np.int32)) if self.Tf else None
         ft_off = (seg[b.n_prefill + b.n_decode:] - self.Ti).astype(np.int32)
         self.ft_off_host = ft_off

@@ -11,11 +11,13 @@ def run_oracle(wl, backward=True, lora=None):
     if len(b.decode_ctx) and wl.ctx_k is not None:
         O.load_context(ck, b.decode_block_tables, b.block_size, wl.ctx_k)
         O.load_context(cv, b.decode_block_tables, b.block_size, wl.ctx_v)
+    extras = {}
     if len(b.ft_lens) == 0:       # inference-only batch: there is no DPO head to run
-        y, slots, saved = O.layer_forward(m, wl.weights, b, wl.x, ck, cv, lora)
+        y, slots, saved = O.layer_forward(m, wl.weights, b, wl.x, ck, cv, lora, extras)
         out = dict(y=y, slots=slots, saved=saved)
     else:
-        out = O.hybrid_iteration(m, wl.weights, b, wl.x, ck, cv, wl.ref_logp, wl.beta, backward=backward, lora=lora)
+        out = O.hybrid_iteration(m, wl.weights, b, wl.x, ck, cv, wl.ref_logp, wl.beta, backward=backward, lora=lora, extras=extras)
+    out["head_norms"] = extras["head_norms"]
     out["cache_k"], out["cache_v"] = ck, cv
     return out
 

@@ -57,3 +57,24 @@ def test_slot_mapping_error_paths(lib):
         B.mace_kv_slot_mapping(np.array([1, -1], np.int32), 16, 16, 1)    # negative block id
     with pytest.raises(B.MaceError):
         B.mace_kv_slot_mapping(np.array([1, 2], np.int32), 12, 0, 1)      # block size not a power of two
+
+
+def test_kv_head_budget_matches_oracle_bit_for_bit():
+    """Host-side integer work: capacity split of Section 4.3, same double-precision decisions."""
+    import numpy as np
+    from oracle import mace_oracle as O
+    from paper_2510_03283_amd import binding as B
+    rng = np.random.default_rng(12)
+    cases = [([1.0, 1.0, 2.0], 10), ([1.0, 1.0, 1.0], 10), ([3.0, 1.0], 8), ([5.0], 17), ([0.5, 0.25, 0.25], 1), ([2.0, 2.0], 0)]
+    for _ in range(300):
+        H = int(rng.integers(1, 65))
+        cases.append((rng.uniform(1e-3, 9.0, H).astype(np.float32).astype(np.float64), int(rng.integers(0, 1 << 20))))
+    for abar, C in cases:
+        got = B.mace_kv_head_budget(abar, C)
+        assert np.array_equal(got, O.head_budget(abar, C)), (abar, C)
+        assert got.sum() == C
+    import pytest
+    with pytest.raises(B.MaceError):
+        B.mace_kv_head_budget([1.0, 0.0], 5)
+    with pytest.raises(B.MaceError):
+        B.mace_kv_head_budget([1.0, float("nan")], 5)

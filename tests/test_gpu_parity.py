@@ -41,6 +41,10 @@ def check_iteration(torch, wl, label, check_grads=True, lora=None):
                 assert e <= TOL_OUT, (label, nm, e)
         # integer side: the slots the library computed are the oracle's, bit for bit
         assert np.array_equal(it.slot_mapping_host.astype(np.int64), ref["slots"])
+        if it.Td:
+            e = max_abs_norm_err(it.head_norms.cpu().numpy(), ref["head_norms"])
+            print(f"[{label}] decode head norms: {e:.2e}", flush=True)
+            assert e <= TOL_OUT, (label, "head norms", e)
         if it.Ti:
             ck, cv = it.cache_k.float().cpu().numpy(), it.cache_v.float().cpu().numpy()
             assert max_abs_norm_err(ck, ref["cache_k"]) <= TOL_OUT and max_abs_norm_err(cv, ref["cache_v"]) <= TOL_OUT
