@@ -25,7 +25,9 @@ adapter path: zero B == base model, equality with the merged weight W + scale*B*
 and in dx, dA = scale*B^T dW and dB = scale*dW A^T against the full-weight gradient, and
 central finite differences on adapter entries; for the pruning statistics: a one-key context
 (the head norm is the norm of that value row), the running mean against the arithmetic mean,
-hand-worked capacity splits and their invariants.  The paper
+hand-worked capacity splits and their invariants; for prefix-shared prefill: zero prefix ==
+plain causal attention, the tail rows of a one-piece prefill of the whole sequence, two
+requests sharing the blocks of one prefix, brute force.  The paper
 prints no worked numerical example for this path, so absolute values of the benchmark
 configurations are pinned by these invariants only.
 """
@@ -154,6 +156,24 @@ def decode_attention(q, K, V):
     return o
 
 
+def prefix_causal_attention(q, K, V, n_prefix):
+    """Attention of L new rows of a request whose first n_prefix tokens are already cached (prefix
+    sharing, Section 4.3: the prefix is prefilled once and its K, V reused by every request below
+    that node).  K, V [n_prefix + L, Hkv, hd] hold the cached prefix followed by the new rows;
+    new row j (position n_prefix + j) attends to keys 0 .. n_prefix + j."""
+    L, Hq, hd = q.shape
+    grp = Hq // K.shape[1]
+    n = K.shape[0]
+    o = np.empty((L, Hq, hd), F64)
+    mask = np.arange(n)[None, :] <= (n_prefix + np.arange(L))[:, None]
+    for h in range(Hq):
+        s = (q[:, h, :] @ K[:, h // grp, :].T) / np.sqrt(F64(hd))
+        s = np.where(mask, s, -np.inf)
+        e = np.exp(s - np.max(s, axis=1, keepdims=True))
+        o[:, h, :] = (e / np.sum(e, axis=1, keepdims=True)) @ V[:, h // grp, :]
+    return o
+
+
 def causal_attention_bwd(do, q, k, v, o, P):
     """D_t = dO_t.O_t ; dV = P^T dO ; dP = dO V^T ; dS = P*(dP - D) ; dQ = dS K / sqrt(hd) ;
     dK = dS^T Q / sqrt(hd); dK, dV summed over the query heads of a group."""
@@ -231,7 +251,8 @@ def layer_forward(dims, W, batch, x, cache_k, cache_v, lora=None, extras=None):
     """One hybrid iteration of the layer, request by request.
 
     batch: object with prefill_lens, decode_ctx, ft_lens, seg_offsets, positions, block_size,
-    prefill_block_tables, decode_block_tables.  x[T, d] rows ordered prefill | decode | ft.
+    prefill_block_tables, decode_block_tables and, optionally, prefill_prefix_lens (tokens of each
+    prefill request that are already cached: shared prefix).  x[T, d] rows ordered prefill | decode | ft.
     cache_k / cache_v: [blocks, Hkv, B, hd] float64, updated in place with the post-RoPE keys
     and the values of the prefill and decode rows.
     lora (optional): adapter on the attention projections; every row of the iteration sees the
@@ -247,16 +268,25 @@ def layer_forward(dims, W, batch, x, cache_k, cache_v, lora=None, extras=None):
     npf, nd = len(batch.prefill_lens), len(batch.decode_ctx)
     B = batch.block_size
     slots_all = []
-    # prefill requests: every token attends to its prefix; K, V go to the cache
+    # prefill requests: every token attends to its prefix; K, V go to the cache.  With a cached
+    # prefix of P tokens the new rows sit at positions P.., are appended behind it, and attend to
+    # the cached rows as well.
+    prefix = getattr(batch, "prefill_prefix_lens", None)
     for i in range(npf):
         o0, o1 = seg[i], seg[i + 1]
+        P = int(prefix[i]) if prefix is not None else 0
         pos = np.asarray(batch.positions[o0:o1])
         a, r1, q, k, v = project_qkv(dims, W, x[o0:o1], pos, lora)
-        slots = slot_mapping(batch.prefill_block_tables[i], B, 0, o1 - o0)
+        slots = slot_mapping(batch.prefill_block_tables[i], B, P, o1 - o0)
         kv_append(cache_k, k, slots)
         kv_append(cache_v, v, slots)
         slots_all.append(slots)
-        o, _, _ = causal_attention(q, k, v)
+        if P == 0:
+            o, _, _ = causal_attention(q, k, v)
+        else:
+            K, _ = kv_gather(cache_k, batch.prefill_block_tables[i], P + o1 - o0)
+            V, _ = kv_gather(cache_v, batch.prefill_block_tables[i], P + o1 - o0)
+            o = prefix_causal_attention(q, np.asarray(K, F64), np.asarray(V, F64), P)
         y[o0:o1], _ = mlp_block(dims, W, x[o0:o1], o.reshape(o1 - o0, -1), lora)
     # decode requests: one new token at position n, appended, attends to n+1 keys
     for j in range(nd):

@@ -31,7 +31,7 @@ STREAMS = {
     "token_ids": 14, "cache_k": 15, "cache_v": 16, "ref_logp": 17, "block_perm": 18,
     "dy": 19,
     "lora_a_q": 20, "lora_b_q": 21, "lora_a_k": 22, "lora_b_k": 23, "lora_a_v": 24, "lora_b_v": 25,
-    "lora_a_o": 26, "lora_b_o": 27,
+    "lora_a_o": 26, "lora_b_o": 27, "prefix_k": 28, "prefix_v": 29,
 }
 
 
@@ -121,6 +121,7 @@ class ConfigSpec:
     beta: float = 0.1
     ref_mode: str = "len"                  # "fixed64": N(-64, 4);  "len": N(-2 len, 0.5 sqrt(len))
     block_size: int = 16
+    prefill_prefix: Optional[List[int]] = None   # tokens of each prefill request that are already cached (prefix sharing)
 
 
 _D7B = dict(d_model=4096, n_q_heads=32, n_kv_heads=32, head_dim=128, d_ff=11008, vocab=32000)
@@ -152,6 +153,7 @@ class Batch:
     prefill_block_tables: List[np.ndarray]   # per prefill request, int32 block ids
     decode_block_tables: np.ndarray          # [n_decode, max_blocks_per_req] int32, -1 padded
     max_blocks_per_req: int
+    prefill_prefix_lens: Optional[np.ndarray] = None   # [n_prefill] cached prefix tokens, None = no prefix anywhere
 
     @property
     def n_prefill(self): return len(self.prefill_lens)
@@ -182,6 +184,8 @@ class Workload:
     ctx_v: Optional[List[np.ndarray]]
     ref_logp: np.ndarray             # [n_ft_seq] float32
     beta: float
+    pre_k: Optional[List[np.ndarray]] = None   # per prefill request [prefix, Hkv, hd] float32: its cached prefix
+    pre_v: Optional[List[np.ndarray]] = None
 
 
 def _maybe_bf16(a: np.ndarray, io_bf16: bool) -> np.ndarray:
@@ -237,6 +241,11 @@ def make_batch(spec: ConfigSpec, n_prefill=None, n_decode=None, n_pairs=None) ->
     else:
         lo, hi = spec.resp_draw
         rl = randint(s, STREAMS["resp_len"], 0, 2 * npairs, lo, hi)
+    px = np.array(spec.prefill_prefix, dtype=np.int64) if spec.prefill_prefix is not None else None
+    if px is not None and len(px) != len(pl):
+        raise ValueError("prefill_prefix needs one entry per prefill request")
+    if n_prefill is not None:
+        px = px[:n_prefill] if px is not None else None
     if n_prefill is not None: pl = pl[:n_prefill]
     if n_decode is not None: dc = dc[:n_decode]
     if n_pairs is not None: rl = rl[:2 * n_pairs]; npairs = n_pairs
@@ -248,7 +257,7 @@ def make_batch(spec: ConfigSpec, n_prefill=None, n_decode=None, n_pairs=None) ->
     T = int(seg_offsets[-1])
     pos = np.empty(T, dtype=np.int32)
     for i, L in enumerate(pl):
-        pos[seg_offsets[i]:seg_offsets[i + 1]] = np.arange(L)
+        pos[seg_offsets[i]:seg_offsets[i + 1]] = np.arange(L) + (int(px[i]) if px is not None else 0)
     for j, n in enumerate(dc):
         pos[seg_offsets[len(pl) + j]] = n
     for q, L in enumerate(ft_lens):
@@ -265,7 +274,7 @@ def make_batch(spec: ConfigSpec, n_prefill=None, n_decode=None, n_pairs=None) ->
     # Paged cache: each request owns ceil(tokens/B) blocks drawn from one seeded permutation of
     # the pool (a fragmented pool, as after a long run of a server).
     B = spec.block_size
-    nb_pre = [int(-(-L // B)) for L in pl]
+    nb_pre = [int(-(-(L + (int(px[i]) if px is not None else 0)) // B)) for i, L in enumerate(pl)]
     nb_dec = [int(-(-(n + 1) // B)) for n in dc]
     need = sum(nb_pre) + sum(nb_dec)
     num_blocks = need + max(4, need // 8)
@@ -278,7 +287,7 @@ def make_batch(spec: ConfigSpec, n_prefill=None, n_decode=None, n_pairs=None) ->
     dbt = np.full((len(dc), mb), -1, dtype=np.int32)
     for j, nb in enumerate(nb_dec):
         dbt[j, :nb] = perm[cur:cur + nb]; cur += nb
-    return Batch(pl, dc, ft_lens, ft_prompt, seg_offsets, pos, tok, B, num_blocks, pbt, dbt, mb)
+    return Batch(pl, dc, ft_lens, ft_prompt, seg_offsets, pos, tok, B, num_blocks, pbt, dbt, mb, px)
 
 
 def make_cached_context(spec: ConfigSpec, batch: Batch):
@@ -294,6 +303,21 @@ def make_cached_context(spec: ConfigSpec, batch: Batch):
         n = int(n)
         ks.append(_maybe_bf16(normal(spec.seed, STREAMS["cache_k"], off * row, n * row), m.io_bf16).reshape(n, m.n_kv_heads, m.head_dim))
         vs.append(_maybe_bf16(normal(spec.seed, STREAMS["cache_v"], off * row, n * row), m.io_bf16).reshape(n, m.n_kv_heads, m.head_dim))
+        off += n
+    return ks, vs
+
+
+def make_cached_prefix(spec: ConfigSpec, batch: Batch):
+    """Cached K and V of the shared prefixes of the prefill requests, N(0,1), laid out like
+    make_cached_context (streams prefix_k / prefix_v)."""
+    m = spec.dims
+    row = m.n_kv_heads * m.head_dim
+    off = 0
+    ks, vs = [], []
+    for n in batch.prefill_prefix_lens:
+        n = int(n)
+        ks.append(_maybe_bf16(normal(spec.seed, STREAMS["prefix_k"], off * row, n * row), m.io_bf16).reshape(n, m.n_kv_heads, m.head_dim))
+        vs.append(_maybe_bf16(normal(spec.seed, STREAMS["prefix_v"], off * row, n * row), m.io_bf16).reshape(n, m.n_kv_heads, m.head_dim))
         off += n
     return ks, vs
 
@@ -315,7 +339,8 @@ def make_workload(name: str, n_prefill=None, n_decode=None, n_pairs=None, with_c
     b = make_batch(spec, n_prefill, n_decode, n_pairs)
     x = w["E"][b.token_ids]
     ck, cv = make_cached_context(spec, b) if with_cache else (None, None)
-    return Workload(spec, spec.dims, w, b, x, ck, cv, make_ref_logp(spec, b), spec.beta)
+    pk, pv = make_cached_prefix(spec, b) if (with_cache and b.prefill_prefix_lens is not None) else (None, None)
+    return Workload(spec, spec.dims, w, b, x, ck, cv, make_ref_logp(spec, b), spec.beta, pk, pv)
 
 
 def make_upstream_grad(spec: ConfigSpec, n_rows: int, scale: float = 1e-3) -> np.ndarray:

@@ -11,6 +11,9 @@ def run_oracle(wl, backward=True, lora=None):
     if len(b.decode_ctx) and wl.ctx_k is not None:
         O.load_context(ck, b.decode_block_tables, b.block_size, wl.ctx_k)
         O.load_context(cv, b.decode_block_tables, b.block_size, wl.ctx_v)
+    if getattr(wl, "pre_k", None) is not None:
+        O.load_context(ck, b.prefill_block_tables, b.block_size, wl.pre_k)
+        O.load_context(cv, b.prefill_block_tables, b.block_size, wl.pre_v)
     extras = {}
     if len(b.ft_lens) == 0:       # inference-only batch: there is no DPO head to run
         y, slots, saved = O.layer_forward(m, wl.weights, b, wl.x, ck, cv, lora, extras)
