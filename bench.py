@@ -50,6 +50,9 @@ def main():
     ap.add_argument("--variant", default="full", choices=["full", "lora"],
                     help="full: all seven weight gradients (the headline metric); lora: frozen base model, rank-16 "
                          "adapters on the attention projections, adapter gradients only")
+    ap.add_argument("--prefix", type=int, default=0,
+                    help="give every prefill request a cached prefix of this many tokens (multiple of the block size; "
+                         "groups of four requests share the blocks of one prefix node): prefix-shared prefill")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket launches with events")
     ap.add_argument("--calib-copy", action="store_true",
@@ -69,7 +72,21 @@ def main():
         sys.exit(2)
     B.load()   # fails loudly when the HIP library is not built
     big_cache = args.workload in ("7b", "7b_decode", "7b_ft")     # cached contexts drawn on the GPU
+    if args.prefix:
+        import dataclasses
+        base = synth.CONFIGS[args.workload]
+        if args.prefix % base.block_size or big_cache:
+            print("bench.py: --prefix needs a multiple of the block size and a host-generated cache (workload edge)", file=sys.stderr)
+            sys.exit(2)
+        n_pre = len(base.prefill_lens) if base.prefill_lens is not None else base.prefill_draw[0]
+        synth.CONFIGS[args.workload] = dataclasses.replace(base, prefill_prefix=[args.prefix] * n_pre)
     wl = synth.make_workload(args.workload, with_cache=not big_cache)
+    if args.prefix:
+        nb = args.prefix // wl.batch.block_size
+        for i in range(wl.batch.n_prefill):          # requests 4k .. 4k+3 hang below one prefix node
+            a = i - i % 4
+            wl.batch.prefill_block_tables[i][:nb] = wl.batch.prefill_block_tables[a][:nb]
+            wl.pre_k[i], wl.pre_v[i] = wl.pre_k[a], wl.pre_v[a]
     lora = synth.make_lora(wl.spec, rank=16, scale=2.0) if args.variant == "lora" else None
     it = DeviceIteration(wl, device_cache_seed=wl.spec.seed if big_cache else None, lora=lora)
     if args.calib_copy:
@@ -116,6 +133,7 @@ def main():
         "config": {"workload": f"{args.workload} (BASELINE.json configs[{synth.CONFIG_ORDER.index(args.workload)}])",
                    "rows": T, "prefill_rows": it.Tp, "decode_rows": it.Td, "ft_rows": it.Tf, "loss_rows": it.R,
                    "decode_context_tokens": int(wl.batch.decode_ctx.sum()), "n_pairs": it.n_pairs,
+                   "prefill_prefix_tokens": args.prefix,
                    "variant": "full fine-tune (7 weight gradients + head)" if lora is None else "LoRA rank 16 on q,k,v,o (adapter gradients only)"},
     }
     if prof:

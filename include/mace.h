@@ -85,6 +85,16 @@ typedef struct {
   const int32_t *context_lens_host;/* host   [n_decode] tokens already cached (the new token is not counted) */
   const int32_t *context_lens;     /* device copy of the same array */
   int32_t max_blocks_per_req;
+  /* Prefix sharing (Section 4.3, "Reduced prefill via prefix tree"): prefill request i may have its
+   * first prefill_prefix_lens[i] tokens cached already (K, V of a shared prefix node); its rows then
+   * sit at positions prefix.., are appended behind the prefix (slot_mapping computed with
+   * start_pos = prefix) and attend to the cached rows through prefill_block_tables[i], which
+   * covers prefix + new tokens.  Requests below one node list the same leading blocks.  All three
+   * pointers NULL = no request has a prefix.  Needs a bf16 cache (io_dtype MACE_BF16). */
+  const int32_t *prefill_block_tables;      /* device [n_prefill, max_blocks_per_prefill] */
+  const int32_t *prefill_prefix_lens_host;  /* host   [n_prefill] */
+  const int32_t *prefill_prefix_lens;       /* device copy of the same array */
+  int32_t max_blocks_per_prefill;
   float *decode_head_norms;        /* optional OUTPUT, device fp32 [n_decode, n_q_heads]: L2 norm of every head's attention
                                       output vector of each decode row (before the output projection) - the signal of the
                                       norm-based cache pruning of Section 4.3; NULL = not wanted */

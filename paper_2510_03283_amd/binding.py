@@ -60,7 +60,9 @@ class BatchT(C.Structure):
     _fields_ = [("n_prefill", C.c_int32), ("n_decode", C.c_int32), ("n_ft_seq", C.c_int32), ("n_tokens", C.c_int32),
                 ("seg_offsets_host", C.c_void_p), ("seg_offsets", C.c_void_p), ("positions", C.c_void_p),
                 ("slot_mapping", C.c_void_p), ("block_tables", C.c_void_p), ("context_lens_host", C.c_void_p),
-                ("context_lens", C.c_void_p), ("max_blocks_per_req", C.c_int32), ("decode_head_norms", C.c_void_p)]
+                ("context_lens", C.c_void_p), ("max_blocks_per_req", C.c_int32), ("prefill_block_tables", C.c_void_p),
+                ("prefill_prefix_lens_host", C.c_void_p), ("prefill_prefix_lens", C.c_void_p), ("max_blocks_per_prefill", C.c_int32),
+                ("decode_head_norms", C.c_void_p)]
 
 
 class ProfileEntryT(C.Structure):
@@ -196,13 +198,19 @@ class BatchDesc:
     """Owns the host arrays a mace_batch_t points to, next to the struct itself."""
 
     def __init__(self, n_prefill, n_decode, n_ft_seq, n_tokens, seg_offsets_host, seg_offsets, positions,
-                 slot_mapping, block_tables, context_lens_host, context_lens, max_blocks_per_req, decode_head_norms=None):
+                 slot_mapping, block_tables, context_lens_host, context_lens, max_blocks_per_req, decode_head_norms=None,
+                 prefill_block_tables=None, prefill_prefix_lens_host=None, prefill_prefix_lens=None, max_blocks_per_prefill=0):
         self._seg, segp = _host_i32(seg_offsets_host)
         self._ctx, ctxp = _host_i32(context_lens_host)
-        self._keep = (seg_offsets, positions, slot_mapping, block_tables, context_lens, decode_head_norms)
+        self._keep = (seg_offsets, positions, slot_mapping, block_tables, context_lens, decode_head_norms,
+                      prefill_block_tables, prefill_prefix_lens)
+        pfxp = None
+        if prefill_prefix_lens_host is not None:
+            self._pfx, pfxp = _host_i32(prefill_prefix_lens_host)
         self.struct = BatchT(n_prefill, n_decode, n_ft_seq, n_tokens, segp, _dev(seg_offsets), _dev(positions),
                              _dev(slot_mapping), _dev(block_tables), ctxp if n_decode else None,
-                             _dev(context_lens), max_blocks_per_req, _dev(decode_head_norms))
+                             _dev(context_lens), max_blocks_per_req, _dev(prefill_block_tables), pfxp,
+                             _dev(prefill_prefix_lens), max_blocks_per_prefill, _dev(decode_head_norms))
 
 
 def mace_hybrid_layer_fwd(h, w: LayerWT, batch: BatchDesc, cache: Optional[KvCacheT], x, y, saved, workspace, stream=None):

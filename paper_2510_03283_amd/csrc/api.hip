@@ -387,6 +387,7 @@ void gp_seg(GemmParams &p, const bf16_t *b_hi, const bf16_t *b_lo, int N, int c_
 struct BatchInfo {
   int Tp, Td, Tf, Ti, T, n_seq_all, max_prefill, max_ft, max_ctx;
   double pairs_prefill, pairs_ft;   // sum of L(L+1)/2 (query, key) pairs, for the algorithmic flop counts
+  bool prefix;                      // prefill requests attend to cached prefixes through block tables
 };
 
 int check_batch(const mace_batch_t *b, BatchInfo &I) {
@@ -412,6 +413,16 @@ int check_batch(const mace_batch_t *b, BatchInfo &I) {
   I.Tf = I.T - I.Ti;
   I.n_seq_all = ns;
   if (b->n_tokens > 0 && (!b->seg_offsets || !b->positions)) return fail(MACE_INVALID_ARG, "seg_offsets/positions device pointer is null");
+  I.prefix = b->prefill_block_tables || b->prefill_prefix_lens_host || b->prefill_prefix_lens;
+  if (I.prefix && b->n_prefill > 0) {
+    if (!b->prefill_block_tables || !b->prefill_prefix_lens_host || !b->prefill_prefix_lens || b->max_blocks_per_prefill <= 0)
+      return fail(MACE_INVALID_ARG, "prefix sharing needs prefill_block_tables, both prefix length arrays and max_blocks_per_prefill");
+    for (int i = 0; i < b->n_prefill; ++i) {
+      const int P = b->prefill_prefix_lens_host[i], L = so[i + 1] - so[i];
+      if (P < 0) return fail(MACE_INVALID_ARG, "negative prefix length");
+      I.pairs_prefill += (double)P * L;
+    }
+  }
   if (b->n_decode > 0) {
     if (!b->context_lens_host || !b->context_lens || !b->block_tables) return fail(MACE_INVALID_ARG, "decode descriptors are null");
     for (int i = 0; i < b->n_decode; ++i) {
@@ -653,6 +664,13 @@ static int layer_fwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
       if ((long long)I.max_ctx + 1 > (long long)batch->max_blocks_per_req * cache->block_size) return fail(MACE_INVALID_ARG, "context longer than the block table");
     }
   }
+  if (I.prefix && batch->n_prefill > 0) {
+    if (!D.bf) return fail(MACE_BAD_SHAPE, "prefix sharing needs a bf16 cache");
+    for (int i = 0; i < batch->n_prefill; ++i) {
+      const long long need = (long long)batch->prefill_prefix_lens_host[i] + batch->seg_offsets_host[i + 1] - batch->seg_offsets_host[i];
+      if (need > (long long)batch->max_blocks_per_prefill * cache->block_size) return fail(MACE_INVALID_ARG, "prefix + new tokens longer than the prefill block table");
+    }
+  }
   if (I.Tf > 0 && !saved) return fail(MACE_INVALID_ARG, "saved is null");
   if (!workspace) return fail(MACE_INVALID_ARG, "workspace is null");
   if (((uintptr_t)workspace & 255) || ((uintptr_t)saved & 255)) return fail(MACE_INVALID_ARG, "workspace/saved must be 256-byte aligned");
@@ -730,7 +748,11 @@ static int layer_fwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
                             nullptr, nullptr, nullptr, D.bf, 0, 1, st), "rope ft");
   // 4. attention: prefill (causal), decode (paged), fine-tune (causal, split operands, LSE kept)
   prof_mark(h, st, T_ATTN_PREFILL, 4.0 * D.hd * D.Hq * I.pairs_prefill);
-  HIP_TRY(launch_attn_fwd(F.q_i, F.k_i, F.v_i, nullptr, nullptr, nullptr, batch->seg_offsets, 0, batch->n_prefill, I.max_prefill, D.Hq, D.Hkv, D.hd, F.o_i, nullptr, nullptr, st), "prefill attention");
+  if (I.prefix && batch->n_prefill > 0)
+    HIP_TRY(launch_attn_fwd_paged(F.q_i, cache->k, cache->v, cache->num_blocks, cache->block_size, batch->prefill_block_tables, batch->max_blocks_per_prefill,
+                                  batch->prefill_prefix_lens, batch->seg_offsets, 0, batch->n_prefill, I.max_prefill, D.Hq, D.Hkv, D.hd, F.o_i, st), "prefix-shared prefill attention");
+  else
+    HIP_TRY(launch_attn_fwd(F.q_i, F.k_i, F.v_i, nullptr, nullptr, nullptr, batch->seg_offsets, 0, batch->n_prefill, I.max_prefill, D.Hq, D.Hkv, D.hd, F.o_i, nullptr, nullptr, st), "prefill attention");
   if (I.Td > 0) {
     double kv_tokens = 0.0;
     for (int i = 0; i < I.Td; ++i) kv_tokens += (double)batch->context_lens_host[i] + 1.0;

@@ -19,13 +19,25 @@ constexpr int KB = 64;    // keys per LDS tile
 
 __device__ __forceinline__ bf16x8_t as_bf8(uint4 u) { return __builtin_bit_cast(bf16x8_t, u); }
 
-template <int HD, bool SPLIT, int NW>
+// Source of K and V for the PAGED variant (prefill rows of requests with a cached prefix): both
+// the prefix and the request's own rows, which the rotary kernel has appended by then, are read
+// from the paged cache through the request's block table.
+struct PagedKV {
+  const bf16_t *cache_k, *cache_v;   // [blocks, Hkv, B, HD] bf16
+  const int32_t *block_tables;       // [n_seq, max_blocks]
+  const int32_t *prefix_lens;        // [n_seq] cached tokens in front of the request's rows
+  long long num_blocks;
+  int max_blocks, bshift;
+};
+
+template <int HD, bool SPLIT, int NW, bool PAGED>
 __global__ __launch_bounds__(64 * NW) void attn_fwd_kernel(const bf16_t *__restrict__ q_hi, const bf16_t *__restrict__ k_hi,
                                                            const bf16_t *__restrict__ v_hi, const bf16_t *__restrict__ q_lo,
                                                            const bf16_t *__restrict__ k_lo, const bf16_t *__restrict__ v_lo,
                                                            const int32_t *__restrict__ seg, int row_base, int Hq, int Hkv,
                                                            bf16_t *__restrict__ o_hi, bf16_t *__restrict__ o_lo,
-                                                           float *__restrict__ lse) {
+                                                           float *__restrict__ lse, const PagedKV pg) {
+  static_assert(!(PAGED && SPLIT), "paged K/V are single bf16 operands");
   constexpr int NT = SPLIT ? 2 : 1;
   constexpr int QB = 32 * NW;
   constexpr int NKK = HD / 16;     // MFMA k-steps over the head dimension
@@ -43,17 +55,26 @@ __global__ __launch_bounds__(64 * NW) void attn_fwd_kernel(const bf16_t *__restr
   const int qw0 = q0 + wave * 32;                        // first query of this wave
   const int qi = qw0 + j;                                // this lane's query (may be >= L: computed, not stored)
   const size_t qld = (size_t)Hq * HD, kld = (size_t)Hkv * HD;
-  const bf16_t *kbase[2] = {k_hi + (size_t)r0 * kld + (size_t)kvh * HD, SPLIT ? k_lo + (size_t)r0 * kld + (size_t)kvh * HD : nullptr};
-  const bf16_t *vbase[2] = {v_hi + (size_t)r0 * kld + (size_t)kvh * HD, SPLIT ? v_lo + (size_t)r0 * kld + (size_t)kvh * HD : nullptr};
+  const bf16_t *kbase[2] = {PAGED ? nullptr : k_hi + (size_t)r0 * kld + (size_t)kvh * HD, SPLIT ? k_lo + (size_t)r0 * kld + (size_t)kvh * HD : nullptr};
+  const bf16_t *vbase[2] = {PAGED ? nullptr : v_hi + (size_t)r0 * kld + (size_t)kvh * HD, SPLIT ? v_lo + (size_t)r0 * kld + (size_t)kvh * HD : nullptr};
 
-  const int kend = min(L, q0 + QB);
+  // key index space: the request's cached prefix (PAGED only) followed by its own rows
+  const int pfx = PAGED ? pg.prefix_lens[s] : 0;
+  const int nkeys = pfx + L;
+  const int kend = min(nkeys, pfx + q0 + QB);
   const int ntiles = (kend + KB - 1) / KB;
   auto issue_tile = [&](int it) {
     bf16_t *S = lds + (it & 1) * STAGE;
+    if constexpr (PAGED) {
+      const int32_t *bt = pg.block_tables + (size_t)s * pg.max_blocks;
+      T::issue_paged(pg.cache_k, bt, pg.bshift, Hkv, kvh, pg.num_blocks, it * KB, nkeys, S);
+      T::issue_paged(pg.cache_v, bt, pg.bshift, Hkv, kvh, pg.num_blocks, it * KB, nkeys, S + T::ELEMS);
+    } else {
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      T::issue(kbase[t], kld, it * KB, L, S + t * T::ELEMS);
-      T::issue(vbase[t], kld, it * KB, L, S + (NT + t) * T::ELEMS);
+      for (int t = 0; t < NT; ++t) {
+        T::issue(kbase[t], kld, it * KB, L, S + t * T::ELEMS);
+        T::issue(vbase[t], kld, it * KB, L, S + (NT + t) * T::ELEMS);
+      }
     }
   };
   issue_tile(0);
@@ -92,7 +113,7 @@ __global__ __launch_bounds__(64 * NW) void attn_fwd_kernel(const bf16_t *__restr
     __syncthreads();                                     // tile it has landed; stage (it+1)&1 is free
     if (it + 1 < ntiles) issue_tile(it + 1);
     const int kb = it * KB;
-    if (kb > qw0 + 31) continue;                         // every key of the tile is in this wave's future
+    if (kb > pfx + qw0 + 31) continue;                   // every key of the tile is in this wave's future
     const bf16_t *Kh = lds + (it & 1) * STAGE, *Kl = Kh + T::ELEMS, *Vh = Kh + NT * T::ELEMS, *Vl = Vh + T::ELEMS;
 
     // ---- S^T = K Q^T for the two 32-key sub-tiles; lane owns query j, register r owns a key
@@ -113,13 +134,13 @@ __global__ __launch_bounds__(64 * NW) void attn_fwd_kernel(const bf16_t *__restr
       }
     }
     // ---- mask (only tiles that touch the diagonal or the end of the sequence), online soft-max
-    if (kb + KB - 1 > qw0 || kb + KB > L) {
+    if (kb + KB - 1 > pfx + qw0 || kb + KB > nkeys) {
 #pragma unroll
       for (int st = 0; st < 2; ++st)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int key = kb + st * 32 + 16 * (r >> 3) + 8 * g + (r & 7);
-          if (!(key <= qi && key < L)) sacc[st][r] = -INFINITY;
+          if (!(key <= pfx + qi && key < nkeys)) sacc[st][r] = -INFINITY;
         }
     }
     float mx = sacc[0][0];
@@ -191,20 +212,20 @@ __global__ __launch_bounds__(64 * NW) void attn_fwd_kernel(const bf16_t *__restr
   }
 }
 
-template <int HD, bool SPLIT, int NW>
+template <int HD, bool SPLIT, int NW, bool PAGED = false>
 hipError_t launch_t(const bf16_t *q_hi, const bf16_t *k_hi, const bf16_t *v_hi, const bf16_t *q_lo, const bf16_t *k_lo,
                     const bf16_t *v_lo, const int32_t *seg, int row_base, int n_seq, int max_len, int Hq, int Hkv,
-                    bf16_t *o_hi, bf16_t *o_lo, float *lse, hipStream_t st) {
+                    bf16_t *o_hi, bf16_t *o_lo, float *lse, hipStream_t st, const PagedKV pg = PagedKV{}) {
   constexpr int NT = SPLIT ? 2 : 1;
   constexpr size_t lds = (size_t)2 * 2 * NT * KB * HD * sizeof(bf16_t);
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void *)attn_fwd_kernel<HD, SPLIT, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = hipFuncSetAttribute((const void *)attn_fwd_kernel<HD, SPLIT, NW, PAGED>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
   dim3 grid(cdiv(max_len, 32 * NW), n_seq, Hq);
-  hipLaunchKernelGGL((attn_fwd_kernel<HD, SPLIT, NW>), grid, dim3(64 * NW), lds, st, q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, Hq, Hkv, o_hi, o_lo, lse);
+  hipLaunchKernelGGL((attn_fwd_kernel<HD, SPLIT, NW, PAGED>), grid, dim3(64 * NW), lds, st, q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, Hq, Hkv, o_hi, o_lo, lse, pg);
   return hipGetLastError();
 }
 
@@ -223,5 +244,18 @@ hipError_t launch_attn_fwd(const bf16_t *q_hi, const bf16_t *k_hi, const bf16_t 
                              : launch_t<64, false, 4>(q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, n_seq, max_len, Hq, Hkv, o_hi, o_lo, lse, st);
   if (hd == 128) return split ? launch_t<128, true, 8>(q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, n_seq, max_len, Hq, Hkv, o_hi, o_lo, lse, st)
                               : launch_t<128, false, 4>(q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, n_seq, max_len, Hq, Hkv, o_hi, o_lo, lse, st);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_attn_fwd_paged(const bf16_t *q, const void *cache_k, const void *cache_v, long long num_blocks, int block_size,
+                                 const int32_t *block_tables, int max_blocks, const int32_t *prefix_lens, const int32_t *seg,
+                                 int row_base, int n_seq, int max_len, int Hq, int Hkv, int hd, bf16_t *o, hipStream_t st) {
+  if (n_seq <= 0 || max_len <= 0) return hipSuccess;
+  if (n_seq > 65535 || Hq > 65535 || block_size <= 0 || (block_size & (block_size - 1)) || max_blocks <= 0) return hipErrorInvalidValue;
+  int bshift = 0;
+  while ((1 << bshift) < block_size) ++bshift;
+  const PagedKV pg{(const bf16_t *)cache_k, (const bf16_t *)cache_v, block_tables, prefix_lens, num_blocks, max_blocks, bshift};
+  if (hd == 64) return launch_t<64, false, 4, true>(q, nullptr, nullptr, nullptr, nullptr, nullptr, seg, row_base, n_seq, max_len, Hq, Hkv, o, nullptr, nullptr, st, pg);
+  if (hd == 128) return launch_t<128, false, 4, true>(q, nullptr, nullptr, nullptr, nullptr, nullptr, seg, row_base, n_seq, max_len, Hq, Hkv, o, nullptr, nullptr, st, pg);
   return hipErrorInvalidValue;
 }

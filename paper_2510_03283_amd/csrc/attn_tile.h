@@ -63,6 +63,28 @@ struct Tile {
     }
   }
 
+  // Same tile, but row p (a token position of one request) is fetched from a paged cache
+  // [blocks, Hkv, B, HD]: block id from the request's block table, B = 1 << bshift.  Positions at or
+  // beyond row_end, and block ids outside [0, num_blocks), read zeros.
+  static __device__ __forceinline__ void issue_paged(const bf16_t *cache, const int32_t *bt, int bshift, int Hkv, int kvh,
+                                                     long long num_blocks, int row0, int row_end, bf16_t *S) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int q = wave + (NTHR / 64) * i;
+      const int chunk = q * 64 + lane;
+      const int lr = chunk / CPR, c = (chunk % CPR) ^ swz(lr);
+      const int pos = row0 + lr;
+      const bf16_t *p = (const bf16_t *)&zero16;
+      if (pos < row_end) {
+        const long long blk = bt[pos >> bshift];
+        if (blk >= 0 && blk < num_blocks)
+          p = cache + ((((size_t)blk * Hkv + kvh) << bshift) + (pos & ((1 << bshift) - 1))) * HD + c * 8;
+      }
+      __builtin_amdgcn_global_load_lds((gbl_void_t *)p, (lds_void_t *)(S + q * 512), 16, 0, 0);
+    }
+  }
+
   struct FragK { int base, sw; };
   static __device__ __forceinline__ FragK frag_k_init(int row) { return FragK{row * HD, swz(row)}; }
   // head-dim elements kk*16 + 8*half .. +7 of the row

@@ -66,6 +66,12 @@ hipError_t launch_attn_fwd(const bf16_t *q_hi, const bf16_t *k_hi, const bf16_t 
                            const bf16_t *k_lo, const bf16_t *v_lo, const int32_t *seg, int row_base, int n_seq,
                            int max_len, int Hq, int Hkv, int hd, bf16_t *o_hi, bf16_t *o_lo, float *lse,
                            hipStream_t st);
+// The same for requests with a cached prefix: keys and values of request s are positions
+// 0 .. prefix_lens[s] + len_s - 1 of its block table in the paged bf16 cache (its own rows must have
+// been appended already); query j of the request sits at position prefix_lens[s] + j.
+hipError_t launch_attn_fwd_paged(const bf16_t *q, const void *cache_k, const void *cache_v, long long num_blocks, int block_size,
+                                 const int32_t *block_tables, int max_blocks, const int32_t *prefix_lens, const int32_t *seg,
+                                 int row_base, int n_seq, int max_len, int Hq, int Hkv, int hd, bf16_t *o, hipStream_t st);
 // ---- attn_decode.hip -------------------------------------------------------------------------
 // One query row per request against its paged context of ctx_len[r]+1 tokens.  q bf16
 // [n_decode, Hq*hd] (rows of the decode class), out bf16 same shape.  partial: fp32 scratch of

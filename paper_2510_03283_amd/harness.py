@@ -45,8 +45,9 @@ class DeviceIteration:
         self.R = b.n_loss_rows
         seg = np.asarray(b.seg_offsets, dtype=np.int32)
         slots = []
+        pfx = b.prefill_prefix_lens
         for i, L in enumerate(b.prefill_lens):
-            slots.append(B.mace_kv_slot_mapping(b.prefill_block_tables[i], b.block_size, 0, int(L)))
+            slots.append(B.mace_kv_slot_mapping(b.prefill_block_tables[i], b.block_size, int(pfx[i]) if pfx is not None else 0, int(L)))
         for j, n in enumerate(b.decode_ctx):
             nb = -(-(int(n) + 1) // b.block_size)
             slots.append(B.mace_kv_slot_mapping(b.decode_block_tables[j][:nb], b.block_size, int(n), 1))
@@ -57,9 +58,17 @@ class DeviceIteration:
         self.bt_dev = up(np.ascontiguousarray(np.maximum(b.decode_block_tables, 0), dtype=np.int32)) if self.Td else None
         self.ctx_dev = up(np.asarray(b.decode_ctx, dtype=np.int32)) if self.Td else None
         self.head_norms = torch.zeros((self.Td, m.n_q_heads), dtype=torch.float32, device=self.dev) if self.Td else None
+        pre = {}
+        if pfx is not None and b.n_prefill:
+            mbp = max(len(tb) for tb in b.prefill_block_tables)
+            pbt = np.zeros((b.n_prefill, mbp), np.int32)
+            for i, tb in enumerate(b.prefill_block_tables):
+                pbt[i, :len(tb)] = tb
+            pre = dict(prefill_block_tables=up(pbt), prefill_prefix_lens_host=np.asarray(pfx, np.int32),
+                       prefill_prefix_lens=up(np.asarray(pfx, np.int32)), max_blocks_per_prefill=mbp)
         self.batch = B.BatchDesc(b.n_prefill, b.n_decode, b.n_ft_seq, self.T, seg, self.seg_dev, self.pos_dev,
                                  self.slot_dev, self.bt_dev, np.asarray(b.decode_ctx, dtype=np.int32), self.ctx_dev,
-                                 b.max_blocks_per_req, self.head_norms)
+                                 b.max_blocks_per_req, self.head_norms, **pre)
         self.tok_ft = up(np.asarray(b.token_ids[self.Ti:], dtype=np.int32)) if self.Tf else None
         ft_off = (seg[b.n_prefill + b.n_decode:] - self.Ti).astype(np.int32)
         self.ft_off_host = ft_off
@@ -83,6 +92,8 @@ class DeviceIteration:
                     c[b0:b0 + step] = torch.randn(c[b0:b0 + step].shape, generator=gen, device=self.dev, dtype=torch.float32).to(self.io_dtype)
         elif load_cache and self.Td and wl.ctx_k is not None:
             self.load_context(wl.ctx_k, wl.ctx_v)
+        if load_cache and getattr(wl, "pre_k", None) is not None:
+            self.load_prefix(wl.pre_k, wl.pre_v)
 
         # buffers
         max_ctx = int(b.decode_ctx.max()) if self.Td else 0
@@ -116,6 +127,23 @@ class DeviceIteration:
             nb = -(-n // b.block_size)
             slots.append(B.mace_kv_slot_mapping(b.decode_block_tables[j][:nb], b.block_size, 0, n))
             ks.append(ctx_k[j]); vs.append(ctx_v[j])
+        if not slots:
+            return
+        sl = torch.from_numpy(np.concatenate(slots).astype(np.int32)).to(self.dev)
+        k = torch.from_numpy(np.concatenate(ks).astype(np.float32)).to(self.dev).to(self.io_dtype).contiguous()
+        v = torch.from_numpy(np.concatenate(vs).astype(np.float32)).to(self.dev).to(self.io_dtype).contiguous()
+        B.mace_kv_cache_append(self.h, self.cache, k, v, sl, int(sl.numel()))
+
+    def load_prefix(self, pre_k, pre_v):
+        """Place the cached prefix of every prefill request through mace_kv_cache_append."""
+        b = self.wl.batch
+        slots, ks, vs = [], [], []
+        for i, n in enumerate(b.prefill_prefix_lens):
+            n = int(n)
+            if n == 0:
+                continue
+            slots.append(B.mace_kv_slot_mapping(b.prefill_block_tables[i], b.block_size, 0, n))
+            ks.append(pre_k[i]); vs.append(pre_v[i])
         if not slots:
             return
         sl = torch.from_numpy(np.concatenate(slots).astype(np.int32)).to(self.dev)
