@@ -27,7 +27,8 @@ central finite differences on adapter entries; for the pruning statistics: a one
 (the head norm is the norm of that value row), the running mean against the arithmetic mean,
 hand-worked capacity splits and their invariants; for prefix-shared prefill: zero prefix ==
 plain causal attention, the tail rows of a one-piece prefill of the whole sequence, two
-requests sharing the blocks of one prefix, brute force.  The paper
+requests sharing the blocks of one prefix, brute force; for the optimizer step: the first-step
+closed form, zero gradient, and torch.optim.AdamW on the CPU.  The paper
 prints no worked numerical example for this path, so absolute values of the benchmark
 configurations are pinned by these invariants only.
 """
@@ -523,6 +524,34 @@ def prune_flags(norms, t_now, t_last_used, window, tau):
     low = norms < tau
     flags = ((t_now - last) > window) | low
     return flags, np.where(low, last, t_now)
+
+
+# --------------------------------------------------------------------------- closing the loop
+
+def next_token_logits(dims, W, y_rows):
+    """Logits of the token that follows each given row (the decode rows, or the last row of a
+    prefill request): final RMSNorm, tied head E.  Returns logits [n, V] and the greedy choice
+    argmax (lowest index on ties) - what the serving loop samples from and checks for
+    end-of-sequence (Section 4.2, CheckEnd)."""
+    n, _ = rmsnorm(np.asarray(y_rows, F64), _w(W, "gf"), dims.rms_eps)
+    logits = n @ _w(W, "E").T
+    return logits, np.argmax(logits, axis=1)
+
+
+def adamw_step(param, grad, m, v, step, lr, beta1, beta2, eps, weight_decay):
+    """One AdamW update (decoupled weight decay), the optimizer step that turns the gradients of an
+    iteration into the model the next iteration sees (Section 2.1: later requests benefit from the
+    updated model).  step counts from 1.
+      m <- b1 m + (1-b1) g ; v <- b2 v + (1-b2) g^2 ; mhat = m/(1-b1^t) ; vhat = v/(1-b2^t)
+      p <- p - lr * (mhat / (sqrt(vhat) + eps) + wd * p)
+    Returns the new (param, m, v)."""
+    p, g = np.asarray(param, F64), np.asarray(grad, F64)
+    m = beta1 * np.asarray(m, F64) + (1.0 - beta1) * g
+    v = beta2 * np.asarray(v, F64) + (1.0 - beta2) * g * g
+    mhat = m / (1.0 - beta1 ** step)
+    vhat = v / (1.0 - beta2 ** step)
+    p = p - lr * (mhat / (np.sqrt(vhat) + eps) + weight_decay * p)
+    return p, m, v
 
 
 # --------------------------------------------------------------------------- whole iteration
