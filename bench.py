@@ -41,6 +41,51 @@ def cpu_baseline(wl, lora=None):
             "sample": f"whole workload, 1 pass ({wl.batch.n_tokens} rows, {dt:.1f} s)"}
 
 
+def time_extras(it, wl, torch, B, reps=10):
+    """Next-token logits (last row of every prefill request + every decode row) and one AdamW step over
+    the seven weight matrices of the layer, each timed with events on the stream they run on."""
+    import numpy as np
+    b, m = wl.batch, wl.dims
+    rows = np.array([int(b.seg_offsets[i + 1]) - 1 for i in range(b.n_prefill)] + list(range(it.Tp, it.Ti)), np.int32)
+    res = {}
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    if len(rows):
+        ridx = torch.from_numpy(rows).cuda()
+        logits = torch.empty((len(rows), m.vocab), dtype=torch.float32, device="cuda")
+        nxt = torch.empty(len(rows), dtype=torch.int32, device="cuda")
+        for _ in range(2):
+            B.mace_next_token_logits(it.h, it.y, ridx, len(rows), it.gf, it.E, logits, nxt, it.ws)
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(reps):
+            B.mace_next_token_logits(it.h, it.y, ridx, len(rows), it.gf, it.E, logits, nxt, it.ws)
+        e1.record(); torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        # HBM-bound at this row count: E [V, d] bf16 read once + fp32 logits written once
+        by = m.vocab * m.d_model * 2 + len(rows) * m.vocab * 4
+        res["next_token_logits"] = {"rows": int(len(rows)), "ms": ms, "GB/s": by / ms / 1e6,
+                                    "TFLOP/s": 2.0 * len(rows) * m.vocab * m.d_model / ms / 1e9}
+    names = [k for k in ("wq", "wk", "wv", "wo", "wg", "wu", "wd")]
+    n_el = sum(it.w[k].numel() for k in names)
+    st = {k: (it.w[k].float().clone(), torch.zeros_like(it.grads[k]), torch.zeros_like(it.grads[k])) for k in names}
+    def step(t):
+        for k in names:
+            master, mm, vv = st[k]
+            B.mace_adamw_step(it.h, it.w[k], master if it.w[k].dtype != torch.float32 else None, it.grads[k], mm, vv,
+                              1e-5, 0.9, 0.95, 1e-8, 0.0, t)
+    step(1)
+    e0, e1 = ev(), ev()
+    e0.record()
+    for r in range(reps):
+        step(2 + r)
+    e1.record(); torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    bpe = 4 * 3 + 4 * 2 + (4 + 4 + 2 + 2 if it.w["wq"].dtype != torch.float32 else 4 + 4) - (2 if it.w["wq"].dtype != torch.float32 else 0)
+    # per element: read g, m, v (12 B), write m, v (8 B); bf16 model: read master 4, write master 4 + param 2; fp32 model: read 4, write 4
+    res["adamw"] = {"elements": int(n_el), "ms": ms, "GB/s": n_el * bpe / ms / 1e6, "frac_of_8TB/s": n_el * bpe / ms / 1e6 / 8000.0}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -53,6 +98,9 @@ def main():
     ap.add_argument("--prefix", type=int, default=0,
                     help="give every prefill request a cached prefix of this many tokens (multiple of the block size; "
                          "groups of four requests share the blocks of one prefix node): prefix-shared prefill")
+    ap.add_argument("--extras", action="store_true",
+                    help="also time the loop-closing entry points (next-token logits of the inference rows' last tokens, "
+                         "AdamW over the layer's weights) and add them to the line as `extras`")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket launches with events")
     ap.add_argument("--calib-copy", action="store_true",
@@ -156,6 +204,8 @@ def main():
         out["kernel_tflops"] = {k: round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 1) for k, v in prof_all.items() if v["launches"] and v["flops"] > 0}
         out["kernel_gbps"] = {k: round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) for k, v in prof_all.items() if v["launches"] and v["bytes"] > 0}
         out["overlapped_classes"] = [k for k, v in prof_all.items() if v["side_launches"]]
+    if args.extras:
+        out["extras"] = time_extras(it, wl, torch, B)
     if not args.no_cpu_baseline and not big_cache:
         out["cpu_baseline"] = cpu_baseline(wl, lora)
     it.close()

@@ -205,6 +205,29 @@ int mace_dpo_logprob_loss(mace_handle_t h, const float *h_ft, const void *g_fina
                           float *dg_final, int accumulate, void *workspace, size_t workspace_bytes,
                           void *stream);
 
+/* Next-token logits of inference rows (decode rows, last row of a prefill request): what the
+ * serving loop samples from and checks for end of sequence (Section 4.2, CheckEnd).  Row row_idx[i]
+ * of y (device fp32 [*, d_model], the output of mace_hybrid_layer_fwd; row_idx device int32 [n],
+ * NULL = rows 0..n-1) goes through the final RMSNorm (g_final) and the tied head w_lm [vocab, d]:
+ * logits_out device fp32 [n, vocab] (required), next_token device int32 [n] (optional) = greedy
+ * arg max of the fp32 logits, lowest index on ties.  Plain bf16 operands (inference precision).
+ * Workspace: mace_workspace_bytes. */
+int mace_next_token_logits(mace_handle_t h, const float *y, const int32_t *row_idx, int32_t n, const void *g_final,
+                           const void *w_lm, float *logits_out, int32_t *next_token, void *workspace,
+                           size_t workspace_bytes, void *stream);
+
+/* AdamW step (decoupled weight decay) on one tensor of n elements: the optimizer step that turns
+ * the gradients of an iteration into the weights the next iteration sees (Section 2.1).  The paper
+ * names no optimizer; AdamW is the reading.  step counts from 1.
+ *   m <- b1 m + (1-b1) g ;  v <- b2 v + (1-b2) g^2
+ *   p <- p - lr * ( (m / (1-b1^step)) / (sqrt(v / (1-b2^step)) + eps) + weight_decay * p )
+ * param: device, the handle's io_dtype, updated in place.  master: optional device fp32 copy of the
+ * parameter; when given it is the value that is updated and param is its rounding (for bf16 models;
+ * without it a bf16 param is updated from its own rounded value).  grad, m, v device fp32.  All
+ * pointers 16-byte aligned. */
+int mace_adamw_step(mace_handle_t h, void *param, float *master, const float *grad, float *m, float *v, int64_t n,
+                    float lr, float beta1, float beta2, float eps, float weight_decay, int32_t step, void *stream);
+
 /* Cache-pruning statistics of Section 4.3 ("Decode KV cache pruning").
  * mace_head_norm_stats (device, elementwise over n requests x n_heads heads), given the norms of
  * this iteration (decode_head_norms of the forward):

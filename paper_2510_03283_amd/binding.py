@@ -19,7 +19,7 @@ EXPORTS = [
     "mace_create", "mace_destroy", "mace_last_error", "mace_fwd_saved_bytes", "mace_workspace_bytes",
     "mace_kv_slot_mapping", "mace_kv_cache_append", "mace_kv_cache_gather", "mace_hybrid_layer_fwd",
     "mace_hybrid_layer_bwd", "mace_hybrid_layer_fwd_lora", "mace_hybrid_layer_bwd_lora", "mace_dpo_logprob_loss",
-    "mace_head_norm_stats", "mace_kv_head_budget", "mace_profile_enable", "mace_profile_collect",
+    "mace_next_token_logits", "mace_adamw_step", "mace_head_norm_stats", "mace_kv_head_budget", "mace_profile_enable", "mace_profile_collect",
 ]
 
 
@@ -109,6 +109,10 @@ def load():
     lib.mace_hybrid_layer_bwd_lora.restype = C.c_int
     lib.mace_dpo_logprob_loss.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, f32, vp, vp, vp, vp, vp, vp, vp, vp, C.c_int, vp, sz, vp]
     lib.mace_dpo_logprob_loss.restype = C.c_int
+    lib.mace_next_token_logits.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.mace_next_token_logits.restype = C.c_int
+    lib.mace_adamw_step.argtypes = [vp, vp, vp, vp, vp, vp, i64, f32, f32, f32, f32, f32, i32, vp]
+    lib.mace_adamw_step.restype = C.c_int
     lib.mace_head_norm_stats.argtypes = [vp, vp, vp, i32, i32, vp, vp, i32, f32, vp, vp]
     lib.mace_head_norm_stats.restype = C.c_int
     lib.mace_kv_head_budget.argtypes = [vp, i32, i64, vp]
@@ -259,6 +263,17 @@ def mace_dpo_logprob_loss(h, h_ft, g_final, w_lm, token_ids, ft_seq_offsets, ft_
                                         _dev(loss_per_pair), _dev(loss_mean), _dev(clpd_out), _dev(win_out), _dev(dh_ft),
                                         _dev(dw_lm), _dev(dg_final), int(accumulate), _dev(workspace),
                                         workspace.numel() * workspace.element_size(), _stream(stream)), "mace_dpo_logprob_loss")
+
+
+def mace_next_token_logits(h, y, row_idx, n, g_final, w_lm, logits_out, next_token, workspace, stream=None):
+    _check(load().mace_next_token_logits(h, _dev(y), _dev(row_idx), int(n), _dev(g_final), _dev(w_lm), _dev(logits_out), _dev(next_token),
+                                         _dev(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
+           "mace_next_token_logits")
+
+
+def mace_adamw_step(h, param, master, grad, m, v, lr, beta1, beta2, eps, weight_decay, step, stream=None):
+    _check(load().mace_adamw_step(h, _dev(param), _dev(master), _dev(grad), _dev(m), _dev(v), param.numel(), float(lr), float(beta1),
+                                  float(beta2), float(eps), float(weight_decay), int(step), _stream(stream)), "mace_adamw_step")
 
 
 def mace_head_norm_stats(h, norms, t_count, abar, last_used=None, window=0, tau=0.0, prune=None, stream=None):

@@ -343,6 +343,17 @@ DpoWs plan_dpo(const Dims &D, size_t R, size_t n_seq, Bump &w) {
   return P;
 }
 
+// ---------------------------------------------------------------- next-token logits scratch
+struct LogitWs {
+  bf16_t *n_hi, *e_hi;
+};
+LogitWs plan_logits(const Dims &D, size_t n, Bump &w) {
+  LogitWs P;
+  P.n_hi = w.take<bf16_t>(n * D.d);
+  P.e_hi = D.bf ? nullptr : w.take<bf16_t>((size_t)D.V * D.d);
+  return P;
+}
+
 int run_gemm(mace_ctx *h, int LA, int LB, GemmParams &p, hipStream_t st, const char *where) {
   if (h->prof_on) {
     double mn = 0.0;
@@ -562,9 +573,60 @@ size_t mace_workspace_bytes(mace_handle_t h, int32_t n_tokens, int32_t n_ft_toke
   plan_bwd(D, (size_t)n_ft_tokens, b);
   plan_lora(D, (size_t)n_ft_tokens, true, b);
   plan_dpo(D, (size_t)n_loss_rows, 1u << 16, p);
+  Bump lg(nullptr);
+  plan_logits(D, (size_t)(n_tokens - n_ft_tokens), lg);
   size_t m = f.off > b.off ? f.off : b.off;
   m = m > p.off ? m : p.off;
+  m = m > lg.off ? m : lg.off;
   return align_up(m, 256) + 256;
+}
+
+int mace_next_token_logits(mace_handle_t h, const float *y, const int32_t *row_idx, int32_t n, const void *g_final, const void *w_lm,
+                           float *logits_out, int32_t *next_token, void *workspace, size_t workspace_bytes, void *stream) {
+  if (!h || !y || !g_final || !w_lm || !logits_out || n < 0) return fail(MACE_INVALID_ARG, "mace_next_token_logits: bad argument");
+  if (n == 0) return MACE_OK;
+  if (!workspace || ((uintptr_t)workspace & 255)) return fail(MACE_INVALID_ARG, "workspace must be non-null and 256-byte aligned");
+  const Dims D(h->m);
+  hipStream_t st = (hipStream_t)stream;
+  {
+    Bump m(nullptr);
+    plan_logits(D, (size_t)n, m);
+    if (m.off > workspace_bytes) return fail(MACE_WORKSPACE_TOO_SMALL, "next-token workspace too small");
+  }
+  Bump wsb(workspace);
+  LogitWs P = plan_logits(D, (size_t)n, wsb);
+  const bf16_t *e_hi = (const bf16_t *)w_lm;
+  if (!D.bf) {
+    prof_mark(h, st, T_MISC);
+    HIP_TRY(launch_split_f32((const float *)w_lm, (size_t)D.V * D.d, P.e_hi, nullptr, st), "split E");
+    e_hi = P.e_hi;
+  }
+  prof_mark(h, st, T_RMSNORM);
+  HIP_TRY(launch_rmsnorm_fwd(y, false, row_idx, g_final, D.bf, n, D.d, h->m.rms_eps, P.n_hi, nullptr, nullptr, st), "final rmsnorm");
+  {
+    GemmParams p = gp_init(D.d, D.d, D.d, D.V);
+    gp_group(p, P.n_hi, nullptr, logits_out, nullptr, n, 1);
+    gp_seg(p, e_hi, nullptr, D.V, 0);
+    TRY(run_gemm(h, 0, 0, p, st, "next-token logits gemm"));
+  }
+  if (next_token) {
+    prof_mark(h, st, T_MISC);
+    HIP_TRY(launch_argmax_rows(logits_out, n, D.V, next_token, st), "argmax");
+  }
+  prof_mark(h, st, -1);
+  return MACE_OK;
+}
+
+int mace_adamw_step(mace_handle_t h, void *param, float *master, const float *grad, float *m, float *v, int64_t n, float lr,
+                    float beta1, float beta2, float eps, float weight_decay, int32_t step, void *stream) {
+  if (!h || !param || !grad || !m || !v || n < 0) return fail(MACE_INVALID_ARG, "mace_adamw_step: bad argument");
+  if (step < 1) return fail(MACE_INVALID_ARG, "step counts from 1");
+  if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) || !(eps >= 0.f) || !std::isfinite(lr) || !std::isfinite(weight_decay))
+    return fail(MACE_INVALID_ARG, "AdamW hyper-parameters");
+  const double c1 = 1.0 / (1.0 - std::pow((double)beta1, (double)step)), c2 = 1.0 / (1.0 - std::pow((double)beta2, (double)step));
+  HIP_TRY(launch_adamw(param, h->m.io_dtype == MACE_BF16, master, grad, m, v, (size_t)n, lr, beta1, beta2, eps, weight_decay, (float)c1, (float)c2,
+                       (hipStream_t)stream), "adamw");
+  return MACE_OK;
 }
 
 int mace_head_norm_stats(mace_handle_t h, const float *norms, const int32_t *t_count, int32_t n, int32_t n_heads, float *abar,

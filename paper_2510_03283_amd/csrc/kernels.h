@@ -50,6 +50,14 @@ hipError_t launch_scale_split(const float *src, size_t n, float scale, bf16_t *h
 // dst[rows, cols] (+)= scale * the window of src (row pitch src_ld) that starts at (r0, c0).
 hipError_t launch_extract(const float *src, int src_ld, int r0, int c0, int rows, int cols, float scale, float *dst, int accumulate, hipStream_t st);
 
+// ---- loop.hip ---------------------------------------------------------------------------------
+// out[r] = arg max_j logits[r, j] (lowest index on ties), fp32 logits [rows, V].
+hipError_t launch_argmax_rows(const float *logits, int rows, int V, int32_t *out, hipStream_t st);
+// AdamW with decoupled weight decay on n elements; param in fp32 or bf16, master (nullable) the
+// fp32 copy that is updated and from which param is rounded; c1, c2 = 1/(1-b1^t), 1/(1-b2^t).
+hipError_t launch_adamw(void *param, bool param_bf16, float *master, const float *grad, float *m, float *v, size_t n, float lr,
+                        float b1, float b2, float eps, float wd, float c1, float c2, hipStream_t st);
+
 // ---- kv_cache.hip ----------------------------------------------------------------------------
 hipError_t launch_kv_append(void *cache_k, void *cache_v, bool bf16, long long num_slots, int block_size, int Hkv,
                             int hd, const void *k_new, const void *v_new, const int32_t *slot_mapping, int n,
