@@ -1,0 +1,111 @@
+"""The three 7B-class configurations at their FULL sizes, in the launch configuration bench.py
+times (whole batch in one call, cache drawn on the GPU), checked on sampled requests: requests are
+independent in the forward and in dx, so the oracle runs a sampled request alone and must
+reproduce that request's rows of the full-batch result.  Weight gradients are sums over all pairs
+and are covered by the request-subsampled tests instead."""
+import types
+
+import numpy as np
+import pytest
+
+from helpers import max_abs_norm_err, rel_fro_err
+from oracle import mace_oracle as O
+from paper_2510_03283_amd import synth
+from test_gpu_parity import TOL_GRAD, TOL_LOSS, TOL_OUT, torch_mod, weights_7b  # noqa: F401  (fixtures)
+
+pytestmark = pytest.mark.gpu
+
+
+def _ns(b, **kw):
+    base = dict(prefill_lens=np.zeros(0, np.int64), decode_ctx=np.zeros(0, np.int64), ft_lens=np.zeros(0, np.int64),
+                ft_prompt_lens=np.zeros(0, np.int64), block_size=b.block_size, prefill_block_tables=[],
+                decode_block_tables=np.zeros((0, 1), np.int32), token_ids=None)
+    base.update(kw)
+    return types.SimpleNamespace(**base)
+
+
+def _gather_ctx(cache, table, n, B):
+    rows = cache[np.asarray(table, np.int64)]                       # [nb, Hkv, B, hd] (torch, on the GPU)
+    rows = rows.permute(0, 2, 1, 3).reshape(-1, cache.shape[1], cache.shape[3])[:n]
+    return rows.float().cpu().numpy().astype(np.float64)
+
+
+def _run_full(torch, name, weights, prefill_ids, decode_ids, pair_ids, pair_backward):
+    from paper_2510_03283_amd.harness import DeviceIteration
+    wl = synth.make_workload(name, with_cache=False, weights=weights)
+    m, b = wl.dims, wl.batch
+    it = DeviceIteration(wl, device_cache_seed=wl.spec.seed)
+    try:
+        print(f"[{name} full] T={it.T} (prefill {it.Tp}, decode {it.Td}, ft {it.Tf}), loss rows {it.R}", flush=True)
+        B = b.block_size
+        ctx = {}
+        for j in decode_ids:                                       # cached rows as the GPU drew them: inputs, read back before the step
+            n = int(b.decode_ctx[j]); nb = -(-(n + 1) // B)
+            ctx[j] = (_gather_ctx(it.cache_k, b.decode_block_tables[j][:nb], n, B), _gather_ctx(it.cache_v, b.decode_block_tables[j][:nb], n, B))
+        it.step()
+        torch.cuda.synchronize()
+        y = it.y.cpu().numpy()
+        assert np.all(np.isfinite(y))
+        seg = b.seg_offsets
+        for i in prefill_ids:
+            o0, o1 = int(seg[i]), int(seg[i + 1]); L = o1 - o0
+            nb = -(-L // B)
+            sb = _ns(b, prefill_lens=np.array([L]), seg_offsets=np.array([0, L], np.int32), positions=b.positions[o0:o1],
+                     prefill_block_tables=[np.arange(nb, dtype=np.int32)])
+            ck = O.new_cache(nb, m.n_kv_heads, B, m.head_dim); cv = O.new_cache(nb, m.n_kv_heads, B, m.head_dim)
+            yo, _, _ = O.layer_forward(m, wl.weights, sb, wl.x[o0:o1], ck, cv)
+            e = max_abs_norm_err(y[o0:o1], yo)
+            print(f"[{name} full] prefill request {i} ({L} rows): {e:.2e}", flush=True)
+            assert e <= TOL_OUT
+            # its K, V rows reached the cache slots of the full batch
+            got = _gather_ctx(it.cache_k, b.prefill_block_tables[i], L, B)
+            want, _ = O.kv_gather(ck, np.arange(nb), L)
+            assert max_abs_norm_err(got, np.asarray(want)) <= TOL_OUT
+        for j in decode_ids:
+            t = int(seg[b.n_prefill + j]); n = int(b.decode_ctx[j]); nb = -(-(n + 1) // B)
+            sb = _ns(b, decode_ctx=np.array([n]), seg_offsets=np.array([0, 1], np.int32), positions=b.positions[t:t + 1],
+                     decode_block_tables=np.arange(nb, dtype=np.int32)[None, :])
+            ck = O.new_cache(nb, m.n_kv_heads, B, m.head_dim); cv = O.new_cache(nb, m.n_kv_heads, B, m.head_dim)
+            O.load_context(ck, sb.decode_block_tables, B, [ctx[j][0]]); O.load_context(cv, sb.decode_block_tables, B, [ctx[j][1]])
+            ex = {}
+            yo, _, _ = O.layer_forward(m, wl.weights, sb, wl.x[t:t + 1], ck, cv, extras=ex)
+            e = max_abs_norm_err(y[t:t + 1], yo)
+            en = max_abs_norm_err(it.head_norms[j].cpu().numpy(), ex["head_norms"][0])
+            print(f"[{name} full] decode request {j} (context {n}): y {e:.2e}, head norms {en:.2e}", flush=True)
+            assert e <= TOL_OUT and en <= TOL_OUT
+        base = b.n_prefill + b.n_decode
+        for p in pair_ids:
+            o0, o1, o2 = int(seg[base + 2 * p]), int(seg[base + 2 * p + 1]), int(seg[base + 2 * p + 2])
+            sb = _ns(b, ft_lens=b.ft_lens[2 * p:2 * p + 2], ft_prompt_lens=b.ft_prompt_lens[2 * p:2 * p + 2],
+                     seg_offsets=np.array([0, o1 - o0, o2 - o0], np.int32), positions=b.positions[o0:o2], token_ids=b.token_ids[o0:o2])
+            ck = O.new_cache(1, m.n_kv_heads, B, m.head_dim)
+            out = O.hybrid_iteration(m, wl.weights, sb, wl.x[o0:o2], ck, ck.copy(), wl.ref_logp[2 * p:2 * p + 2], wl.beta, backward=pair_backward)
+            e = max_abs_norm_err(y[o0:o2], out["y"])
+            lp = it.logp.cpu().numpy()[2 * p:2 * p + 2].astype(np.float64)
+            dl = abs(float(it.loss_pair.cpu().numpy()[p]) - out["head"]["loss_per_pair"][0])
+            print(f"[{name} full] pair {p} ({o2 - o0} rows): y {e:.2e}, |dloss| {dl:.2e}, max |dlogp| {np.abs(lp - out['head']['logp']).max():.2e}", flush=True)
+            assert e <= TOL_OUT and dl <= TOL_LOSS
+            if pair_backward:      # the pair alone has n_pairs = 1; in the batch its gradients carry 1 / n_pairs
+                scale = 1.0 / it.n_pairs
+                rows = slice(o0 - it.Ti, o2 - it.Ti)
+                for nm, a, w in (("dh", it.dh, out["dy_ft"]), ("dx", it.dx, out["dx_ft"])):
+                    e = rel_fro_err(a[rows].cpu().numpy(), w * scale)
+                    print(f"[{name} full] pair {p} {nm}: {e:.2e}", flush=True)
+                    assert e <= TOL_GRAD
+    finally:
+        it.close()
+
+
+def test_7b_full_size_sampled(torch_mod, weights_7b):
+    b = synth.make_batch(synth.CONFIGS["7b"])
+    _run_full(torch_mod, "7b", weights_7b, prefill_ids=[1], decode_ids=[int(np.argmax(b.decode_ctx))], pair_ids=[3], pair_backward=True)
+
+
+def test_7b_decode_full_size_sampled(torch_mod, weights_7b):
+    b = synth.make_batch(synth.CONFIGS["7b_decode"])
+    _run_full(torch_mod, "7b_decode", weights_7b, prefill_ids=[], decode_ids=[int(np.argmax(b.decode_ctx)), int(np.argmin(b.decode_ctx)), 100],
+              pair_ids=[1], pair_backward=True)
+
+
+def test_7b_ft_full_size_sampled(torch_mod, weights_7b):
+    _run_full(torch_mod, "7b_ft", weights_7b, prefill_ids=[0], decode_ids=[5], pair_ids=[17], pair_backward=False)
