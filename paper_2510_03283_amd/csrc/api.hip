@@ -151,8 +151,8 @@ int prepare_weights(const Dims &D, const mace_layer_w_t *w, Bump &ws, bool need_
 
 // ---------------------------------------------------------------- saved activations (ft rows)
 struct Saved {
-  float *rstd1, *rstd2, *lse, *x1, *gu;
-  bf16_t *a, *q, *k, *v, *o, *b;
+  float *rstd1, *rstd2, *lse, *x1;
+  bf16_t *a, *q, *k, *v, *o, *b, *gu;   // gu = [G | U] of the MLP, bf16
   bf16_t *tq, *to;   // adapter variant: scale * (a [A_q;A_k;A_v]^T) [Tf, 3*64] and scale * (o A_o^T) [Tf, 64]
 };
 constexpr int LR = 64;   // adapter rank as the GEMM sees it (zero-padded)
@@ -162,7 +162,7 @@ Saved plan_saved(const Dims &D, size_t Tf, Bump &s) {
   S.rstd2 = s.take<float>(Tf);
   S.lse = s.take<float>(Tf * D.Hq);
   S.x1 = s.take<float>(Tf * D.d);
-  S.gu = s.take<float>(Tf * 2 * D.F);
+  S.gu = s.take<bf16_t>(Tf * 2 * D.F);
   S.a = s.take<bf16_t>(Tf * D.d);
   S.q = s.take<bf16_t>(Tf * D.qd);
   S.k = s.take<bf16_t>(Tf * D.kd);
@@ -178,7 +178,7 @@ Saved plan_saved(const Dims &D, size_t Tf, Bump &s) {
 struct FwdWs {
   // inference rows
   bf16_t *a_i, *q_i, *k_i, *v_i, *o_i, *b_i, *hm_i;
-  float *qkv_i, *x1_i, *gu_i, *dec_partial;
+  float *qkv_i, *x1_i, *dec_partial;
   // fine-tune rows
   float *qkv_f;
   bf16_t *a_lo, *q_lo, *k_lo, *v_lo, *o_lo, *b_lo, *hm_hi, *hm_lo;
@@ -193,7 +193,6 @@ FwdWs plan_fwd(const Dims &D, size_t Ti, size_t Tf, int n_decode, int max_ctx, B
   F.o_i = w.take<bf16_t>(Ti * D.qd);
   F.x1_i = w.take<float>(Ti * D.d);
   F.b_i = w.take<bf16_t>(Ti * D.d);
-  F.gu_i = w.take<float>(Ti * 2 * D.F);
   F.hm_i = w.take<bf16_t>(Ti * D.F);
   F.dec_partial = w.take<float>(decode_partial_floats(n_decode, D.Hq, D.hd, max_ctx));
   F.qkv_f = w.take<float>(Tf * D.nqkv);
@@ -860,17 +859,17 @@ static int layer_fwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
   prof_mark(h, st, T_RMSNORM);
   HIP_TRY(launch_rmsnorm_fwd(S.x1, false, nullptr, w->g_mlp, D.bf, I.Tf, D.d, h->m.rms_eps, S.b, F.b_lo, S.rstd2, st), "rmsnorm2 ft");
   {
-    GemmParams p = gp_init(D.d, D.d, D.d, 2 * D.F);
-    gp_group(p, S.b, F.b_lo, S.gu, nullptr, I.Tf, np_ft);
-    gp_group(p, F.b_i, nullptr, F.gu_i, nullptr, I.Ti, 1);
+    // gate and up projections with SwiGLU in the epilogue: hm = silu(G) * U leaves the kernel as bf16
+    // (two terms for the fine-tune rows, whose G and U are kept as bf16 for the backward pass)
+    GemmParams p = gp_init(D.d, D.d, D.d, D.F);
+    p.swiglu = 1; p.out_bf16 = 1;
+    gp_group(p, S.b, F.b_lo, F.hm_hi, nullptr, I.Tf, np_ft);
+    if (I.Tf > 0) { p.mg[p.n_mg - 1].c_lo = F.hm_lo; p.mg[p.n_mg - 1].c_gu = S.gu; }
+    gp_group(p, F.b_i, nullptr, F.hm_i, nullptr, I.Ti, 1);
     gp_seg(p, W.hi[W_G], W.lo[W_G], D.F, 0);
     gp_seg(p, W.hi[W_U], W.lo[W_U], D.F, D.F);
     TRY(run_gemm(h, 0, 0, p, st, "gate/up gemm"));
   }
-  prof_mark(h, st, T_SWIGLU);
-  HIP_TRY(launch_swiglu_fwd(F.gu_i, I.Ti, D.F, F.hm_i, nullptr, st), "swiglu");
-  prof_mark(h, st, T_SWIGLU);
-  HIP_TRY(launch_swiglu_fwd(S.gu, I.Tf, D.F, F.hm_hi, F.hm_lo, st), "swiglu ft");
   {
     GemmParams p = gp_init(D.F, D.F, D.F, D.d);
     p.resid_kind = 1; p.ldr = D.d;

@@ -107,14 +107,24 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const float *dy, const
   }
 }
 
-// 32 columns per block; the 8 thread rows of a block stride over the partial rows, then reduce in LDS.
+// 32 columns per block; the 8 thread rows of a block stride over the partial rows with eight
+// independent loads in flight each (the kernel is latency-bound: a few MB spread over few blocks),
+// then reduce in LDS.  Fixed summation order: deterministic.
 __global__ __launch_bounds__(256) void colsum_kernel(const float *part, int n_part, int d, float *out, int accumulate) {
   __shared__ float red[8][33];
   const int c = threadIdx.x & 31, rg = threadIdx.x >> 5;
   const int j = blockIdx.x * 32 + c;
   float s = 0.f;
-  if (j < d)
-    for (int i = rg; i < n_part; i += 8) s += part[(size_t)i * d + j];
+  if (j < d) {
+    float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    int i = rg;
+    for (; i + 56 < n_part; i += 64) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) a[u] += part[(size_t)(i + 8 * u) * d + j];
+    }
+    for (; i < n_part; i += 8) a[0] += part[(size_t)i * d + j];
+    s = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
+  }
   red[rg][c] = s;
   __syncthreads();
   if (rg == 0 && j < d) {
@@ -214,25 +224,13 @@ __global__ __launch_bounds__(256) void rope_bwd_kernel(const float *dq, const fl
 }
 
 // ------------------------------------------------------------------ SwiGLU
-__global__ __launch_bounds__(256) void swiglu_fwd_kernel(const float *gu, int F, bf16_t *hm_hi, bf16_t *hm_lo) {
-  const int r = blockIdx.x;
-  const int k = 4 * (blockIdx.y * 256 + threadIdx.x);
-  if (k >= F) return;
-  float gv[4], uv[4], o[4];
-  ld4<false>(gu, (size_t)r * 2 * F + k, gv);
-  ld4<false>(gu, (size_t)r * 2 * F + F + k, uv);
-#pragma unroll
-  for (int j = 0; j < 4; ++j) o[j] = gv[j] / (1.0f + expf(-gv[j])) * uv[j];
-  st4_split(hm_hi, hm_lo, (size_t)r * F + k, o);
-}
-
-__global__ __launch_bounds__(256) void swiglu_bwd_kernel(const bf16_t *dhm, const float *gu, int F, bf16_t *dgu, bf16_t *hm) {
+__global__ __launch_bounds__(256) void swiglu_bwd_kernel(const bf16_t *dhm, const bf16_t *gu, int F, bf16_t *dgu, bf16_t *hm) {
   const int r = blockIdx.x;
   const int k = 4 * (blockIdx.y * 256 + threadIdx.x);
   if (k >= F) return;
   float gv[4], uv[4], dh[4], dg[4], du[4], h[4];
-  ld4<false>(gu, (size_t)r * 2 * F + k, gv);
-  ld4<false>(gu, (size_t)r * 2 * F + F + k, uv);
+  ld4<true>(gu, (size_t)r * 2 * F + k, gv);
+  ld4<true>(gu, (size_t)r * 2 * F + F + k, uv);
   ld4<true>(dhm, (size_t)r * F + k, dh);
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
@@ -326,13 +324,7 @@ hipError_t launch_rope_bwd(const float *dq, const float *dk, const float *dv, co
   return hipGetLastError();
 }
 
-hipError_t launch_swiglu_fwd(const float *gu, int rows, int F, bf16_t *hm_hi, bf16_t *hm_lo, hipStream_t st) {
-  if (rows <= 0) return hipSuccess;
-  hipLaunchKernelGGL(swiglu_fwd_kernel, dim3(rows, cdiv(F, 1024)), dim3(256), 0, st, gu, F, hm_hi, hm_lo);
-  return hipGetLastError();
-}
-
-hipError_t launch_swiglu_bwd(const bf16_t *dhm, const float *gu, int rows, int F, bf16_t *dgu, bf16_t *hm, hipStream_t st) {
+hipError_t launch_swiglu_bwd(const bf16_t *dhm, const bf16_t *gu, int rows, int F, bf16_t *dgu, bf16_t *hm, hipStream_t st) {
   if (rows <= 0) return hipSuccess;
   hipLaunchKernelGGL(swiglu_bwd_kernel, dim3(rows, cdiv(F, 1024)), dim3(256), 0, st, dhm, gu, F, dgu, hm);
   return hipGetLastError();

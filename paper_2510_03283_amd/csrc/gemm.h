@@ -19,6 +19,10 @@ struct GemmMGroup {
   const void *resid;    // first residual row of the group (may be null)
   int M;                // rows in the group
   int npass;            // 1: A0*B0   2: + A1*B0   3: + A0*B1
+  // SwiGLU mode only: c receives hm = silu(G) * U as bf16 [M, F]; c_lo (nullable) its second bf16
+  // term; c_gu (nullable) G and U as bf16 [M, 2F] (G in columns [0,F), U in [F,2F)).
+  void *c_lo;
+  void *c_gu;
 };
 struct GemmNSeg {
   const bf16_t *b[2];   // [0] = hi (or only) operand, [1] = lo term (pass 3)
@@ -40,6 +44,10 @@ struct GemmParams {
   int n_kseg;
   const bf16_t *kseg_b[3];
   int kseg_start[4];
+  // SwiGLU mode (NT form only): ns[0] = gate weights, ns[1] = up weights, both [F, K]; every wave
+  // multiplies 32 gate columns and the 32 up columns of the same hidden units, and the epilogue
+  // writes silu(G) * U instead of G and U (ldc = F).
+  int swiglu;
   int k_splits;     // > 1: grid.y slices of the k range; slice z writes fp32 partial sums at C + z * c_split_stride
   long long c_split_stride;   // elements
   int mt_start[4];  // filled by gemm_launch

@@ -75,6 +75,24 @@ struct DirectStage {
       __builtin_amdgcn_global_load_lds((gbl_void_t *)src, (lds_void_t *)(S + q * 512), 16, 0, 0);
     }
   }
+  // SwiGLU mode (LAYOUT 0): LDS rows [64 w, 64 w + 32) hold gate rows f0 + 32 w .. and rows
+  // [64 w + 32, 64 w + 64) the up rows of the same hidden units, so that the two 32-column MFMA
+  // tiles of wave column w are G and U of one unit range.
+  static __device__ __forceinline__ void issue_gu(const bf16_t *bg, const bf16_t *bu, long long ld, int f0, int F, int k0, bf16_t *S) {
+    static_assert(LAYOUT == 0, "gate/up interleaving is defined for k-contiguous weights");
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int q = wave + (NTHR / 64) * i;
+      const int chunk = q * 64 + lane;
+      const int lr = chunk / CPR, pos = chunk % CPR;
+      const int kc = pos ^ ((lr / RPB) % CPR);
+      const int f = f0 + (lr >> 6) * 32 + (lr & 31);
+      const bf16_t *src = ((lr >> 5) & 1 ? bu : bg) + (long long)f * ld + k0 + kc * 8;
+      if (f >= F) src = (const bf16_t *)&g_zero16;
+      __builtin_amdgcn_global_load_lds((gbl_void_t *)src, (lds_void_t *)(S + q * 512), 16, 0, 0);
+    }
+  }
   // per-lane fragment address pieces
   struct Frag { int base; int sw; };
   static __device__ __forceinline__ Frag frag_init(int r0, int lane) {
@@ -126,7 +144,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(const Gemm
   // that land on XCD x (block id % 8) take a contiguous chunk of the group's tile list, ordered in
   // bands of GROUP_M m-tiles, so the tiles resident on one XCD share A and B panels in its L2 and
   // every XCD gets the same mix of long and short tiles.
-  const int total_nt = p.nt_start[p.n_ns];
+  const int n_ns_eff = p.swiglu ? 1 : p.n_ns;      // SwiGLU mode: one logical column range of F hidden units
+  const int total_nt = p.nt_start[n_ns_eff];
   int g = 0, first_blk = 0;
   while (g + 1 < p.n_mg && (int)blockIdx.x >= first_blk + (p.mt_start[g + 1] - p.mt_start[g]) * total_nt) {
     first_blk += (p.mt_start[g + 1] - p.mt_start[g]) * total_nt;
@@ -147,10 +166,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(const Gemm
   const int gm = min(mtc - first_m, GROUP_M);
   const int mt_l = first_m + (v % grp_sz) % gm, nt_g = (v % grp_sz) / gm;
   int s = 0;
-  while (s + 1 < p.n_ns && nt_g >= p.nt_start[s + 1]) ++s;
+  while (s + 1 < n_ns_eff && nt_g >= p.nt_start[s + 1]) ++s;
   const GemmMGroup &G = p.mg[g];
   const GemmNSeg &S = p.ns[s];
-  const int m0 = mt_l * BM, n0 = (nt_g - p.nt_start[s]) * BN;
+  const int m0 = mt_l * BM, n0 = p.swiglu ? nt_g * (BN / 2) : (nt_g - p.nt_start[s]) * BN;
   const int M = G.M, N = S.N, K = p.K;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
@@ -177,6 +196,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(const Gemm
       int ks = 0;
       while (ks + 1 < p.n_kseg && kt * BKT >= p.kseg_start[ks + 1]) ++ks;
       SB::issue(p.kseg_b[ks], p.ldb, n0, N, kt * BKT - p.kseg_start[ks], p.kseg_start[ks + 1] - p.kseg_start[ks], st + SA::ELEMS);
+    } else if (p.swiglu) {
+      if constexpr (LB == 0) SB::issue_gu(p.ns[0].b[pass == 2 ? 1 : 0], p.ns[1].b[pass == 2 ? 1 : 0], p.ldb, n0, N, kt * BKT, st + SA::ELEMS);
     } else {
       SB::issue(S.b[pass == 2 ? 1 : 0], p.ldb, n0, N, kt * BKT, K, st + SA::ELEMS);
     }
@@ -228,9 +249,75 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(const Gemm
     st_cur = st_cur == NST - 1 ? 0 : st_cur + 1;
   }
 
-  // epilogue: accumulator register r of a 32x32 tile holds row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
+  // epilogue: accumulator register r of a 32x32 tile holds row 8*(r/4) + 4*(lane/32) + r%4, column lane%32.
+  // bf16 outputs are stored as packed pairs: neighbouring lanes (columns f, f+1) swap one value of
+  // a register pair (rows row, row+1), the even lane then stores columns (f, f+1) of row and the
+  // odd lane columns (f-1, f) of row+1 - one 4-byte store per lane instead of two 2-byte ones.
   const int rk = p.resid_kind, obf = p.out_bf16;
   const long long ldc = p.ldc, ldr = p.ldr;
+  const bool odd = lane & 1;
+  auto swap_pair = [&](float mine_r, float mine_r1) -> float {     // returns the partner's value for the row this lane stores
+    const float send = odd ? mine_r : mine_r1;
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(send), 0xB1, 0xF, 0xF, true));
+  };
+  if (p.swiglu) {
+    if constexpr (TN == 2 && LB == 0) {
+      const int f = n0 + wn * 32 + (lane & 31);
+      const int F = N;
+      bf16_t *hi = (bf16_t *)G.c, *lo = (bf16_t *)G.c_lo, *gu = (bf16_t *)G.c_gu;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int rbase = m0 + wm * WTM + i * 32 + 4 * (lane >> 5);
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) {
+          const int row0 = rbase + 8 * (r >> 2) + (r & 3);
+          float g2[2] = {acc[i][0][r], acc[i][0][r + 1]}, u2[2] = {acc[i][1][r], acc[i][1][r + 1]}, h2[2];
+#pragma unroll
+          for (int e = 0; e < 2; ++e) h2[e] = g2[e] / (1.0f + expf(-g2[e])) * u2[e];
+          const float hp = swap_pair(h2[0], h2[1]), gp = swap_pair(g2[0], g2[1]), up = swap_pair(u2[0], u2[1]);
+          const int row = row0 + (odd ? 1 : 0), fc = f - (odd ? 1 : 0);          // this lane stores (row, fc .. fc+1)
+          if (row < M && fc < F) {
+            const float ha = odd ? hp : h2[0], hb = odd ? h2[1] : hp;
+            uint32_t ph, pl;
+            split_pk_bf16(ha, hb, ph, pl);
+            *(uint32_t *)(hi + (long long)row * ldc + fc) = ph;
+            if (lo) *(uint32_t *)(lo + (long long)row * ldc + fc) = pl;
+            if (gu) {
+              *(uint32_t *)(gu + (long long)row * 2 * F + fc) = cvt_pk_bf16(odd ? gp : g2[0], odd ? g2[1] : gp);
+              *(uint32_t *)(gu + (long long)row * 2 * F + F + fc) = cvt_pk_bf16(odd ? up : u2[0], odd ? u2[1] : up);
+            }
+          }
+        }
+      }
+    }
+    return;
+  }
+  if (obf && !(N & 1) && !(S.c_col & 1)) {
+    // packed bf16 path (every lane takes part in the swap, also those beyond the matrix edge)
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int col = n0 + wn * WTN + j * 32 + (lane & 31);
+        const int rbase = m0 + wm * WTM + i * 32 + 4 * (lane >> 5);
+        const long long cc = S.c_col + col;
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) {
+          const int row0 = rbase + 8 * (r >> 2) + (r & 3);
+          float va = acc[i][j][r], vb = acc[i][j][r + 1];
+          if (rk && col < N) {
+            if (row0 < M) va += rk == 1 ? ((const float *)G.resid)[row0 * ldr + cc] : bf2f(((const bf16_t *)G.resid)[row0 * ldr + cc]);
+            if (row0 + 1 < M) vb += rk == 1 ? ((const float *)G.resid)[(row0 + 1) * ldr + cc] : bf2f(((const bf16_t *)G.resid)[(row0 + 1) * ldr + cc]);
+          }
+          const float vp = swap_pair(va, vb);
+          const int row = row0 + (odd ? 1 : 0);
+          if (row < M && col - (odd ? 1 : 0) < N)
+            *(uint32_t *)((bf16_t *)G.c + row * ldc + cc - (odd ? 1 : 0)) = cvt_pk_bf16(odd ? vp : va, odd ? vb : vp);
+        }
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -259,6 +346,12 @@ int count_tiles(GemmParams &p) {
   int mt = 0, nt = 0;
   for (int g = 0; g < p.n_mg; ++g) { p.mt_start[g] = mt; mt += cdiv(p.mg[g].M, BM); }
   p.mt_start[p.n_mg] = mt;
+  if (p.swiglu) {
+    p.nt_start[0] = 0;
+    nt = cdiv(p.ns[0].N, BN / 2);
+    p.nt_start[1] = nt;
+    return mt * nt;
+  }
   for (int s = 0; s < p.n_ns; ++s) { p.nt_start[s] = nt; nt += cdiv(p.ns[s].N, BN); }
   p.nt_start[p.n_ns] = nt;
   return mt * nt;
@@ -342,6 +435,13 @@ hipError_t gemm_launch(int LA, int LB, GemmParams &p, hipStream_t stream, const 
     const GemmNSeg &S = p.ns[s];
     if (S.N <= 0 || !S.b[0] || !aligned16(S.b[0]) || (S.b[1] && !aligned16(S.b[1]))) { *why = "gemm: bad column segment"; return hipErrorInvalidValue; }
     if (LB == 1 && S.N % 8) { *why = "gemm: N of an n-contiguous operand must be a multiple of 8"; return hipErrorInvalidValue; }
+  }
+  if (p.out_bf16 && p.ldc % 2) { *why = "gemm: bf16 output needs an even leading dimension"; return hipErrorInvalidValue; }
+  if (p.swiglu) {
+    if (LA != 0 || LB != 0 || p.n_ns != 2 || p.ns[0].N != p.ns[1].N || p.ns[0].N % 2 || p.k_splits > 1 || p.resid_kind || p.n_kseg > 1 || p.ldc % 2) {
+      *why = "gemm: SwiGLU mode needs the NT form, two equal column segments and a plain bf16 output";
+      return hipErrorInvalidValue;
+    }
   }
   if (p.n_kseg > 1) {
     if (p.n_kseg > 3 || p.n_ns != 1 || p.kseg_start[0] != 0 || p.kseg_start[p.n_kseg] != p.K) { *why = "gemm: bad k segments"; return hipErrorInvalidValue; }
