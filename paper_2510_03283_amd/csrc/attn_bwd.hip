@@ -40,7 +40,7 @@ __global__ __launch_bounds__(256) void attn_dvec_kernel(const bf16_t *__restrict
 
 // ------------------------------------------------------------------ dQ
 template <int HD>
-__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
                                                           const bf16_t *__restrict__ v, const bf16_t *__restrict__ d_o,
                                                           const float *__restrict__ lse, const float *__restrict__ dvec,
                                                           const int32_t *__restrict__ seg, int row_base, int Hq, int Hkv,
@@ -149,7 +149,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16_t *__restri
 
 // ------------------------------------------------------------------ dK, dV
 template <int HD>
-__global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
+__global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
                                                             const bf16_t *__restrict__ v, const bf16_t *__restrict__ d_o,
                                                             const float *__restrict__ lse, const float *__restrict__ dvec,
                                                             const int32_t *__restrict__ seg, int row_base, int Hq,

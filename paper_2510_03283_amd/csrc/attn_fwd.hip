@@ -31,7 +31,7 @@ struct PagedKV {
 };
 
 template <int HD, bool SPLIT, int NW, bool PAGED>
-__global__ __launch_bounds__(64 * NW) void attn_fwd_kernel(const bf16_t *__restrict__ q_hi, const bf16_t *__restrict__ k_hi,
+__global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_fwd_kernel(const bf16_t *__restrict__ q_hi, const bf16_t *__restrict__ k_hi,
                                                            const bf16_t *__restrict__ v_hi, const bf16_t *__restrict__ q_lo,
                                                            const bf16_t *__restrict__ k_lo, const bf16_t *__restrict__ v_lo,
                                                            const int32_t *__restrict__ seg, int row_base, int Hq, int Hkv,
