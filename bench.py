@@ -22,7 +22,7 @@ PEAK_HBM_GBS = 8000.0
 # rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, scaled by a plain copy, bytes per launch averaged over one step's
 # launches of the class: (workload, kernel class) -> bytes.  Source: profiles/bench_edge_gemm_nt_hbm_traffic.md
 # and profiles/bench_7b_decode_attn_decode_hbm_traffic.md.  Not measured -> null.
-TRAFFIC_BYTES_PER_LAUNCH = {("edge", "gemm_nt"): 6.561e8, ("7b_decode", "attn_decode"): 2.2127e10}
+TRAFFIC_BYTES_PER_LAUNCH = {("edge", "gemm_nt"): 6.409e8, ("7b_decode", "attn_decode"): 2.2127e10}
 
 
 def cpu_baseline(wl, lora=None):
