@@ -3,7 +3,11 @@
 
 A step = forward of all rows (prefill + decode + fine-tune), DPO head forward and backward, and
 the layer backward of the fine-tune rows, over one synthetic mixed batch that is resident in HBM.
-Prints ONE JSON line; see the design doc for the meaning of every field."""
+Prints ONE JSON line: value = rows of the batch per second over the timed steps; roofline = the
+kernel class with the largest summed time among those that run alone, timed with HIP events that
+the library records on the launch stream (achieved = algorithmic flops or bytes / time, against the
+MI355X peak); kernel_* = per-class figures of an untimed pass in which every launch is bracketed;
+cpu_baseline = the fp64 oracle timed once on the same workload on the host cores."""
 from __future__ import annotations
 
 import argparse
@@ -20,8 +24,8 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
 PEAK_HBM_GBS = 8000.0
 
 # rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, scaled by a plain copy, bytes per launch averaged over one step's
-# launches of the class: (workload, kernel class) -> bytes.  Source: profiles/bench_edge_gemm_nt_hbm_traffic.md
-# and profiles/bench_7b_decode_attn_decode_hbm_traffic.md.  Not measured -> null.
+# launches of the class: (workload, kernel class) -> bytes, from the two committed counter summaries
+# (edge GEMM NT class, decode-heavy attention).  Not measured -> null.
 TRAFFIC_BYTES_PER_LAUNCH = {("edge", "gemm_nt"): 6.409e8, ("7b_decode", "attn_decode"): 2.2127e10}
 
 
