@@ -279,7 +279,8 @@ hipError_t launch_t(const bf16_t *q, const bf16_t *k, const bf16_t *v, const bf1
                     int Hkv, float *dvec, float *dq, float *dk, float *dv, hipStream_t st) {
   constexpr size_t lds_q = (size_t)2 * (2 * TB * HD) * sizeof(bf16_t);
   constexpr size_t lds_k = (size_t)2 * (2 * TB * HD + 4 * TB) * sizeof(bf16_t);
-  static bool attr_done = false;
+  static bool attr_flags[16] = {};
+  bool &attr_done = device_once(attr_flags);
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute((const void *)attn_bwd_dq_kernel<HD>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_q);
     if (e != hipSuccess) return e;

@@ -218,7 +218,8 @@ hipError_t launch_t(const bf16_t *q_hi, const bf16_t *k_hi, const bf16_t *v_hi, 
                     bf16_t *o_hi, bf16_t *o_lo, float *lse, hipStream_t st, const PagedKV pg = PagedKV{}) {
   constexpr int NT = SPLIT ? 2 : 1;
   constexpr size_t lds = (size_t)2 * 2 * NT * KB * HD * sizeof(bf16_t);
-  static bool attr_done = false;
+  static bool attr_flags[16] = {};
+  bool &attr_done = device_once(attr_flags);
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute((const void *)attn_fwd_kernel<HD, SPLIT, NW, PAGED>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;

@@ -92,5 +92,16 @@ __device__ __forceinline__ float block_max(float v, float *red) {
   return t;
 }
 
+// Per-device "done once" flag for launch attributes that HIP keeps per device (dynamic LDS limit).
+// Returns the flag of the current device; for a device beyond the table the flag always reads
+// false, which only costs a repeated (idempotent) attribute call.
+static inline bool &device_once(bool (&flags)[16]) {
+  static thread_local bool never;
+  never = false;
+  int dev = 0;
+  (void)hipGetDevice(&dev);
+  return dev >= 0 && dev < 16 ? flags[dev] : never;
+}
+
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline int cdiv(int a, int b) { return (a + b - 1) / b; }

@@ -364,7 +364,8 @@ hipError_t launch_dl(GemmParams &p, hipStream_t stream) {
   constexpr int NTHR = 64 * WGM * WGN;
   constexpr size_t lds = (size_t)NST * (BM + BN) * BKT * sizeof(bf16_t);
   static_assert(lds <= 160 * 1024, "LDS budget of a gfx950 CU");
-  static bool attr_done = false;
+  static bool attr_flags[16] = {};
+  bool &attr_done = device_once(attr_flags);
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute((const void *)gemm_bf16_dl_kernel<BM, BN, WGM, WGN, LA, LB, BKT, NST>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
