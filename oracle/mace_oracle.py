@@ -28,7 +28,9 @@ central finite differences on adapter entries; for the pruning statistics: a one
 hand-worked capacity splits and their invariants; for prefix-shared prefill: zero prefix ==
 plain causal attention, the tail rows of a one-piece prefill of the whole sequence, two
 requests sharing the blocks of one prefix, brute force; for the optimizer step: the first-step
-closed form, zero gradient, and torch.optim.AdamW on the CPU.  The paper
+closed form, zero gradient, and torch.optim.AdamW on the CPU; for the shared-prompt layout of
+a pair: losses, log-probabilities and every weight gradient equal those of the two-sequence
+layout, and dx of a prompt row is the sum of its two copies.  The paper
 prints no worked numerical example for this path, so absolute values of the benchmark
 configurations are pinned by these invariants only.
 """
@@ -120,16 +122,22 @@ def kv_gather(cache, block_table, ctx_len):
 
 # --------------------------------------------------------------------------- attention
 
-def causal_attention(q, k, v):
+def causal_attention(q, k, v, excl=None):
     """Exact causal attention of one sequence.  q[L, Hq, hd], k, v[L, Hkv, hd].
     Query head h uses kv head h // (Hq/Hkv).  Returns o[L, Hq, hd], lse[L, Hq] and the
-    probabilities P[Hq, L, L] (kept for the hand-written backward)."""
+    probabilities P[Hq, L, L] (kept for the hand-written backward).
+    excl = (lo, hi), optional: rows >= hi do not see keys lo .. hi-1.  With the rows of a preference
+    pair laid out as prompt | chosen response | rejected response and (lo, hi) = the chosen
+    response, both responses attend to ONE copy of the prompt and not to each other."""
     L, Hq, hd = q.shape
     grp = Hq // k.shape[1]
     o = np.empty((L, Hq, hd), F64)
     lse = np.empty((L, Hq), F64)
     P = np.zeros((Hq, L, L), F64)
     mask = np.tril(np.ones((L, L), dtype=bool))
+    if excl is not None:
+        lo, hi = int(excl[0]), int(excl[1])
+        mask[hi:, lo:hi] = False
     for h in range(Hq):
         kh, vh = k[:, h // grp, :], v[:, h // grp, :]
         s = (q[:, h, :] @ kh.T) / np.sqrt(F64(hd))
@@ -310,7 +318,11 @@ def layer_forward(dims, W, batch, x, cache_k, cache_v, lora=None, extras=None):
         o0, o1 = seg[npf + nd + s], seg[npf + nd + s + 1]
         pos = np.asarray(batch.positions[o0:o1])
         a, r1, q, k, v = project_qkv(dims, W, x[o0:o1], pos, lora)
-        o, lse, P = causal_attention(q, k, v)
+        chosen = getattr(batch, "ft_chosen_lens", None)       # shared-prompt layout: prompt | chosen | rejected
+        excl = None
+        if chosen is not None:
+            excl = (int(batch.ft_prompt_lens[s]), int(batch.ft_prompt_lens[s]) + int(chosen[s]))
+        o, lse, P = causal_attention(q, k, v, excl)
         y[o0:o1], sv = mlp_block(dims, W, x[o0:o1], o.reshape(o1 - o0, -1), lora)
         sv.update(x=x[o0:o1], a=a, r1=r1, q=q, k=k, v=v, o=o, lse=lse, P=P, pos=pos)
         saved.append(sv)
@@ -422,6 +434,49 @@ def dpo_head_forward(dims, W, batch, y_ft_list, ref_logp, beta):
     logp = np.array(logp, F64)
     loss, loss_mean, clpd, win, z, dlogp = dpo_pair_loss(logp, ref_logp, beta)
     return dict(logp=logp, loss_per_pair=loss, loss_mean=loss_mean, clpd=clpd, win=win, z=z, dlogp=dlogp, saved=saved)
+
+
+def rows_logprob(dims, W, y_seq, rows, labels):
+    """Sum over the given rows of log softmax(E RMSNorm(y_row))[label]: sequence_logprob with the
+    rows and their next tokens listed explicitly."""
+    rows, labels = np.asarray(rows, np.int64), np.asarray(labels, np.int64)
+    n, rf = rmsnorm(y_seq[rows], _w(W, "gf"), dims.rms_eps)
+    logits = n @ _w(W, "E").T
+    lse = logsumexp(logits, axis=1)
+    logp_t = logits[np.arange(len(rows)), labels] - lse
+    return float(np.sum(logp_t)), dict(rows=rows, n=n, rf=rf, logits=logits, lse=lse, labels=labels, logp_t=logp_t)
+
+
+def dpo_head_forward_shared(dims, W, batch, y_ft_list, ref_logp, beta):
+    """DPO head when a pair is stored once as prompt | chosen response | rejected response (the
+    prompt rows are shared).  The first token of either response is predicted by the LAST PROMPT
+    row, the others by the response rows before them; everything else is dpo_head_forward.
+    Sequence numbering of logp / ref_logp stays 2i = chosen, 2i+1 = rejected."""
+    seg = np.asarray(batch.seg_offsets, dtype=np.int64)
+    base = len(batch.prefill_lens) + len(batch.decode_ctx)
+    logp, saved = [], []
+    for i, y_seq in enumerate(y_ft_list):
+        y_seq = np.asarray(y_seq, F64)
+        ids = np.asarray(batch.token_ids[seg[base + i]:seg[base + i + 1]])
+        P, Rc = int(batch.ft_prompt_lens[i]), int(batch.ft_chosen_lens[i])
+        L = y_seq.shape[0]
+        Rr = L - P - Rc
+        for start, R in ((P, Rc), (P + Rc, Rr)):
+            rows = np.concatenate([[P - 1], np.arange(start, start + R - 1)])
+            lp, sv = rows_logprob(dims, W, y_seq, rows, ids[start:start + R])
+            sv["y"], sv["pair"] = y_seq, i
+            logp.append(lp)
+            saved.append(sv)
+    logp = np.array(logp, F64)
+    loss, loss_mean, clpd, win, z, dlogp = dpo_pair_loss(logp, ref_logp, beta)
+    return dict(logp=logp, loss_per_pair=loss, loss_mean=loss_mean, clpd=clpd, win=win, z=z, dlogp=dlogp, saved=saved)
+
+
+def dpo_head_backward_shared(dims, W, head, n_pairs):
+    """dpo_head_backward for the shared-prompt layout: the two sequences of a pair scatter into the
+    rows of one stored pair, and the last prompt row receives the gradient of both."""
+    dys_seq, dE, dgf = dpo_head_backward(dims, W, head)
+    return [dys_seq[2 * i] + dys_seq[2 * i + 1] for i in range(n_pairs)], dE, dgf
 
 
 def dpo_head_backward(dims, W, head):
@@ -564,10 +619,11 @@ def hybrid_iteration(dims, W, batch, x, cache_k, cache_v, ref_logp, beta, backwa
     seg = np.asarray(batch.seg_offsets, dtype=np.int64)
     base = len(batch.prefill_lens) + len(batch.decode_ctx)
     y_ft = [y[seg[base + s]:seg[base + s + 1]] for s in range(len(batch.ft_lens))]
-    head = dpo_head_forward(dims, W, batch, y_ft, ref_logp, beta)
+    shared = getattr(batch, "ft_chosen_lens", None) is not None
+    head = (dpo_head_forward_shared if shared else dpo_head_forward)(dims, W, batch, y_ft, ref_logp, beta)
     out = dict(y=y, slots=slots, head=head, saved=saved)
     if backward:
-        dys, dE, dgf = dpo_head_backward(dims, W, head)
+        dys, dE, dgf = dpo_head_backward_shared(dims, W, head, len(y_ft)) if shared else dpo_head_backward(dims, W, head)
         if lora is not None:
             dxs, grads = layer_backward_lora(dims, W, lora, saved, dys)
         else:

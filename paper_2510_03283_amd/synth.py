@@ -154,6 +154,8 @@ class Batch:
     decode_block_tables: np.ndarray          # [n_decode, max_blocks_per_req] int32, -1 padded
     max_blocks_per_req: int
     prefill_prefix_lens: Optional[np.ndarray] = None   # [n_prefill] cached prefix tokens, None = no prefix anywhere
+    ft_chosen_lens: Optional[np.ndarray] = None        # shared-prompt layout: one stored sequence per pair,
+                                                       # prompt | chosen response | rejected response; [n_pairs] chosen lengths
 
     @property
     def n_prefill(self): return len(self.prefill_lens)
@@ -341,6 +343,35 @@ def make_workload(name: str, n_prefill=None, n_decode=None, n_pairs=None, with_c
     ck, cv = make_cached_context(spec, b) if with_cache else (None, None)
     pk, pv = make_cached_prefix(spec, b) if (with_cache and b.prefill_prefix_lens is not None) else (None, None)
     return Workload(spec, spec.dims, w, b, x, ck, cv, make_ref_logp(spec, b), spec.beta, pk, pv)
+
+
+def to_shared_prompt(wl: Workload) -> Workload:
+    """The same workload with every preference pair stored once as prompt | chosen response |
+    rejected response (the two sequences of a pair share their prompt tokens, so nothing is lost):
+    same tokens, same positions (both responses start at position P), same ref_logp, 2 P + Rc + Rr
+    rows per pair become P + Rc + Rr."""
+    b = wl.batch
+    base = b.n_prefill + b.n_decode
+    n_pairs = b.n_ft_seq // 2
+    seg = b.seg_offsets
+    Ti = int(seg[base])
+    rows, pos, lens, chosen, prompts = [], [], [], [], []
+    for i in range(n_pairs):
+        o0, o1, o2 = int(seg[base + 2 * i]), int(seg[base + 2 * i + 1]), int(seg[base + 2 * i + 2])
+        P = int(b.ft_prompt_lens[2 * i])
+        assert P == int(b.ft_prompt_lens[2 * i + 1]) and np.array_equal(b.token_ids[o0:o0 + P], b.token_ids[o1:o1 + P])
+        rows += list(range(o0, o1)) + list(range(o1 + P, o2))
+        Rc, Rr = o1 - o0 - P, o2 - o1 - P
+        pos += list(range(P + Rc)) + list(range(P, P + Rr))
+        lens.append(P + Rc + Rr); chosen.append(Rc); prompts.append(P)
+    rows = np.array(rows, dtype=np.int64)
+    keep = np.concatenate([np.arange(Ti), rows])
+    ft_lens = np.array(lens, dtype=np.int64)
+    seg_new = np.concatenate([seg[:base + 1], Ti + np.cumsum(ft_lens)]).astype(np.int32)
+    nb = dataclasses.replace(b, ft_lens=ft_lens, ft_prompt_lens=np.array(prompts, dtype=np.int64), seg_offsets=seg_new,
+                             positions=np.concatenate([b.positions[:Ti], np.array(pos, dtype=np.int32)]).astype(np.int32),
+                             token_ids=b.token_ids[keep], ft_chosen_lens=np.array(chosen, dtype=np.int64))
+    return dataclasses.replace(wl, batch=nb, x=wl.x[keep])
 
 
 def make_upstream_grad(spec: ConfigSpec, n_rows: int, scale: float = 1e-3) -> np.ndarray:
