@@ -95,6 +95,14 @@ typedef struct {
   const int32_t *prefill_prefix_lens_host;  /* host   [n_prefill] */
   const int32_t *prefill_prefix_lens;       /* device copy of the same array */
   int32_t max_blocks_per_prefill;
+  /* Shared-prompt preference pairs (the exact optimisation of the DPO forward/backward: a pair
+   * (x, y+, y-) of Section 3.1 stored ONCE as the rows  prompt | chosen response | rejected response,
+   * positions 0..P-1 | P.. | P..).  Fine-tune sequence s is then one pair; its rows at or beyond
+   * ft_excl_hi[s] (the rejected response) do not attend to rows ft_excl_lo[s] .. ft_excl_hi[s]-1
+   * (the chosen response); everything else is causal over the stored order.  Device int32
+   * [n_ft_seq], row numbers relative to the sequence start; both NULL = ordinary sequences.
+   * mace_dpo_logprob_loss_shared is the matching head. */
+  const int32_t *ft_excl_lo, *ft_excl_hi;
   float *decode_head_norms;        /* optional OUTPUT, device fp32 [n_decode, n_q_heads]: L2 norm of every head's attention
                                       output vector of each decode row (before the output projection) - the signal of the
                                       norm-based cache pruning of Section 4.3; NULL = not wanted */
@@ -204,6 +212,22 @@ int mace_dpo_logprob_loss(mace_handle_t h, const float *h_ft, const void *g_fina
                           float *clpd_out, int32_t *win_out, float *dh_ft, float *dw_lm,
                           float *dg_final, int accumulate, void *workspace, size_t workspace_bytes,
                           void *stream);
+
+/* The same head for shared-prompt pairs (see mace_batch_t.ft_excl_lo): pair_offsets [n_pairs+1],
+ * prompt_lens [n_pairs] and chosen_lens [n_pairs] (each as device and host array) describe stored
+ * pair i = prompt (P_i rows) | chosen response (Rc_i rows) | rejected response.  The first token of
+ * either response is predicted by the last prompt row, which therefore receives the gradient of
+ * both.  logp_out / ref_logp keep the numbering 2i = chosen, 2i+1 = rejected; h_ft, dh_ft are
+ * [sum of stored rows, d_model].  All other arguments as in mace_dpo_logprob_loss. */
+int mace_dpo_logprob_loss_shared(mace_handle_t h, const float *h_ft, const void *g_final, const void *w_lm,
+                                 const int32_t *token_ids, const int32_t *pair_offsets,
+                                 const int32_t *pair_offsets_host, const int32_t *prompt_lens,
+                                 const int32_t *prompt_lens_host, const int32_t *chosen_lens,
+                                 const int32_t *chosen_lens_host, int32_t n_pairs, const float *ref_logp,
+                                 float beta, float *logp_out, float *loss_per_pair, float *loss_mean,
+                                 float *clpd_out, int32_t *win_out, float *dh_ft, float *dw_lm,
+                                 float *dg_final, int accumulate, void *workspace, size_t workspace_bytes,
+                                 void *stream);
 
 /* Next-token logits of inference rows (decode rows, last row of a prefill request): what the
  * serving loop samples from and checks for end of sequence (Section 4.2, CheckEnd).  Row row_idx[i]

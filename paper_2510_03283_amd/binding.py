@@ -18,7 +18,7 @@ MACE_F32, MACE_BF16 = 0, 1
 EXPORTS = [
     "mace_create", "mace_destroy", "mace_last_error", "mace_fwd_saved_bytes", "mace_workspace_bytes",
     "mace_kv_slot_mapping", "mace_kv_cache_append", "mace_kv_cache_gather", "mace_hybrid_layer_fwd",
-    "mace_hybrid_layer_bwd", "mace_hybrid_layer_fwd_lora", "mace_hybrid_layer_bwd_lora", "mace_dpo_logprob_loss",
+    "mace_hybrid_layer_bwd", "mace_hybrid_layer_fwd_lora", "mace_hybrid_layer_bwd_lora", "mace_dpo_logprob_loss", "mace_dpo_logprob_loss_shared",
     "mace_next_token_logits", "mace_adamw_step", "mace_head_norm_stats", "mace_kv_head_budget", "mace_profile_enable", "mace_profile_collect",
 ]
 
@@ -62,7 +62,7 @@ class BatchT(C.Structure):
                 ("slot_mapping", C.c_void_p), ("block_tables", C.c_void_p), ("context_lens_host", C.c_void_p),
                 ("context_lens", C.c_void_p), ("max_blocks_per_req", C.c_int32), ("prefill_block_tables", C.c_void_p),
                 ("prefill_prefix_lens_host", C.c_void_p), ("prefill_prefix_lens", C.c_void_p), ("max_blocks_per_prefill", C.c_int32),
-                ("decode_head_norms", C.c_void_p)]
+                ("ft_excl_lo", C.c_void_p), ("ft_excl_hi", C.c_void_p), ("decode_head_norms", C.c_void_p)]
 
 
 class ProfileEntryT(C.Structure):
@@ -117,6 +117,8 @@ def load():
     lib.mace_head_norm_stats.restype = C.c_int
     lib.mace_kv_head_budget.argtypes = [vp, i32, i64, vp]
     lib.mace_kv_head_budget.restype = C.c_int
+    lib.mace_dpo_logprob_loss_shared.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, f32, vp, vp, vp, vp, vp, vp, vp, vp, C.c_int, vp, sz, vp]
+    lib.mace_dpo_logprob_loss_shared.restype = C.c_int
     lib.mace_profile_enable.argtypes = [vp, C.c_int]
     lib.mace_profile_enable.restype = C.c_int
     lib.mace_profile_collect.argtypes = [vp, C.POINTER(ProfileEntryT), i32, C.POINTER(i32)]
@@ -203,18 +205,20 @@ class BatchDesc:
 
     def __init__(self, n_prefill, n_decode, n_ft_seq, n_tokens, seg_offsets_host, seg_offsets, positions,
                  slot_mapping, block_tables, context_lens_host, context_lens, max_blocks_per_req, decode_head_norms=None,
-                 prefill_block_tables=None, prefill_prefix_lens_host=None, prefill_prefix_lens=None, max_blocks_per_prefill=0):
+                 prefill_block_tables=None, prefill_prefix_lens_host=None, prefill_prefix_lens=None, max_blocks_per_prefill=0,
+                 ft_excl_lo=None, ft_excl_hi=None):
         self._seg, segp = _host_i32(seg_offsets_host)
         self._ctx, ctxp = _host_i32(context_lens_host)
         self._keep = (seg_offsets, positions, slot_mapping, block_tables, context_lens, decode_head_norms,
-                      prefill_block_tables, prefill_prefix_lens)
+                      prefill_block_tables, prefill_prefix_lens, ft_excl_lo, ft_excl_hi)
         pfxp = None
         if prefill_prefix_lens_host is not None:
             self._pfx, pfxp = _host_i32(prefill_prefix_lens_host)
         self.struct = BatchT(n_prefill, n_decode, n_ft_seq, n_tokens, segp, _dev(seg_offsets), _dev(positions),
                              _dev(slot_mapping), _dev(block_tables), ctxp if n_decode else None,
                              _dev(context_lens), max_blocks_per_req, _dev(prefill_block_tables), pfxp,
-                             _dev(prefill_prefix_lens), max_blocks_per_prefill, _dev(decode_head_norms))
+                             _dev(prefill_prefix_lens), max_blocks_per_prefill, _dev(ft_excl_lo), _dev(ft_excl_hi),
+                             _dev(decode_head_norms))
 
 
 def mace_hybrid_layer_fwd(h, w: LayerWT, batch: BatchDesc, cache: Optional[KvCacheT], x, y, saved, workspace, stream=None):
@@ -263,6 +267,20 @@ def mace_dpo_logprob_loss(h, h_ft, g_final, w_lm, token_ids, ft_seq_offsets, ft_
                                         _dev(loss_per_pair), _dev(loss_mean), _dev(clpd_out), _dev(win_out), _dev(dh_ft),
                                         _dev(dw_lm), _dev(dg_final), int(accumulate), _dev(workspace),
                                         workspace.numel() * workspace.element_size(), _stream(stream)), "mace_dpo_logprob_loss")
+
+
+def mace_dpo_logprob_loss_shared(h, h_ft, g_final, w_lm, token_ids, pair_offsets, pair_offsets_host, prompt_lens, prompt_lens_host,
+                                 chosen_lens, chosen_lens_host, n_pairs, ref_logp, beta, logp_out, loss_per_pair, loss_mean, clpd_out,
+                                 win_out, dh_ft, dw_lm, dg_final, accumulate, workspace, stream=None):
+    so, sop = _host_i32(pair_offsets_host)
+    pl, plp = _host_i32(prompt_lens_host)
+    cl, clp = _host_i32(chosen_lens_host)
+    _check(load().mace_dpo_logprob_loss_shared(h, _dev(h_ft), _dev(g_final), _dev(w_lm), _dev(token_ids), _dev(pair_offsets), sop,
+                                               _dev(prompt_lens), plp, _dev(chosen_lens), clp, n_pairs, _dev(ref_logp), float(beta),
+                                               _dev(logp_out), _dev(loss_per_pair), _dev(loss_mean), _dev(clpd_out), _dev(win_out),
+                                               _dev(dh_ft), _dev(dw_lm), _dev(dg_final), int(accumulate), _dev(workspace),
+                                               workspace.numel() * workspace.element_size(), _stream(stream)),
+           "mace_dpo_logprob_loss_shared")
 
 
 def mace_next_token_logits(h, y, row_idx, n, g_final, w_lm, logits_out, next_token, workspace, stream=None):

@@ -313,7 +313,7 @@ int prepare_lora(const Dims &D, const mace_lora_t *l, const LoraWs &L, float b_s
 
 // ---------------------------------------------------------------- DPO head scratch
 struct DpoWs {
-  int32_t *row_idx, *label, *seq_id;
+  int32_t *row_idx, *label, *seq_id, *partner, *vseq_off, *vprompt;   // the last three: shared-prompt layout only
   bf16_t *n_hi, *n_lo, *dl, *e_hi, *e_lo;
   float *rstd, *logits, *logp_t, *lse, *dlogp, *dn, *dn_part, *dg_part;
 };
@@ -322,6 +322,9 @@ DpoWs plan_dpo(const Dims &D, size_t R, size_t n_seq, Bump &w) {
   P.row_idx = w.take<int32_t>(R);
   P.label = w.take<int32_t>(R);
   P.seq_id = w.take<int32_t>(R);
+  P.partner = w.take<int32_t>(R);
+  P.vseq_off = w.take<int32_t>(n_seq + 1);
+  P.vprompt = w.take<int32_t>(n_seq);
   P.n_hi = w.take<bf16_t>(R * D.d);
   P.n_lo = w.take<bf16_t>(R * D.d);
   P.rstd = w.take<float>(R);
@@ -433,6 +436,7 @@ int check_batch(const mace_batch_t *b, BatchInfo &I) {
       I.pairs_prefill += (double)P * L;
     }
   }
+  if ((b->ft_excl_lo == nullptr) != (b->ft_excl_hi == nullptr)) return fail(MACE_INVALID_ARG, "ft_excl_lo and ft_excl_hi go together");
   if (b->n_decode > 0) {
     if (!b->context_lens_host || !b->context_lens || !b->block_tables) return fail(MACE_INVALID_ARG, "decode descriptors are null");
     for (int i = 0; i < b->n_decode; ++i) {
@@ -822,7 +826,7 @@ static int layer_fwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
                                batch->context_lens, I.Td, I.max_ctx, D.Hq, D.Hkv, D.hd, F.dec_partial, F.o_i + (size_t)I.Tp * D.qd, batch->decode_head_norms, st), "decode attention");
   }
   prof_mark(h, st, T_ATTN_FT, 4.0 * D.hd * D.Hq * I.pairs_ft);
-  HIP_TRY(launch_attn_fwd(S.q, S.k, S.v, F.q_lo, F.k_lo, F.v_lo, batch->seg_offsets + batch->n_prefill + batch->n_decode, I.Ti, batch->n_ft_seq, I.max_ft, D.Hq, D.Hkv, D.hd, S.o, F.o_lo, S.lse, st), "ft attention");
+  HIP_TRY(launch_attn_fwd(S.q, S.k, S.v, F.q_lo, F.k_lo, F.v_lo, batch->seg_offsets + batch->n_prefill + batch->n_decode, I.Ti, batch->n_ft_seq, I.max_ft, D.Hq, D.Hkv, D.hd, S.o, F.o_lo, S.lse, st, batch->ft_excl_lo, batch->ft_excl_hi), "ft attention");
   // 5. output projection + residual (adapter variant: t = o A_o^T beside it, then x1 += (scale t) B_o^T)
   if (lora) {
     hipStream_t s2 = side_fork(h, st);
@@ -1036,7 +1040,7 @@ static int layer_bwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
   // attention backward, RoPE backward
   prof_mark(h, st, T_ATTN_BWD, 10.0 * D.hd * D.Hq * I.pairs_ft);
   HIP_TRY(launch_attn_bwd(S.q, S.k, S.v, S.o, B.dattn, S.lse, batch->seg_offsets + batch->n_prefill + batch->n_decode, I.Ti, batch->n_ft_seq, I.max_ft, Tf,
-                          D.Hq, D.Hkv, D.hd, B.dvec, B.dq, B.dk, B.dv, st), "attention bwd");
+                          D.Hq, D.Hkv, D.hd, B.dvec, B.dq, B.dk, B.dv, st, batch->ft_excl_lo, batch->ft_excl_hi), "attention bwd");
   prof_mark(h, st, T_ROPE);
   HIP_TRY(launch_rope_bwd(B.dq, B.dk, B.dv, batch->positions + I.Ti, h->inv_freq, Tf, D.Hq, D.Hkv, D.hd, B.dqkv, st), "rope bwd");
   // da = dq Wq + dk Wk + dv Wv ; dWq, dWk, dWv
@@ -1138,28 +1142,35 @@ int mace_hybrid_layer_bwd_lora(mace_handle_t h, const mace_layer_w_t *w, const m
   return layer_bwd_impl(h, w, lora, batch, x, dy_ft, saved, dx_ft, nullptr, grads, accumulate, workspace, workspace_bytes, stream);
 }
 
-int mace_dpo_logprob_loss(mace_handle_t h, const float *h_ft, const void *g_final, const void *w_lm,
-                          const int32_t *token_ids, const int32_t *ft_seq_offsets, const int32_t *ft_seq_offsets_host,
-                          const int32_t *prompt_lens, const int32_t *prompt_lens_host, int32_t n_pairs,
-                          const float *ref_logp, float beta, float *logp_out, float *loss_per_pair, float *loss_mean,
-                          float *clpd_out, int32_t *win_out, float *dh_ft, float *dw_lm, float *dg_final, int accumulate,
-                          void *workspace, size_t workspace_bytes, void *stream) {
+// chosen_lens / chosen_lens_host non-null selects the shared-prompt layout: offsets and prompt
+// lengths are then per PAIR (prompt | chosen | rejected stored once).
+static int dpo_impl(mace_handle_t h, const float *h_ft, const void *g_final, const void *w_lm,
+                    const int32_t *token_ids, const int32_t *ft_seq_offsets, const int32_t *ft_seq_offsets_host,
+                    const int32_t *prompt_lens, const int32_t *prompt_lens_host, const int32_t *chosen_lens,
+                    const int32_t *chosen_lens_host, int32_t n_pairs,
+                    const float *ref_logp, float beta, float *logp_out, float *loss_per_pair, float *loss_mean,
+                    float *clpd_out, int32_t *win_out, float *dh_ft, float *dw_lm, float *dg_final, int accumulate,
+                    void *workspace, size_t workspace_bytes, void *stream) {
   if (!h || !h_ft || !g_final || !w_lm || !token_ids || !ft_seq_offsets || !ft_seq_offsets_host || !prompt_lens || !prompt_lens_host ||
       !ref_logp || !logp_out || !loss_per_pair || !loss_mean)
     return fail(MACE_INVALID_ARG, "mace_dpo_logprob_loss: null argument");
   if (n_pairs <= 0 || n_pairs > 32767) return fail(MACE_INVALID_ARG, "n_pairs must be in 1..32767");
   if (!std::isfinite(beta)) return fail(MACE_INVALID_ARG, "beta");
+  const bool shared = chosen_lens_host != nullptr;
+  if (shared && !chosen_lens) return fail(MACE_INVALID_ARG, "chosen_lens device pointer is null");
   const Dims D(h->m);
   const int n_seq = 2 * n_pairs;
+  const int n_stored = shared ? n_pairs : n_seq;       // stored row ranges
   if (ft_seq_offsets_host[0] != 0) return fail(MACE_INVALID_ARG, "ft_seq_offsets must start at 0");
   long long R = 0;
-  for (int s = 0; s < n_seq; ++s) {
+  for (int s = 0; s < n_stored; ++s) {
     const int L = ft_seq_offsets_host[s + 1] - ft_seq_offsets_host[s], P = prompt_lens_host[s];
     if (L < 1 || P < 1 || P > L) return fail(MACE_INVALID_ARG, "need 1 <= prompt_len <= sequence length");
+    if (shared && (chosen_lens_host[s] < 1 || L - P - chosen_lens_host[s] < 1)) return fail(MACE_INVALID_ARG, "both responses of a pair need at least one token");
     R += L - P;
   }
   if (R > INT32_MAX / 2) return fail(MACE_INVALID_ARG, "too many loss rows");
-  const int Tf = ft_seq_offsets_host[n_seq];
+  const int Tf = ft_seq_offsets_host[n_stored];
   if (!workspace || ((uintptr_t)workspace & 255)) return fail(MACE_INVALID_ARG, "workspace must be non-null and 256-byte aligned");
   {
     Bump m(nullptr);
@@ -1179,7 +1190,11 @@ int mace_dpo_logprob_loss(mace_handle_t h, const float *h_ft, const void *g_fina
   const bool want_grad = dh_ft || dw_lm || dg_final;
   if (Ri > 0) {
     prof_mark(h, st, T_MISC);
-    HIP_TRY(launch_loss_rows(ft_seq_offsets, prompt_lens, token_ids, n_seq, P.row_idx, P.label, P.seq_id, st), "loss rows");
+    if (shared)
+      HIP_TRY(launch_loss_rows_shared(ft_seq_offsets, prompt_lens, chosen_lens, token_ids, n_pairs, P.row_idx, P.label, P.seq_id, P.partner,
+                                      P.vseq_off, P.vprompt, st), "loss rows (shared prompt)");
+    else
+      HIP_TRY(launch_loss_rows(ft_seq_offsets, prompt_lens, token_ids, n_seq, P.row_idx, P.label, P.seq_id, st), "loss rows");
     prof_mark(h, st, T_RMSNORM);
     HIP_TRY(launch_rmsnorm_fwd(h_ft, false, P.row_idx, g_final, D.bf, Ri, D.d, h->m.rms_eps, P.n_hi, P.n_lo, P.rstd, st), "final rmsnorm");
     GemmParams p = gp_init(D.d, D.d, D.d, D.V);
@@ -1190,7 +1205,7 @@ int mace_dpo_logprob_loss(mace_handle_t h, const float *h_ft, const void *g_fina
     HIP_TRY(launch_logsoftmax_gather(P.logits, Ri, D.V, P.label, P.logp_t, P.lse, st), "log-softmax");
   }
   prof_mark(h, st, T_MISC);
-  HIP_TRY(launch_dpo_pairs(P.logp_t, ft_seq_offsets, prompt_lens, n_seq, ref_logp, beta, logp_out, loss_per_pair, loss_mean, clpd_out, win_out, P.dlogp, st), "dpo pairs");
+  HIP_TRY(launch_dpo_pairs(P.logp_t, shared ? P.vseq_off : ft_seq_offsets, shared ? P.vprompt : prompt_lens, n_seq, ref_logp, beta, logp_out, loss_per_pair, loss_mean, clpd_out, win_out, P.dlogp, st), "dpo pairs");
   if (!want_grad) { prof_mark(h, st, -1); return MACE_OK; }
   const int acc = accumulate ? 1 : 0;
   if (dh_ft) { prof_mark(h, st, T_MISC); HIP_TRY(launch_fill_f32(dh_ft, (size_t)Tf * D.d, 0.f, st), "zero dh");
@@ -1229,6 +1244,13 @@ int mace_dpo_logprob_loss(mace_handle_t h, const float *h_ft, const void *g_fina
     // without dh_ft the row gradients still have to land somewhere: reuse the logits buffer
     float *dx_dst = dh_ft ? dh_ft : P.logits;
     prof_mark(h, st, T_RMSNORM);
+    if (shared) {
+      // two loss rows of a pair (the first token of either response) land on the same stored row: norm backward
+      // in place on the dense rows, then a scatter that adds the two
+      HIP_TRY(launch_rmsnorm_bwd(P.dn, h_ft, false, P.row_idx, g_final, D.bf, P.rstd, nullptr, Ri, D.d, P.dn, nullptr, P.dg_part, n_part, st, 1), "final rmsnorm bwd");
+      if (dh_ft) { prof_mark(h, st, T_MISC); HIP_TRY(launch_scatter_rows(P.dn, P.row_idx, P.partner, Ri, D.d, dh_ft, st), "scatter dh");
+      }
+    } else
     HIP_TRY(launch_rmsnorm_bwd(P.dn, h_ft, false, P.row_idx, g_final, D.bf, P.rstd, nullptr, Ri, D.d, dx_dst, nullptr, P.dg_part, n_part, st), "final rmsnorm bwd");
     if (dg_final) { prof_mark(h, st, T_MISC); HIP_TRY(launch_colsum(P.dg_part, n_part, D.d, dg_final, acc, st), "dg_final");
     }
@@ -1236,6 +1258,30 @@ int mace_dpo_logprob_loss(mace_handle_t h, const float *h_ft, const void *g_fina
   prof_mark(h, st, -1);
   HIP_TRY(side_join(h, st), "join side stream");
   return MACE_OK;
+}
+
+int mace_dpo_logprob_loss(mace_handle_t h, const float *h_ft, const void *g_final, const void *w_lm,
+                          const int32_t *token_ids, const int32_t *ft_seq_offsets, const int32_t *ft_seq_offsets_host,
+                          const int32_t *prompt_lens, const int32_t *prompt_lens_host, int32_t n_pairs,
+                          const float *ref_logp, float beta, float *logp_out, float *loss_per_pair, float *loss_mean,
+                          float *clpd_out, int32_t *win_out, float *dh_ft, float *dw_lm, float *dg_final, int accumulate,
+                          void *workspace, size_t workspace_bytes, void *stream) {
+  return dpo_impl(h, h_ft, g_final, w_lm, token_ids, ft_seq_offsets, ft_seq_offsets_host, prompt_lens, prompt_lens_host, nullptr, nullptr,
+                  n_pairs, ref_logp, beta, logp_out, loss_per_pair, loss_mean, clpd_out, win_out, dh_ft, dw_lm, dg_final, accumulate,
+                  workspace, workspace_bytes, stream);
+}
+
+int mace_dpo_logprob_loss_shared(mace_handle_t h, const float *h_ft, const void *g_final, const void *w_lm,
+                                 const int32_t *token_ids, const int32_t *pair_offsets, const int32_t *pair_offsets_host,
+                                 const int32_t *prompt_lens, const int32_t *prompt_lens_host, const int32_t *chosen_lens,
+                                 const int32_t *chosen_lens_host, int32_t n_pairs, const float *ref_logp, float beta,
+                                 float *logp_out, float *loss_per_pair, float *loss_mean, float *clpd_out, int32_t *win_out,
+                                 float *dh_ft, float *dw_lm, float *dg_final, int accumulate, void *workspace,
+                                 size_t workspace_bytes, void *stream) {
+  if (!chosen_lens || !chosen_lens_host) return fail(MACE_INVALID_ARG, "mace_dpo_logprob_loss_shared: null argument");
+  return dpo_impl(h, h_ft, g_final, w_lm, token_ids, pair_offsets, pair_offsets_host, prompt_lens, prompt_lens_host, chosen_lens,
+                  chosen_lens_host, n_pairs, ref_logp, beta, logp_out, loss_per_pair, loss_mean, clpd_out, win_out, dh_ft, dw_lm, dg_final,
+                  accumulate, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -44,7 +44,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16_t *__res
                                                           const bf16_t *__restrict__ v, const bf16_t *__restrict__ d_o,
                                                           const float *__restrict__ lse, const float *__restrict__ dvec,
                                                           const int32_t *__restrict__ seg, int row_base, int Hq, int Hkv,
-                                                          float *__restrict__ dq) {
+                                                          float *__restrict__ dq, const int32_t *__restrict__ excl_lo,
+                                                          const int32_t *__restrict__ excl_hi) {
   constexpr int NKK = HD / 16, NOT = HD / 32;
   using T = Tile<TB, HD, 256>;
   constexpr int STAGE = 2 * T::ELEMS;       // K tile, V tile
@@ -60,6 +61,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16_t *__res
   const bf16_t *kbase = k + (size_t)r0 * kld + (size_t)kvh * HD, *vbase = v + (size_t)r0 * kld + (size_t)kvh * HD;
   const int kend = min(L, q0 + 128);
   const int ntiles = (kend + TB - 1) / TB;
+  const int xlo = excl_lo ? excl_lo[s] : L, xhi = excl_lo ? excl_hi[s] : L;   // queries >= xhi skip keys xlo .. xhi-1
   auto issue_tile = [&](int it) {
     bf16_t *S = lds + (it & 1) * STAGE;
     T::issue(kbase, kld, it * TB, L, S);
@@ -102,8 +104,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16_t *__res
     if (it + 1 < ntiles) issue_tile(it + 1);
     const int kb = it * TB;
     if (kb > qw0 + 31) continue;
+    if (qw0 >= xhi && kb >= xlo && kb + TB <= xhi) continue;
     const bf16_t *Ks = lds + (it & 1) * STAGE, *Vs = Ks + T::ELEMS;
-    const bool need_mask = kb + TB - 1 > qw0 || kb + TB > L;
+    const bool need_mask = kb + TB - 1 > qw0 || kb + TB > L || (qw0 + 31 >= xhi && kb < xhi && kb + TB > xlo);
 #pragma unroll
     for (int st = 0; st < 2; ++st) {
       f32x16_t sa, dp;
@@ -122,7 +125,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16_t *__res
         float p = __builtin_amdgcn_exp2f(fmaf(sa[r], sc, -lse2));
         if (need_mask) {
           const int key = kb + st * 32 + 16 * (r >> 3) + 8 * g + (r & 7);
-          if (!(key <= qi && key < L)) p = 0.f;
+          if (!(key <= qi && key < L) || (qi >= xhi && key >= xlo && key < xhi)) p = 0.f;
         }
         ds[r] = p * (dp[r] - dv_) * rs;
       }
@@ -153,7 +156,8 @@ __global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(co
                                                             const bf16_t *__restrict__ v, const bf16_t *__restrict__ d_o,
                                                             const float *__restrict__ lse, const float *__restrict__ dvec,
                                                             const int32_t *__restrict__ seg, int row_base, int Hq,
-                                                            int Hkv, float *__restrict__ dk, float *__restrict__ dv) {
+                                                            int Hkv, float *__restrict__ dk, float *__restrict__ dv,
+                                                            const int32_t *__restrict__ excl_lo, const int32_t *__restrict__ excl_hi) {
   constexpr int NKK = HD / 16, NOT = HD / 32;
   using T = Tile<TB, HD, 256>;
   constexpr int STAGE = 2 * T::ELEMS + 4 * TB;    // Q tile, dO tile, lse[TB] and D[TB] as fp32 (2 bf16 slots each)
@@ -166,6 +170,7 @@ __global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(co
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, j = lane & 31;
   const int kw0 = k0 + wave * 32, ki = kw0 + j;      // this lane's key
   const size_t qld = (size_t)Hq * HD, kld = (size_t)Hkv * HD;
+  const int xlo = excl_lo ? excl_lo[s] : L, xhi = excl_lo ? excl_hi[s] : L;   // queries >= xhi skip keys xlo .. xhi-1
   const int nqt = (L - k0 + TB - 1) / TB;            // query tiles per head (k0 is a multiple of TB)
   const int niter = grp * nqt;
   auto issue_tile = [&](int it) {
@@ -213,9 +218,10 @@ __global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(co
     if (it + 1 < niter) issue_tile(it + 1);
     const int qb = k0 + (it % nqt) * TB;
     if (qb + TB - 1 < kw0) continue;                 // every query of the tile precedes this wave's keys
+    if (kw0 >= xlo && kw0 + 32 <= xhi && qb >= xhi) continue;   // ... or none of them may see these keys
     const bf16_t *Qs = lds + (it & 1) * STAGE, *Os = Qs + T::ELEMS;
     const float *lse_s = (const float *)(Os + T::ELEMS), *d_s = lse_s + TB;
-    const bool need_mask = qb < kw0 + 31 || qb + TB > L || kw0 + 32 > L;
+    const bool need_mask = qb < kw0 + 31 || qb + TB > L || kw0 + 32 > L || (kw0 + 31 >= xlo && kw0 < xhi && qb + TB > xhi);
 #pragma unroll
     for (int st = 0; st < 2; ++st) {
       f32x16_t sa, dp;
@@ -242,7 +248,7 @@ __global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(co
           float p = __builtin_amdgcn_exp2f(fmaf(sa[r], sc, -1.4426950408889634f * ll[e]));
           if (need_mask) {
             const int qq = qb + qo + e;
-            if (!(qq >= ki && qq < L && ki < L)) p = 0.f;
+            if (!(qq >= ki && qq < L && ki < L) || (qq >= xhi && ki >= xlo && ki < xhi)) p = 0.f;
           }
           pv[r] = p;
           ds[r] = p * (dp[r] - dd[e]) * rs;
@@ -276,7 +282,8 @@ __global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(co
 template <int HD>
 hipError_t launch_t(const bf16_t *q, const bf16_t *k, const bf16_t *v, const bf16_t *o, const bf16_t *d_o,
                     const float *lse, const int32_t *seg, int row_base, int n_seq, int max_len, int rows, int Hq,
-                    int Hkv, float *dvec, float *dq, float *dk, float *dv, hipStream_t st) {
+                    int Hkv, float *dvec, float *dq, float *dk, float *dv, hipStream_t st, const int32_t *excl_lo,
+                    const int32_t *excl_hi) {
   constexpr size_t lds_q = (size_t)2 * (2 * TB * HD) * sizeof(bf16_t);
   constexpr size_t lds_k = (size_t)2 * (2 * TB * HD + 4 * TB) * sizeof(bf16_t);
   static bool attr_flags[16] = {};
@@ -292,10 +299,10 @@ hipError_t launch_t(const bf16_t *q, const bf16_t *k, const bf16_t *v, const bf1
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   dim3 grid_q(cdiv(max_len, 128), n_seq, Hq), grid_k(cdiv(max_len, 128), n_seq, Hkv);
-  hipLaunchKernelGGL((attn_bwd_dq_kernel<HD>), grid_q, dim3(256), lds_q, st, q, k, v, d_o, lse, dvec, seg, row_base, Hq, Hkv, dq);
+  hipLaunchKernelGGL((attn_bwd_dq_kernel<HD>), grid_q, dim3(256), lds_q, st, q, k, v, d_o, lse, dvec, seg, row_base, Hq, Hkv, dq, excl_lo, excl_hi);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((attn_bwd_dkdv_kernel<HD>), grid_k, dim3(256), lds_k, st, q, k, v, d_o, lse, dvec, seg, row_base, Hq, Hkv, dk, dv);
+  hipLaunchKernelGGL((attn_bwd_dkdv_kernel<HD>), grid_k, dim3(256), lds_k, st, q, k, v, d_o, lse, dvec, seg, row_base, Hq, Hkv, dk, dv, excl_lo, excl_hi);
   return hipGetLastError();
 }
 
@@ -303,10 +310,11 @@ hipError_t launch_t(const bf16_t *q, const bf16_t *k, const bf16_t *v, const bf1
 
 hipError_t launch_attn_bwd(const bf16_t *q, const bf16_t *k, const bf16_t *v, const bf16_t *o, const bf16_t *d_o,
                            const float *lse, const int32_t *seg, int row_base, int n_seq, int max_len, int rows,
-                           int Hq, int Hkv, int hd, float *dvec, float *dq, float *dk, float *dv, hipStream_t st) {
+                           int Hq, int Hkv, int hd, float *dvec, float *dq, float *dk, float *dv, hipStream_t st,
+                           const int32_t *excl_lo, const int32_t *excl_hi) {
   if (n_seq <= 0 || rows <= 0) return hipSuccess;
-  if (n_seq > 65535 || Hq > 65535) return hipErrorInvalidValue;
-  if (hd == 64) return launch_t<64>(q, k, v, o, d_o, lse, seg, row_base, n_seq, max_len, rows, Hq, Hkv, dvec, dq, dk, dv, st);
-  if (hd == 128) return launch_t<128>(q, k, v, o, d_o, lse, seg, row_base, n_seq, max_len, rows, Hq, Hkv, dvec, dq, dk, dv, st);
+  if (n_seq > 65535 || Hq > 65535 || ((excl_lo == nullptr) != (excl_hi == nullptr))) return hipErrorInvalidValue;
+  if (hd == 64) return launch_t<64>(q, k, v, o, d_o, lse, seg, row_base, n_seq, max_len, rows, Hq, Hkv, dvec, dq, dk, dv, st, excl_lo, excl_hi);
+  if (hd == 128) return launch_t<128>(q, k, v, o, d_o, lse, seg, row_base, n_seq, max_len, rows, Hq, Hkv, dvec, dq, dk, dv, st, excl_lo, excl_hi);
   return hipErrorInvalidValue;
 }

@@ -36,7 +36,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_fwd_kernel(cons
                                                            const bf16_t *__restrict__ k_lo, const bf16_t *__restrict__ v_lo,
                                                            const int32_t *__restrict__ seg, int row_base, int Hq, int Hkv,
                                                            bf16_t *__restrict__ o_hi, bf16_t *__restrict__ o_lo,
-                                                           float *__restrict__ lse, const PagedKV pg) {
+                                                           float *__restrict__ lse, const PagedKV pg,
+                                                           const int32_t *__restrict__ excl_lo, const int32_t *__restrict__ excl_hi) {
   static_assert(!(PAGED && SPLIT), "paged K/V are single bf16 operands");
   constexpr int NT = SPLIT ? 2 : 1;
   constexpr int QB = 32 * NW;
@@ -63,6 +64,9 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_fwd_kernel(cons
   const int nkeys = pfx + L;
   const int kend = min(nkeys, pfx + q0 + QB);
   const int ntiles = (kend + KB - 1) / KB;
+  // optional excluded rectangle: queries >= xhi do not see keys xlo .. xhi-1 (a preference pair stored
+  // as prompt | chosen | rejected: the rejected response skips the chosen one)
+  const int xlo = excl_lo ? excl_lo[s] : L, xhi = excl_lo ? excl_hi[s] : L;
   auto issue_tile = [&](int it) {
     bf16_t *S = lds + (it & 1) * STAGE;
     if constexpr (PAGED) {
@@ -114,6 +118,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_fwd_kernel(cons
     if (it + 1 < ntiles) issue_tile(it + 1);
     const int kb = it * KB;
     if (kb > pfx + qw0 + 31) continue;                   // every key of the tile is in this wave's future
+    if (qw0 >= xhi && kb >= xlo && kb + KB <= xhi) continue;   // ... or inside the rectangle this wave must not see
     const bf16_t *Kh = lds + (it & 1) * STAGE, *Kl = Kh + T::ELEMS, *Vh = Kh + NT * T::ELEMS, *Vl = Vh + T::ELEMS;
 
     // ---- S^T = K Q^T for the two 32-key sub-tiles; lane owns query j, register r owns a key
@@ -134,13 +139,13 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_fwd_kernel(cons
       }
     }
     // ---- mask (only tiles that touch the diagonal or the end of the sequence), online soft-max
-    if (kb + KB - 1 > pfx + qw0 || kb + KB > nkeys) {
+    if (kb + KB - 1 > pfx + qw0 || kb + KB > nkeys || (qw0 + 31 >= xhi && kb < xhi && kb + KB > xlo)) {
 #pragma unroll
       for (int st = 0; st < 2; ++st)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int key = kb + st * 32 + 16 * (r >> 3) + 8 * g + (r & 7);
-          if (!(key <= pfx + qi && key < nkeys)) sacc[st][r] = -INFINITY;
+          if (!(key <= pfx + qi && key < nkeys) || (qi >= xhi && key >= xlo && key < xhi)) sacc[st][r] = -INFINITY;
         }
     }
     float mx = sacc[0][0];
@@ -215,7 +220,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_fwd_kernel(cons
 template <int HD, bool SPLIT, int NW, bool PAGED = false>
 hipError_t launch_t(const bf16_t *q_hi, const bf16_t *k_hi, const bf16_t *v_hi, const bf16_t *q_lo, const bf16_t *k_lo,
                     const bf16_t *v_lo, const int32_t *seg, int row_base, int n_seq, int max_len, int Hq, int Hkv,
-                    bf16_t *o_hi, bf16_t *o_lo, float *lse, hipStream_t st, const PagedKV pg = PagedKV{}) {
+                    bf16_t *o_hi, bf16_t *o_lo, float *lse, hipStream_t st, const PagedKV pg = PagedKV{},
+                    const int32_t *excl_lo = nullptr, const int32_t *excl_hi = nullptr) {
   constexpr int NT = SPLIT ? 2 : 1;
   constexpr size_t lds = (size_t)2 * 2 * NT * KB * HD * sizeof(bf16_t);
   static bool attr_flags[16] = {};
@@ -226,7 +232,7 @@ hipError_t launch_t(const bf16_t *q_hi, const bf16_t *k_hi, const bf16_t *v_hi, 
     attr_done = true;
   }
   dim3 grid(cdiv(max_len, 32 * NW), n_seq, Hq);
-  hipLaunchKernelGGL((attn_fwd_kernel<HD, SPLIT, NW, PAGED>), grid, dim3(64 * NW), lds, st, q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, Hq, Hkv, o_hi, o_lo, lse, pg);
+  hipLaunchKernelGGL((attn_fwd_kernel<HD, SPLIT, NW, PAGED>), grid, dim3(64 * NW), lds, st, q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, Hq, Hkv, o_hi, o_lo, lse, pg, excl_lo, excl_hi);
   return hipGetLastError();
 }
 
@@ -235,16 +241,16 @@ hipError_t launch_t(const bf16_t *q_hi, const bf16_t *k_hi, const bf16_t *v_hi, 
 hipError_t launch_attn_fwd(const bf16_t *q_hi, const bf16_t *k_hi, const bf16_t *v_hi, const bf16_t *q_lo,
                            const bf16_t *k_lo, const bf16_t *v_lo, const int32_t *seg, int row_base, int n_seq,
                            int max_len, int Hq, int Hkv, int hd, bf16_t *o_hi, bf16_t *o_lo, float *lse,
-                           hipStream_t st) {
+                           hipStream_t st, const int32_t *excl_lo, const int32_t *excl_hi) {
   if (n_seq <= 0 || max_len <= 0) return hipSuccess;
-  if (n_seq > 65535 || Hq > 65535) return hipErrorInvalidValue;
+  if (n_seq > 65535 || Hq > 65535 || ((excl_lo == nullptr) != (excl_hi == nullptr))) return hipErrorInvalidValue;
   const bool split = q_lo != nullptr;
   if (split && (!k_lo || !v_lo)) return hipErrorInvalidValue;
   // two-term operands at head dim 128 need 128 KB of LDS per block: 8 waves share it
-  if (hd == 64) return split ? launch_t<64, true, 4>(q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, n_seq, max_len, Hq, Hkv, o_hi, o_lo, lse, st)
-                             : launch_t<64, false, 4>(q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, n_seq, max_len, Hq, Hkv, o_hi, o_lo, lse, st);
-  if (hd == 128) return split ? launch_t<128, true, 8>(q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, n_seq, max_len, Hq, Hkv, o_hi, o_lo, lse, st)
-                              : launch_t<128, false, 4>(q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, n_seq, max_len, Hq, Hkv, o_hi, o_lo, lse, st);
+  if (hd == 64) return split ? launch_t<64, true, 4>(q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, n_seq, max_len, Hq, Hkv, o_hi, o_lo, lse, st, PagedKV{}, excl_lo, excl_hi)
+                             : launch_t<64, false, 4>(q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, n_seq, max_len, Hq, Hkv, o_hi, o_lo, lse, st, PagedKV{}, excl_lo, excl_hi);
+  if (hd == 128) return split ? launch_t<128, true, 8>(q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, n_seq, max_len, Hq, Hkv, o_hi, o_lo, lse, st, PagedKV{}, excl_lo, excl_hi)
+                              : launch_t<128, false, 4>(q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, n_seq, max_len, Hq, Hkv, o_hi, o_lo, lse, st, PagedKV{}, excl_lo, excl_hi);
   return hipErrorInvalidValue;
 }
 

@@ -21,6 +21,46 @@ __global__ __launch_bounds__(256) void loss_rows_kernel(const int32_t *ft_seq_of
   }
 }
 
+// Shared-prompt layout, one block per pair.
+__global__ __launch_bounds__(256) void loss_rows_shared_kernel(const int32_t *pair_offsets, const int32_t *prompt_lens,
+                                                               const int32_t *chosen_lens, const int32_t *token_ids, int n_pairs,
+                                                               int32_t *row_idx, int32_t *label, int32_t *seq_id, int32_t *partner,
+                                                               int32_t *vseq_off, int32_t *vprompt) {
+  const int i = blockIdx.x;
+  int base = 0;
+  for (int k = 0; k < i; ++k) base += (pair_offsets[k + 1] - pair_offsets[k]) - prompt_lens[k];
+  const int o = pair_offsets[i], L = pair_offsets[i + 1] - o, P = prompt_lens[i], Rc = chosen_lens[i], Rr = L - P - Rc;
+  for (int q = 0; q < 2; ++q) {
+    const int start = q ? P + Rc : P, R = q ? Rr : Rc, b0 = base + (q ? Rc : 0);
+    for (int j = threadIdx.x; j < R; j += 256) {
+      const int t = j == 0 ? P - 1 : start + j - 1;           // the row that predicts response token j
+      row_idx[b0 + j] = o + t;
+      label[b0 + j] = token_ids[o + start + j];
+      seq_id[b0 + j] = 2 * i + q;
+      partner[b0 + j] = j == 0 ? (q ? -2 : (Rr > 0 ? base + Rc : -1)) : -1;
+    }
+  }
+  if (threadIdx.x == 0) {
+    vseq_off[2 * i] = base;
+    vseq_off[2 * i + 1] = base + Rc;
+    if (i == n_pairs - 1) vseq_off[2 * n_pairs] = base + Rc + Rr;
+    vprompt[2 * i] = vprompt[2 * i + 1] = 0;
+  }
+}
+
+__global__ __launch_bounds__(256) void scatter_rows_kernel(const float *__restrict__ src, const int32_t *__restrict__ row_idx,
+                                                           const int32_t *__restrict__ partner, int d, float *__restrict__ dst) {
+  const int r = blockIdx.x, p = partner[r];
+  if (p == -2) return;
+  const float *a = src + (size_t)r * d, *b = p >= 0 ? src + (size_t)p * d : nullptr;
+  float *o = dst + (size_t)row_idx[r] * d;
+  for (int k = 4 * threadIdx.x; k < d; k += 1024) {        // d % 4 == 0
+    float4 v = *(const float4 *)(a + k);
+    if (b) { const float4 w = *(const float4 *)(b + k); v.x += w.x; v.y += w.y; v.z += w.z; v.w += w.w; }
+    *(float4 *)(o + k) = v;
+  }
+}
+
 // One block per loss row: single pass over the V logits with an online (max, sum) pair.
 __global__ __launch_bounds__(256) void logsoftmax_gather_kernel(const float *__restrict__ logits, int V,
                                                                 const int32_t *__restrict__ label,
@@ -135,6 +175,22 @@ hipError_t launch_dpo_pairs(const float *logp_t, const int32_t *ft_seq_offsets, 
                             const float *ref_logp, float beta, float *logp_out, float *loss_per_pair, float *loss_mean,
                             float *clpd, int32_t *win, float *dlogp, hipStream_t st) {
   hipLaunchKernelGGL(dpo_pairs_kernel, dim3(1), dim3(256), 0, st, logp_t, ft_seq_offsets, prompt_lens, n_seq, ref_logp, beta, logp_out, loss_per_pair, loss_mean, clpd, win, dlogp);
+  return hipGetLastError();
+}
+
+hipError_t launch_loss_rows_shared(const int32_t *pair_offsets, const int32_t *prompt_lens, const int32_t *chosen_lens,
+                                   const int32_t *token_ids, int n_pairs, int32_t *row_idx, int32_t *label, int32_t *seq_id,
+                                   int32_t *partner, int32_t *vseq_off, int32_t *vprompt, hipStream_t st) {
+  if (n_pairs <= 0) return hipSuccess;
+  hipLaunchKernelGGL(loss_rows_shared_kernel, dim3(n_pairs), dim3(256), 0, st, pair_offsets, prompt_lens, chosen_lens, token_ids, n_pairs,
+                     row_idx, label, seq_id, partner, vseq_off, vprompt);
+  return hipGetLastError();
+}
+
+hipError_t launch_scatter_rows(const float *src, const int32_t *row_idx, const int32_t *partner, int rows, int d, float *dst,
+                               hipStream_t st) {
+  if (rows <= 0) return hipSuccess;
+  hipLaunchKernelGGL(scatter_rows_kernel, dim3(rows), dim3(256), 0, st, src, row_idx, partner, d, dst);
   return hipGetLastError();
 }
 

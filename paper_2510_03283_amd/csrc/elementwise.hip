@@ -55,7 +55,7 @@ template <bool XBF, bool GBF>
 __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const float *dy, const void *x, const int32_t *row_idx,
                                                           const void *g, const float *rstd, const float *resid,
                                                           int rows, int d, float *dx_out, bf16_t *dx_bf,
-                                                          float *dg_partial) {
+                                                          float *dg_partial, int dense_out) {
   __shared__ float red[4];
   float dgacc[RB_MAXV][4];
 #pragma unroll
@@ -95,8 +95,9 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const float *dy, const
         if (resid) ld4<false>(resid, yr + k, rr);
 #pragma unroll
         for (int j = 0; j < 4; ++j) o[j] = rr[j] + rs * dv[j] * gg[j] - xv[j] * c;
-        *(float4 *)(dx_out + xr + k) = make_float4(o[0], o[1], o[2], o[3]);
-        if (dx_bf) *(uint2 *)(dx_bf + xr + k) = make_uint2(pack2(f2bf(o[0]), f2bf(o[1])), pack2(f2bf(o[2]), f2bf(o[3])));
+        const size_t orow = dense_out ? yr : xr;      // dense: output row r (may be dy itself), else the gathered row
+        *(float4 *)(dx_out + orow + k) = make_float4(o[0], o[1], o[2], o[3]);
+        if (dx_bf) *(uint2 *)(dx_bf + orow + k) = make_uint2(pack2(f2bf(o[0]), f2bf(o[1])), pack2(f2bf(o[2]), f2bf(o[3])));
       }
     }
   }
@@ -287,14 +288,14 @@ hipError_t launch_rmsnorm_fwd(const void *x, bool x_bf16, const int32_t *row_idx
 
 hipError_t launch_rmsnorm_bwd(const float *dy, const void *x, bool x_bf16, const int32_t *row_idx, const void *g,
                               bool g_bf16, const float *rstd, const float *resid, int rows, int d, float *dx_out,
-                              bf16_t *dx_bf, float *dg_partial, int n_part, hipStream_t st) {
+                              bf16_t *dx_bf, float *dg_partial, int n_part, hipStream_t st, int dense_out) {
   if (rows <= 0 || n_part <= 0) return hipSuccess;
   if (d > 1024 * RB_MAXV) return hipErrorInvalidValue;
   dim3 grid(n_part), blk(256);
-  if (x_bf16 && g_bf16) hipLaunchKernelGGL((rmsnorm_bwd_kernel<true, true>), grid, blk, 0, st, dy, x, row_idx, g, rstd, resid, rows, d, dx_out, dx_bf, dg_partial);
-  else if (!x_bf16 && g_bf16) hipLaunchKernelGGL((rmsnorm_bwd_kernel<false, true>), grid, blk, 0, st, dy, x, row_idx, g, rstd, resid, rows, d, dx_out, dx_bf, dg_partial);
-  else if (!x_bf16 && !g_bf16) hipLaunchKernelGGL((rmsnorm_bwd_kernel<false, false>), grid, blk, 0, st, dy, x, row_idx, g, rstd, resid, rows, d, dx_out, dx_bf, dg_partial);
-  else hipLaunchKernelGGL((rmsnorm_bwd_kernel<true, false>), grid, blk, 0, st, dy, x, row_idx, g, rstd, resid, rows, d, dx_out, dx_bf, dg_partial);
+  if (x_bf16 && g_bf16) hipLaunchKernelGGL((rmsnorm_bwd_kernel<true, true>), grid, blk, 0, st, dy, x, row_idx, g, rstd, resid, rows, d, dx_out, dx_bf, dg_partial, dense_out);
+  else if (!x_bf16 && g_bf16) hipLaunchKernelGGL((rmsnorm_bwd_kernel<false, true>), grid, blk, 0, st, dy, x, row_idx, g, rstd, resid, rows, d, dx_out, dx_bf, dg_partial, dense_out);
+  else if (!x_bf16 && !g_bf16) hipLaunchKernelGGL((rmsnorm_bwd_kernel<false, false>), grid, blk, 0, st, dy, x, row_idx, g, rstd, resid, rows, d, dx_out, dx_bf, dg_partial, dense_out);
+  else hipLaunchKernelGGL((rmsnorm_bwd_kernel<true, false>), grid, blk, 0, st, dy, x, row_idx, g, rstd, resid, rows, d, dx_out, dx_bf, dg_partial, dense_out);
   return hipGetLastError();
 }
 

@@ -14,9 +14,12 @@ hipError_t launch_rmsnorm_fwd(const void *x, bool x_bf16, const int32_t *row_idx
 // out_row = row_idx ? row_idx[r] : r and x is read at the same row; resid (nullable) fp32.
 // dg_partial [n_part, d] receives per-block partial sums of dy*x*rstd (reduce with
 // launch_colsum).  dx_bf (nullable) gets a bf16 copy of dx_out rows (same row mapping).
+// dense_out != 0: output row r is written at row r (dx_out may then be dy itself) while x is still
+// read at row_idx[r].
 hipError_t launch_rmsnorm_bwd(const float *dy, const void *x, bool x_bf16, const int32_t *row_idx, const void *g,
                               bool g_bf16, const float *rstd, const float *resid, int rows, int d,
-                              float *dx_out, bf16_t *dx_bf, float *dg_partial, int n_part, hipStream_t st);
+                              float *dx_out, bf16_t *dx_bf, float *dg_partial, int n_part, hipStream_t st,
+                              int dense_out = 0);
 // out[j] (+)= sum_i part[i, j]
 hipError_t launch_colsum(const float *part, int n_part, int d, float *out, int accumulate, hipStream_t st);
 // Rotary embedding of q and k inside qkv fp32 [rows, (Hq+2Hkv)*hd], split into head-major bf16
@@ -72,7 +75,9 @@ hipError_t launch_kv_gather(const void *cache_k, const void *cache_v, bool bf16,
 hipError_t launch_attn_fwd(const bf16_t *q_hi, const bf16_t *k_hi, const bf16_t *v_hi, const bf16_t *q_lo,
                            const bf16_t *k_lo, const bf16_t *v_lo, const int32_t *seg, int row_base, int n_seq,
                            int max_len, int Hq, int Hkv, int hd, bf16_t *o_hi, bf16_t *o_lo, float *lse,
-                           hipStream_t st);
+                           hipStream_t st, const int32_t *excl_lo = nullptr, const int32_t *excl_hi = nullptr);
+// excl_lo / excl_hi (nullable, device [n_seq], rows relative to the sequence start): queries at or
+// beyond excl_hi[s] do not see keys excl_lo[s] .. excl_hi[s]-1 (shared-prompt preference pairs).
 // The same for requests with a cached prefix: keys and values of request s are positions
 // 0 .. prefix_lens[s] + len_s - 1 of its block table in the paged bf16 cache (its own rows must have
 // been appended already); query j of the request sits at position prefix_lens[s] + j.
@@ -96,13 +101,26 @@ hipError_t launch_head_norm_stats(const float *norms, const int32_t *t_count, in
 // dvec: fp32 scratch [rows, Hq].
 hipError_t launch_attn_bwd(const bf16_t *q, const bf16_t *k, const bf16_t *v, const bf16_t *o, const bf16_t *d_o,
                            const float *lse, const int32_t *seg, int row_base, int n_seq, int max_len, int rows,
-                           int Hq, int Hkv, int hd, float *dvec, float *dq, float *dk, float *dv, hipStream_t st);
+                           int Hq, int Hkv, int hd, float *dvec, float *dq, float *dk, float *dv, hipStream_t st,
+                           const int32_t *excl_lo = nullptr, const int32_t *excl_hi = nullptr);
 
 // ---- dpo_head.hip ----------------------------------------------------------------------------
 // For every loss row (sequence s, t = P_s-1 .. L_s-2, in sequence order): row_idx = index of row
 // t among the fine-tune rows, label = token_ids[t+1], seq_id = s.
 hipError_t launch_loss_rows(const int32_t *ft_seq_offsets, const int32_t *prompt_lens, const int32_t *token_ids,
                             int n_seq, int32_t *row_idx, int32_t *label, int32_t *seq_id, hipStream_t st);
+// Shared-prompt layout (a pair stored once as prompt | chosen | rejected; offsets per PAIR): loss
+// rows of sequence 2i (chosen) are the last prompt row and the chosen rows but the last, of 2i+1 the
+// last prompt row and the rejected rows but the last.  partner[r]: -1, or for the chosen sequence's
+// first loss row the index of the rejected sequence's first loss row (same target row), which
+// itself gets -2.  vseq_off [2 n_pairs + 1] / vprompt [2 n_pairs]: a virtual (offsets, prompt
+// lengths) pair with the loss-row counts of the 2 n_pairs sequences, for launch_dpo_pairs.
+hipError_t launch_loss_rows_shared(const int32_t *pair_offsets, const int32_t *prompt_lens, const int32_t *chosen_lens,
+                                   const int32_t *token_ids, int n_pairs, int32_t *row_idx, int32_t *label, int32_t *seq_id,
+                                   int32_t *partner, int32_t *vseq_off, int32_t *vprompt, hipStream_t st);
+// dst[row_idx[r], :] = src[r, :] (+ src[partner[r], :] when partner[r] >= 0); rows with partner -2 are skipped.
+hipError_t launch_scatter_rows(const float *src, const int32_t *row_idx, const int32_t *partner, int rows, int d, float *dst,
+                               hipStream_t st);
 // logp_t[r] = logits[r, label[r]] - logsumexp(logits[r, :]); lse[r] kept.
 hipError_t launch_logsoftmax_gather(const float *logits, int rows, int V, const int32_t *label, float *logp_t,
                                     float *lse, hipStream_t st);

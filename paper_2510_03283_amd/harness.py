@@ -66,6 +66,12 @@ class DeviceIteration:
                 pbt[i, :len(tb)] = tb
             pre = dict(prefill_block_tables=up(pbt), prefill_prefix_lens_host=np.asarray(pfx, np.int32),
                        prefill_prefix_lens=up(np.asarray(pfx, np.int32)), max_blocks_per_prefill=mbp)
+        self.shared = getattr(b, "ft_chosen_lens", None) is not None
+        if self.shared:      # one stored sequence per pair: rejected rows skip the chosen-response keys
+            lo = np.asarray(b.ft_prompt_lens, dtype=np.int32)
+            self.chosen_host = np.asarray(b.ft_chosen_lens, dtype=np.int32)
+            self.chosen_dev = up(self.chosen_host)
+            pre.update(ft_excl_lo=up(lo), ft_excl_hi=up(lo + self.chosen_host))
         self.batch = B.BatchDesc(b.n_prefill, b.n_decode, b.n_ft_seq, self.T, seg, self.seg_dev, self.pos_dev,
                                  self.slot_dev, self.bt_dev, np.asarray(b.decode_ctx, dtype=np.int32), self.ctx_dev,
                                  b.max_blocks_per_req, self.head_norms, **pre)
@@ -76,7 +82,7 @@ class DeviceIteration:
         self.prompt_host = np.asarray(b.ft_prompt_lens, dtype=np.int32)
         self.prompt_dev = up(self.prompt_host)
         self.ref_dev = up(np.asarray(wl.ref_logp, dtype=np.float32))
-        self.n_pairs = b.n_ft_seq // 2
+        self.n_pairs = b.n_ft_seq if self.shared else b.n_ft_seq // 2
 
         # paged cache
         cshape = (b.num_blocks, m.n_kv_heads, b.block_size, m.head_dim)
@@ -101,7 +107,7 @@ class DeviceIteration:
         self.ws = torch.empty(B.mace_workspace_bytes(self.h, self.T, self.Tf, self.Td, max_ctx, self.R), dtype=torch.uint8, device=self.dev)
         f32 = dict(dtype=torch.float32, device=self.dev)
         self.y = torch.empty((self.T, m.d_model), **f32)
-        self.logp = torch.empty(max(b.n_ft_seq, 1), **f32)
+        self.logp = torch.empty(max(2 * self.n_pairs, 1), **f32)
         self.loss_pair = torch.empty(max(self.n_pairs, 1), **f32)
         self.loss_mean = torch.empty(1, **f32)
         self.clpd = torch.empty(max(self.n_pairs, 1), **f32)
@@ -161,6 +167,14 @@ class DeviceIteration:
 
     def dpo(self, backward: bool = True):
         y_ft = self.y[self.Ti:]
+        if self.shared:
+            frozen = self.lora is not None
+            B.mace_dpo_logprob_loss_shared(self.h, y_ft, self.gf, self.E, self.tok_ft, self.ft_off_dev, self.ft_off_host,
+                                           self.prompt_dev, self.prompt_host, self.chosen_dev, self.chosen_host, self.n_pairs,
+                                           self.ref_dev, self.wl.beta, self.logp, self.loss_pair, self.loss_mean, self.clpd, self.win,
+                                           self.dh if backward else None, self.dE if backward and not frozen else None,
+                                           self.dgf if backward and not frozen else None, 0, self.ws)
+            return
         if self.lora is not None and backward:      # frozen base model: only the row gradients are needed
             B.mace_dpo_logprob_loss(self.h, y_ft, self.gf, self.E, self.tok_ft, self.ft_off_dev, self.ft_off_host,
                                     self.prompt_dev, self.prompt_host, self.n_pairs, self.ref_dev, self.wl.beta, self.logp,

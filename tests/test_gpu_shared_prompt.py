@@ -1,0 +1,92 @@
+"""GPU parity of the shared-prompt layout of a preference pair: each pair stored once as
+prompt | chosen response | rejected response, the rejected rows masked from the chosen keys, the
+DPO head reading two log-probabilities per stored sequence.  Compared with the oracle's
+shared-prompt path at the same bars as the two-sequence layout; the two layouts are also compared
+with each other on the GPU (same loss up to rounding order)."""
+import numpy as np
+import pytest
+
+from paper_2510_03283_amd import synth
+from test_gpu_parity import SMALL, TOL_LOSS, check_iteration, custom_workload, torch_mod  # noqa: F401  (fixture)
+
+pytestmark = pytest.mark.gpu
+
+
+def test_tiny_shared_prompt(torch_mod):
+    """fp32 model (three-pass operands), prompt 32 + two responses of 32."""
+    check_iteration(torch_mod, synth.to_shared_prompt(synth.make_workload("tiny")), "tiny shared")
+
+
+def test_edge_shared_prompt_full_size(torch_mod):
+    check_iteration(torch_mod, synth.to_shared_prompt(synth.make_workload("edge")), "edge shared")
+
+
+@pytest.mark.parametrize("hq,hkv,hd,bf", [(4, 4, 64, True), (8, 2, 64, False), (4, 2, 128, True), (2, 2, 128, False)])
+@pytest.mark.parametrize("prompt,resp", [(5, (1, 140)), (64, (60, 70)), (129, (1, 3)), (200, (120, 300))])
+def test_ragged_shared_prompt(torch_mod, hq, hkv, hd, bf, prompt, resp):
+    """Prompts and responses on and off the 64/128-row tile edges, single-token responses (the two
+    loss rows of a pair then fall on one stored row), responses that span several key tiles (the
+    masked rectangle covers whole tiles), MHA and GQA, both head sizes, both storage types."""
+    dims = synth.ModelDims(n_q_heads=hq, n_kv_heads=hkv, head_dim=hd, io_bf16=bf, **SMALL)
+    wl = custom_workload("shared", dims, prefill=[33, 130], decode=[7, 300], n_pairs=3, prompt=prompt, resp=resp)
+    check_iteration(torch_mod, synth.to_shared_prompt(wl), f"shared Hq{hq} Hkv{hkv} hd{hd} bf{bf} P{prompt} R{resp}")
+
+
+def test_shared_prompt_only_pairs(torch_mod):
+    dims = synth.ModelDims(n_q_heads=4, n_kv_heads=1, head_dim=64, **SMALL)
+    wl = custom_workload("shared_only", dims, prefill=[], decode=[], n_pairs=2, prompt=70, resp=(1, 200))
+    check_iteration(torch_mod, synth.to_shared_prompt(wl), "shared, fine-tune rows only")
+
+
+def test_shared_prompt_lora(torch_mod):
+    dims = synth.ModelDims(512, 8, 2, 128, 1408, 4096, io_bf16=True)
+    wl = custom_workload("shared_lora", dims, prefill=(37,), decode=(5, 300), n_pairs=2, prompt=33, resp=(7, 70))
+    spec = synth.ConfigSpec("shared_lora", 77, dims, None, None, None, None, 2, 33, None, (7, 70))
+    check_iteration(torch_mod, synth.to_shared_prompt(wl), "shared+lora16", lora=synth.make_lora(spec, rank=16, scale=1.0))
+
+
+def test_layouts_agree_on_gpu(torch_mod):
+    """Both layouts of the same pairs on the GPU: same per-pair losses and log-probabilities up to
+    summation order, and the weight gradients agree (the shared layout adds the two prompt copies'
+    contributions inside one row instead of across two)."""
+    torch = torch_mod
+    from paper_2510_03283_amd.harness import DeviceIteration
+    dims = synth.ModelDims(n_q_heads=4, n_kv_heads=2, head_dim=64, **SMALL)
+    wl = custom_workload("both", dims, prefill=[20], decode=[40], n_pairs=3, prompt=90, resp=(30, 150))
+    a, b = DeviceIteration(wl), DeviceIteration(synth.to_shared_prompt(wl))
+    try:
+        for it in (a, b):
+            it.forward(); it.dpo(True); it.backward()
+        torch.cuda.synchronize()
+        assert np.abs(a.loss_pair.cpu().numpy() - b.loss_pair.cpu().numpy()).max() <= TOL_LOSS
+        assert np.abs(a.logp.cpu().numpy() - b.logp.cpu().numpy()).max() <= 2e-3
+        for k in a.grads:
+            ga, gb = a.grads[k].cpu().numpy().astype(np.float64), b.grads[k].cpu().numpy().astype(np.float64)
+            assert np.linalg.norm(ga - gb) <= 2e-2 * np.linalg.norm(ga), k
+    finally:
+        a.close(); b.close()
+
+
+def test_shared_prompt_error_paths(torch_mod):
+    torch = torch_mod
+    from paper_2510_03283_amd import binding as B
+    from paper_2510_03283_amd.harness import DeviceIteration
+    it = DeviceIteration(synth.to_shared_prompt(synth.make_workload("tiny")))
+    try:
+        it.forward()
+        y_ft = it.y[it.Ti:]
+        bad_chosen = it.chosen_host.copy()
+        bad_chosen[0] = int(it.ft_off_host[1] - it.ft_off_host[0] - it.prompt_host[0])      # leaves no rejected token
+        with pytest.raises(B.MaceError):
+            B.mace_dpo_logprob_loss_shared(it.h, y_ft, it.gf, it.E, it.tok_ft, it.ft_off_dev, it.ft_off_host, it.prompt_dev, it.prompt_host,
+                                           it.chosen_dev, bad_chosen, it.n_pairs, it.ref_dev, 0.1, it.logp, it.loss_pair, it.loss_mean,
+                                           it.clpd, it.win, None, None, None, 0, it.ws)
+        # the mask bounds come in pairs
+        with pytest.raises((B.MaceError, ValueError)):
+            bad = B.BatchDesc(it.wl.batch.n_prefill, it.wl.batch.n_decode, it.wl.batch.n_ft_seq, it.T, np.asarray(it.wl.batch.seg_offsets, dtype=np.int32), it.seg_dev, it.pos_dev,
+                              it.slot_dev, it.bt_dev, np.asarray(it.wl.batch.decode_ctx, dtype=np.int32), it.ctx_dev,
+                              it.wl.batch.max_blocks_per_req, it.head_norms, ft_excl_lo=it.prompt_dev)
+            B.mace_hybrid_layer_fwd(it.h, it.w_struct, bad, it.cache, it.x, it.y, it.saved, it.ws)
+        torch.cuda.synchronize()
+    finally:
+        it.close()
