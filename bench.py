@@ -102,6 +102,10 @@ def main():
     ap.add_argument("--prefix", type=int, default=0,
                     help="give every prefill request a cached prefix of this many tokens (multiple of the block size; "
                          "groups of four requests share the blocks of one prefix node): prefix-shared prefill")
+    ap.add_argument("--shared-prompt", action="store_true",
+                    help="store every preference pair once as prompt | chosen | rejected (both responses attend to one "
+                         "copy of the prompt): same losses and gradients from fewer rows; `value` counts the stored rows, "
+                         "`config.equivalent_tokens_per_s` the rows of the two-sequence layout the step replaces")
     ap.add_argument("--extras", action="store_true",
                     help="also time the loop-closing entry points (next-token logits of the inference rows' last tokens, "
                          "AdamW over the layer's weights) and add them to the line as `extras`")
@@ -139,6 +143,9 @@ def main():
             a = i - i % 4
             wl.batch.prefill_block_tables[i][:nb] = wl.batch.prefill_block_tables[a][:nb]
             wl.pre_k[i], wl.pre_v[i] = wl.pre_k[a], wl.pre_v[a]
+    rows_two_seq = wl.batch.n_tokens
+    if args.shared_prompt:
+        wl = synth.to_shared_prompt(wl)
     lora = synth.make_lora(wl.spec, rank=16, scale=2.0) if args.variant == "lora" else None
     it = DeviceIteration(wl, device_cache_seed=wl.spec.seed if big_cache else None, lora=lora)
     if args.calib_copy:
@@ -188,6 +195,10 @@ def main():
                    "prefill_prefix_tokens": args.prefix,
                    "variant": "full fine-tune (7 weight gradients + head)" if lora is None else "LoRA rank 16 on q,k,v,o (adapter gradients only)"},
     }
+    if args.shared_prompt:
+        out["config"]["ft_layout"] = "shared prompt (one stored sequence per pair)"
+        out["config"]["rows_two_sequence_layout"] = rows_two_seq
+        out["config"]["equivalent_tokens_per_s"] = rows_two_seq * args.steps / dt
     if prof:
         e = prof[dom]
         avg_ms = e["ms"] / e["launches"]
