@@ -112,7 +112,7 @@ struct Dims {
         bf(m.io_dtype == MACE_BF16) {}
 };
 
-constexpr int DG_PARTS = 512;   // blocks (and partial rows) of the RMSNorm backward
+constexpr int DG_PARTS = 1024;   // blocks (and partial rows) of the RMSNorm backward
 
 // bf16 (hi, lo) views of the seven weight matrices; for bf16 models hi aliases the caller's weights.
 struct WSplit {

@@ -51,79 +51,85 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const void *x, const i
 
 // ------------------------------------------------------------------ RMSNorm backward
 constexpr int RB_MAXV = 8;   // d <= 8192
-template <bool XBF, bool GBF>
+// One block per partial row of dg; a block walks rows r = blockIdx.x, + gridDim.x, ...  NV = float4
+// chunks per thread (d <= 1024 NV): the row of dy and of x stays in registers between the reduction
+// and the output pass, and g is read once per block.
+template <bool XBF, bool GBF, int NV>
 __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const float *dy, const void *x, const int32_t *row_idx,
                                                           const void *g, const float *rstd, const float *resid,
                                                           int rows, int d, float *dx_out, bf16_t *dx_bf,
                                                           float *dg_partial, int dense_out) {
   __shared__ float red[4];
-  float dgacc[RB_MAXV][4];
+  float dgacc[NV][4], gg[NV][4];
 #pragma unroll
-  for (int i = 0; i < RB_MAXV; ++i)
+  for (int i = 0; i < NV; ++i) {
+    const int k = 4 * threadIdx.x + 1024 * i;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) dgacc[i][j] = 0.f;
+    for (int j = 0; j < 4; ++j) dgacc[i][j] = gg[i][j] = 0.f;
+    if (k < d) ld4<GBF>(g, k, gg[i]);
+  }
   for (int r = blockIdx.x; r < rows; r += gridDim.x) {
     const size_t xr = (size_t)(row_idx ? row_idx[r] : r) * d, yr = (size_t)r * d;
+    float dv[NV][4], xv[NV][4], rr[NV][4];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int k = 4 * threadIdx.x + 1024 * i;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) dv[i][j] = xv[i][j] = rr[i][j] = 0.f;
+      if (k < d) {
+        ld4<false>(dy, yr + k, dv[i]);
+        ld4<XBF>(x, xr + k, xv[i]);
+        if (resid) ld4<false>(resid, yr + k, rr[i]);
+      }
+    }
     const float rs = rstd[r];
     float s = 0.f;
 #pragma unroll
-    for (int i = 0; i < RB_MAXV; ++i) {
-      const int k = 4 * threadIdx.x + 1024 * i;
-      if (k < d) {
-        float dv[4], xv[4], gg[4];
-        ld4<false>(dy, yr + k, dv);
-        ld4<XBF>(x, xr + k, xv);
-        ld4<GBF>(g, k, gg);
+    for (int i = 0; i < NV; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          s += dv[j] * gg[j] * xv[j];
-          dgacc[i][j] += dv[j] * xv[j] * rs;
-        }
+      for (int j = 0; j < 4; ++j) {
+        s += dv[i][j] * gg[i][j] * xv[i][j];
+        dgacc[i][j] += dv[i][j] * xv[i][j] * rs;
       }
-    }
     s = block_sum<256>(s, red);
     const float c = rs * rs * rs * s / (float)d;
+    const size_t orow = dense_out ? yr : xr;      // dense: output row r (may be dy itself), else the gathered row
 #pragma unroll
-    for (int i = 0; i < RB_MAXV; ++i) {
+    for (int i = 0; i < NV; ++i) {
       const int k = 4 * threadIdx.x + 1024 * i;
       if (k < d) {
-        float dv[4], xv[4], gg[4], o[4];
-        ld4<false>(dy, yr + k, dv);
-        ld4<XBF>(x, xr + k, xv);
-        ld4<GBF>(g, k, gg);
-        float rr[4] = {0.f, 0.f, 0.f, 0.f};
-        if (resid) ld4<false>(resid, yr + k, rr);
+        float o[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) o[j] = rr[j] + rs * dv[j] * gg[j] - xv[j] * c;
-        const size_t orow = dense_out ? yr : xr;      // dense: output row r (may be dy itself), else the gathered row
+        for (int j = 0; j < 4; ++j) o[j] = rr[i][j] + rs * dv[i][j] * gg[i][j] - xv[i][j] * c;
         *(float4 *)(dx_out + orow + k) = make_float4(o[0], o[1], o[2], o[3]);
         if (dx_bf) *(uint2 *)(dx_bf + orow + k) = make_uint2(pack2(f2bf(o[0]), f2bf(o[1])), pack2(f2bf(o[2]), f2bf(o[3])));
       }
     }
   }
 #pragma unroll
-  for (int i = 0; i < RB_MAXV; ++i) {
+  for (int i = 0; i < NV; ++i) {
     const int k = 4 * threadIdx.x + 1024 * i;
     if (k < d) *(float4 *)(dg_partial + (size_t)blockIdx.x * d + k) = make_float4(dgacc[i][0], dgacc[i][1], dgacc[i][2], dgacc[i][3]);
   }
 }
 
-// 32 columns per block; the 8 thread rows of a block stride over the partial rows with eight
+// 32 columns per block; the 32 thread rows of a block stride over the partial rows with eight
 // independent loads in flight each (the kernel is latency-bound: a few MB spread over few blocks),
 // then reduce in LDS.  Fixed summation order: deterministic.
-__global__ __launch_bounds__(256) void colsum_kernel(const float *part, int n_part, int d, float *out, int accumulate) {
-  __shared__ float red[8][33];
+__global__ __launch_bounds__(1024) void colsum_kernel(const float *part, int n_part, int d, float *out, int accumulate) {
+  constexpr int RG = 32;
+  __shared__ float red[RG][33];
   const int c = threadIdx.x & 31, rg = threadIdx.x >> 5;
   const int j = blockIdx.x * 32 + c;
   float s = 0.f;
   if (j < d) {
     float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     int i = rg;
-    for (; i + 56 < n_part; i += 64) {
+    for (; i + 7 * RG < n_part; i += 8 * RG) {
 #pragma unroll
-      for (int u = 0; u < 8; ++u) a[u] += part[(size_t)(i + 8 * u) * d + j];
+      for (int u = 0; u < 8; ++u) a[u] += part[(size_t)(i + RG * u) * d + j];
     }
-    for (; i < n_part; i += 8) a[0] += part[(size_t)i * d + j];
+    for (; i < n_part; i += RG) a[0] += part[(size_t)i * d + j];
     s = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
   }
   red[rg][c] = s;
@@ -131,7 +137,7 @@ __global__ __launch_bounds__(256) void colsum_kernel(const float *part, int n_pa
   if (rg == 0 && j < d) {
     float t = 0.f;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) t += red[k][c];
+    for (int k = 0; k < RG; ++k) t += red[k][c];
     out[j] = accumulate ? out[j] + t : t;
   }
 }
@@ -286,21 +292,33 @@ hipError_t launch_rmsnorm_fwd(const void *x, bool x_bf16, const int32_t *row_idx
   return hipGetLastError();
 }
 
+template <bool XBF, bool GBF>
+static void rmsnorm_bwd_nv(int nv, dim3 grid, hipStream_t st, const float *dy, const void *x, const int32_t *row_idx, const void *g,
+                           const float *rstd, const float *resid, int rows, int d, float *dx_out, bf16_t *dx_bf,
+                           float *dg_partial, int dense_out) {
+  const dim3 blk(256);
+  if (nv <= 1) hipLaunchKernelGGL((rmsnorm_bwd_kernel<XBF, GBF, 1>), grid, blk, 0, st, dy, x, row_idx, g, rstd, resid, rows, d, dx_out, dx_bf, dg_partial, dense_out);
+  else if (nv <= 2) hipLaunchKernelGGL((rmsnorm_bwd_kernel<XBF, GBF, 2>), grid, blk, 0, st, dy, x, row_idx, g, rstd, resid, rows, d, dx_out, dx_bf, dg_partial, dense_out);
+  else if (nv <= 4) hipLaunchKernelGGL((rmsnorm_bwd_kernel<XBF, GBF, 4>), grid, blk, 0, st, dy, x, row_idx, g, rstd, resid, rows, d, dx_out, dx_bf, dg_partial, dense_out);
+  else hipLaunchKernelGGL((rmsnorm_bwd_kernel<XBF, GBF, RB_MAXV>), grid, blk, 0, st, dy, x, row_idx, g, rstd, resid, rows, d, dx_out, dx_bf, dg_partial, dense_out);
+}
+
 hipError_t launch_rmsnorm_bwd(const float *dy, const void *x, bool x_bf16, const int32_t *row_idx, const void *g,
                               bool g_bf16, const float *rstd, const float *resid, int rows, int d, float *dx_out,
                               bf16_t *dx_bf, float *dg_partial, int n_part, hipStream_t st, int dense_out) {
   if (rows <= 0 || n_part <= 0) return hipSuccess;
   if (d > 1024 * RB_MAXV) return hipErrorInvalidValue;
-  dim3 grid(n_part), blk(256);
-  if (x_bf16 && g_bf16) hipLaunchKernelGGL((rmsnorm_bwd_kernel<true, true>), grid, blk, 0, st, dy, x, row_idx, g, rstd, resid, rows, d, dx_out, dx_bf, dg_partial, dense_out);
-  else if (!x_bf16 && g_bf16) hipLaunchKernelGGL((rmsnorm_bwd_kernel<false, true>), grid, blk, 0, st, dy, x, row_idx, g, rstd, resid, rows, d, dx_out, dx_bf, dg_partial, dense_out);
-  else if (!x_bf16 && !g_bf16) hipLaunchKernelGGL((rmsnorm_bwd_kernel<false, false>), grid, blk, 0, st, dy, x, row_idx, g, rstd, resid, rows, d, dx_out, dx_bf, dg_partial, dense_out);
-  else hipLaunchKernelGGL((rmsnorm_bwd_kernel<true, false>), grid, blk, 0, st, dy, x, row_idx, g, rstd, resid, rows, d, dx_out, dx_bf, dg_partial, dense_out);
+  const dim3 grid(n_part);
+  const int nv = (d + 1023) / 1024;
+  if (x_bf16 && g_bf16) rmsnorm_bwd_nv<true, true>(nv, grid, st, dy, x, row_idx, g, rstd, resid, rows, d, dx_out, dx_bf, dg_partial, dense_out);
+  else if (!x_bf16 && g_bf16) rmsnorm_bwd_nv<false, true>(nv, grid, st, dy, x, row_idx, g, rstd, resid, rows, d, dx_out, dx_bf, dg_partial, dense_out);
+  else if (!x_bf16 && !g_bf16) rmsnorm_bwd_nv<false, false>(nv, grid, st, dy, x, row_idx, g, rstd, resid, rows, d, dx_out, dx_bf, dg_partial, dense_out);
+  else rmsnorm_bwd_nv<true, false>(nv, grid, st, dy, x, row_idx, g, rstd, resid, rows, d, dx_out, dx_bf, dg_partial, dense_out);
   return hipGetLastError();
 }
 
 hipError_t launch_colsum(const float *part, int n_part, int d, float *out, int accumulate, hipStream_t st) {
-  hipLaunchKernelGGL(colsum_kernel, dim3(cdiv(d, 32)), dim3(256), 0, st, part, n_part, d, out, accumulate);
+  hipLaunchKernelGGL(colsum_kernel, dim3(cdiv(d, 32)), dim3(1024), 0, st, part, n_part, d, out, accumulate);
   return hipGetLastError();
 }
 

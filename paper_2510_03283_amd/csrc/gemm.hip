@@ -20,6 +20,7 @@ constexpr int NSTAGES = 2;
 
 typedef __attribute__((ext_vector_type(4))) short s16x4_t;
 typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;   // per-lane byte offsets of up to four tile loads
 
 constexpr int GROUP_M = 8;   // m tiles per swizzle group (L2 reuse of the B tiles)
 
@@ -42,7 +43,7 @@ struct DirectStage {
   static constexpr int ELEMS = ROWS * BKT;
   static constexpr int NCH = ROWS * BKT / 8;             // 16-byte chunks
   static constexpr int NI = NCH / NTHR;                  // wave-wide loads per wave
-  static_assert(NCH % NTHR == 0, "tile must split evenly over the waves");
+  static_assert(NCH % NTHR == 0 && NI <= 4, "tile must split evenly over the waves, at most four loads per lane");
   static constexpr int CPR = LAYOUT == 0 ? BKT / 8 : ROWS / 8;   // chunks per LDS row
   static constexpr int RPB = LAYOUT == 0 ? 16 / CPR : 1;         // LDS rows per 256 bytes (LAYOUT 0)
 
@@ -91,6 +92,58 @@ struct DirectStage {
       const bf16_t *src = ((lr >> 5) & 1 ? bu : bg) + (long long)f * ld + k0 + kc * 8;
       if (f >= F) src = (const bf16_t *)&g_zero16;
       __builtin_amdgcn_global_load_lds((gbl_void_t *)src, (lds_void_t *)(S + q * 512), 16, 0, 0);
+    }
+  }
+  // Fast path of the main loop: every lane keeps one 32-bit byte offset per load, relative to a tile
+  // origin that is uniform over the block, so a k step costs scalar pointer arithmetic only and the
+  // loads take the (scalar base + lane offset) form.  Rows past the matrix edge are clamped onto the
+  // last valid row (8-row chunk): they only feed accumulator rows / columns that are never stored.
+  // Tiles that cross the end of the k range go through issue() instead (zero fill).
+  static __device__ __forceinline__ u32x4_t lane_offsets(long long ld, int row0, int rows, int wave) {
+    const int lane = threadIdx.x & 63;
+    u32x4_t off = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int chunk = (wave + (NTHR / 64) * i) * 64 + lane;
+      const int lr = chunk / CPR, pos = chunk % CPR;
+      if constexpr (LAYOUT == 0) {
+        const int kc = pos ^ ((lr / RPB) % CPR);
+        off[i] = (uint32_t)(((long long)min(lr, rows - 1 - row0) * ld + kc * 8) * 2);
+      } else {
+        const int c = POW2 ? pos ^ ((lr & 3) << 2) : (pos + CPR - 4 * (lr & 3)) % CPR;
+        off[i] = (uint32_t)(((long long)lr * ld + min(8 * c, rows - 8 - row0)) * 2);
+      }
+    }
+    return off;
+  }
+  static __device__ __forceinline__ u32x4_t lane_offsets_gu(long long ld, int f0, int F, int wave) {
+    const int lane = threadIdx.x & 63;
+    u32x4_t off = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int chunk = (wave + (NTHR / 64) * i) * 64 + lane;
+      const int lr = chunk / CPR, pos = chunk % CPR;
+      const int kc = pos ^ ((lr / RPB) % CPR);
+      const int fr = (lr >> 6) * 32 + (lr & 31);
+      off[i] = (uint32_t)(((long long)min(fr, F - 1 - f0) * ld + kc * 8) * 2);
+    }
+    return off;
+  }
+  static __device__ __forceinline__ void issue_fast(const char *origin, const u32x4_t off, int wave, bf16_t *S) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int q = wave + (NTHR / 64) * i;
+      __builtin_amdgcn_global_load_lds((gbl_void_t *)(origin + off[i]), (lds_void_t *)(S + q * 512), 16, 0, 0);
+    }
+  }
+  // SwiGLU mode: a wave-wide load covers 8 LDS rows, so it reads gate rows or up rows, never both
+  static __device__ __forceinline__ void issue_fast_gu(const char *origin_g, const char *origin_u, const u32x4_t off, int wave, bf16_t *S) {
+    static_assert(LAYOUT == 0 && CPR == 8, "gate/up interleaving is defined for k-contiguous 64-wide tiles");
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int q = wave + (NTHR / 64) * i;
+      const char *origin = (q >> 2) & 1 ? origin_u : origin_g;
+      __builtin_amdgcn_global_load_lds((gbl_void_t *)(origin + off[i]), (lds_void_t *)(S + q * 512), 16, 0, 0);
     }
   }
   // per-lane fragment address pieces
@@ -171,7 +224,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(const Gemm
   const GemmNSeg &S = p.ns[s];
   const int m0 = mt_l * BM, n0 = p.swiglu ? nt_g * (BN / 2) : (nt_g - p.nt_start[s]) * BN;
   const int M = G.M, N = S.N, K = p.K;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave / WGN, wn = wave % WGN;
 
   f32x16_t acc[TM][TN];
@@ -188,20 +241,19 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(const Gemm
   const int kt0 = (int)blockIdx.y * nk_per;
   const int nk = max(0, min(nk_per, nk_all - kt0));
   const int n_it = nk * G.npass;
-  auto issue = [&](int it, int stage) {
-    const int pass = it / nk, kt = kt0 + it - pass * nk;
-    bf16_t *st = lds + stage * STAGE;
-    SA::issue(G.a[pass == 1 ? 1 : 0], p.lda, m0, M, kt * BKT, K, st);
-    if (p.n_kseg > 1) {
-      int ks = 0;
-      while (ks + 1 < p.n_kseg && kt * BKT >= p.kseg_start[ks + 1]) ++ks;
-      SB::issue(p.kseg_b[ks], p.ldb, n0, N, kt * BKT - p.kseg_start[ks], p.kseg_start[ks + 1] - p.kseg_start[ks], st + SA::ELEMS);
-    } else if (p.swiglu) {
-      if constexpr (LB == 0) SB::issue_gu(p.ns[0].b[pass == 2 ? 1 : 0], p.ns[1].b[pass == 2 ? 1 : 0], p.ldb, n0, N, kt * BKT, st + SA::ELEMS);
-    } else {
-      SB::issue(S.b[pass == 2 ? 1 : 0], p.ldb, n0, N, kt * BKT, K, st + SA::ELEMS);
-    }
-  };
+  // operand bases of this block's row group / column segment (scalar registers), and every lane's
+  // byte offsets inside a tile
+  const char *const a_hi = (const char *)G.a[0], *const a_lo = (const char *)G.a[1];
+  const char *const b_hi = (const char *)(p.swiglu ? p.ns[0].b[0] : S.b[0]), *const b_lo = (const char *)(p.swiglu ? p.ns[0].b[1] : S.b[1]);
+  const char *const u_hi = (const char *)p.ns[1].b[0], *const u_lo = (const char *)p.ns[1].b[1];      // SwiGLU mode: up weights
+  const char *const ks_b0 = (const char *)p.kseg_b[0], *const ks_b1 = (const char *)p.kseg_b[1], *const ks_b2 = (const char *)p.kseg_b[2];
+  const int ks_s1 = p.kseg_start[1], ks_s2 = p.kseg_start[2];
+  const int n_kseg = p.n_kseg, swiglu = p.swiglu;
+  const long long lda = p.lda, ldb = p.ldb;
+  const u32x4_t offA = SA::lane_offsets(lda, m0, M, wave);
+  u32x4_t offB;
+  if constexpr (LB == 0) offB = swiglu ? SB::lane_offsets_gu(ldb, n0, N, wave) : SB::lane_offsets(ldb, n0, N, wave);
+  else offB = SB::lane_offsets(ldb, n0, N, wave);
   typename SA::Frag fa[TM];
   typename SB::Frag fb[TN];
 #pragma unroll
@@ -209,21 +261,54 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(const Gemm
 #pragma unroll
   for (int j = 0; j < TN; ++j) fb[j] = SB::frag_init(wn * WTN + j * 32, lane);
 
-  // prologue: the first P tiles are requested
-#pragma unroll
-  for (int t = 0; t < P; ++t)
-    if (t < n_it) issue(t, t);
-
-  int st_cur = 0;
-  for (int it = 0; it < n_it; ++it) {
-    // tile `it` has landed once at most the loads of the P-1 younger tiles are outstanding
-    if (it + P - 1 < n_it) wait_vmcnt<(P - 1) * LPT>();
-    else wait_vmcnt<0>();
-    __syncthreads();   // tile it visible to every wave; every wave is done with the stage of tile it-1
-    {
-      const int st_new = st_cur == 0 ? NST - 1 : st_cur - 1;   // stage of tile it-1 == stage of tile it+P
-      if (it + P < n_it) issue(it + P, st_new);
+  // One loop requests and multiplies: iteration `it` first waits for tile `it`, then requests tile
+  // it + P into the stage that tile it - 1 has just left, then multiplies tile `it`.  The first P
+  // iterations (it < 0) only request.  (The request code appears once, in line: as a lambda called
+  // from two places its captured bases end up in private memory.)
+  int st_cur = 0, st_req = 0;
+  for (int it = -P; it < n_it; ++it) {
+    if (it >= 0) {
+      // tile `it` has landed once at most the loads of the P-1 younger tiles are outstanding
+      if (it + P - 1 < n_it) wait_vmcnt<(P - 1) * LPT>();
+      else wait_vmcnt<0>();
+      __syncthreads();   // tile it visible to every wave; every wave is done with the stage of tile it-1
     }
+    if (it + P < n_it) {
+      const int t = it + P;
+      const int pass = t >= 2 * nk ? 2 : (t >= nk ? 1 : 0);
+      const int kt = kt0 + t - pass * nk, k0 = kt * BKT;
+      bf16_t *st = lds + st_req * STAGE;
+      st_req = st_req == NST - 1 ? 0 : st_req + 1;
+      if ((LA == 1 || LB == 1) && k0 + BKT > K) {
+        // the tile crosses the end of the k range: per-lane bounds checks and zero fill
+        SA::issue((const bf16_t *)(pass == 1 ? a_lo : a_hi), lda, m0, M, k0, K, st);
+        if (n_kseg > 1) {
+          const int ks = (k0 >= ks_s1 ? 1 : 0) + (n_kseg > 2 && k0 >= ks_s2 ? 1 : 0);
+          const int s0 = ks == 0 ? 0 : (ks == 1 ? ks_s1 : ks_s2), s1 = ks + 1 == n_kseg ? K : (ks == 0 ? ks_s1 : ks_s2);
+          SB::issue((const bf16_t *)(ks == 0 ? ks_b0 : (ks == 1 ? ks_b1 : ks_b2)), ldb, n0, N, k0 - s0, s1 - s0, st + SA::ELEMS);
+        } else {
+          SB::issue((const bf16_t *)(pass == 2 ? b_lo : b_hi), ldb, n0, N, k0, K, st + SA::ELEMS);
+        }
+      } else {
+        const char *ao = (pass == 1 ? a_lo : a_hi) + (LA == 0 ? (long long)m0 * lda + k0 : (long long)k0 * lda + m0) * 2;
+        SA::issue_fast(ao, offA, wave, st);
+        if (n_kseg > 1) {
+          const int ks = (k0 >= ks_s1 ? 1 : 0) + (n_kseg > 2 && k0 >= ks_s2 ? 1 : 0);
+          const int kl = k0 - (ks == 0 ? 0 : (ks == 1 ? ks_s1 : ks_s2));
+          const char *bo = (ks == 0 ? ks_b0 : (ks == 1 ? ks_b1 : ks_b2)) + (LB == 0 ? (long long)n0 * ldb + kl : (long long)kl * ldb + n0) * 2;
+          SB::issue_fast(bo, offB, wave, st + SA::ELEMS);
+        } else if (swiglu) {
+          if constexpr (LB == 0) {
+            const long long o = ((long long)n0 * ldb + k0) * 2;
+            SB::issue_fast_gu((pass == 2 ? b_lo : b_hi) + o, (pass == 2 ? u_lo : u_hi) + o, offB, wave, st + SA::ELEMS);
+          }
+        } else {
+          const char *bo = (pass == 2 ? b_lo : b_hi) + (LB == 0 ? (long long)n0 * ldb + k0 : (long long)k0 * ldb + n0) * 2;
+          SB::issue_fast(bo, offB, wave, st + SA::ELEMS);
+        }
+      }
+    }
+    if (it < 0) continue;
     const bf16_t *Ac = lds + st_cur * STAGE, *Bc = Ac + SA::ELEMS;
     bf16x8_t af[2][TM], bfr[2][TN];
 #pragma unroll
@@ -421,6 +506,7 @@ hipError_t gemm_launch(int LA, int LB, GemmParams &p, hipStream_t stream, const 
   if (p.k_splits > 1 && (p.resid_kind || p.out_bf16 || p.c_split_stride <= 0)) { *why = "gemm: split-K needs fp32 output without residual"; return hipErrorInvalidValue; }
   if ((LA == 0 || LB == 0) && p.K % BK) { *why = "gemm: K of a k-contiguous operand must be a multiple of 64"; return hipErrorInvalidValue; }
   if (p.lda % 8 || p.ldb % 8) { *why = "gemm: leading dimension not a multiple of 8"; return hipErrorInvalidValue; }
+  if (p.lda <= 0 || p.ldb <= 0 || p.lda >= (1 << 22) || p.ldb >= (1 << 22)) { *why = "gemm: leading dimension out of range"; return hipErrorInvalidValue; }
   for (int g = 0; g < p.n_mg; ++g) {
     const GemmMGroup &G = p.mg[g];
     if (G.M < 0 || G.npass < 1 || G.npass > 3) { *why = "gemm: bad row group"; return hipErrorInvalidValue; }
