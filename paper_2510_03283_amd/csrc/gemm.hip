@@ -20,6 +20,7 @@ constexpr int NSTAGES = 2;
 
 typedef __attribute__((ext_vector_type(4))) short s16x4_t;
 typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;   // per-lane byte offsets of up to four tile loads
 
 constexpr int GROUP_M = 8;   // m tiles per swizzle group (L2 reuse of the B tiles)
@@ -146,37 +147,62 @@ struct DirectStage {
       __builtin_amdgcn_global_load_lds((gbl_void_t *)(origin + off[i]), (lds_void_t *)(S + q * 512), 16, 0, 0);
     }
   }
-  // per-lane fragment address pieces
-  struct Frag { int base; int sw; };
-  static __device__ __forceinline__ Frag frag_init(int r0, int lane) {
-    Frag f;
-    if constexpr (LAYOUT == 0) {
-      const int row = r0 + (lane & 31);
-      f.base = row * BKT;
-      f.sw = (row / RPB) % CPR;
-    } else {
-      const int grp = lane >> 4, j = lane & 15;
-      const int cl = (r0 >> 3) + 2 * (grp & 1) + ((j & 3) >> 1);
-      const int chunk = POW2 ? cl ^ ((j >> 2) << 2) : (cl + 4 * (j >> 2)) % CPR;
-      f.base = (8 * (grp >> 1) + (j >> 2)) * ROWS + chunk * 8 + 4 * (j & 1);
-      f.sw = 0;
+  // MFMA fragments (8 consecutive k of one row per lane).  The LDS reads are issued as asm and the
+  // kernel counts them itself (s_waitcnt lgkmcnt(n) before the MFMAs that need them): while a direct
+  // global->LDS load is in flight the compiler's own wait insertion turns every wait for an LDS
+  // read into a wait for ALL outstanding LDS reads, which serialises fragment reads and MFMAs.
+  // A read's result must not be touched before that wait; cook() turns it into the MFMA operand.
+  static constexpr int RPF = LAYOUT == 0 ? 1 : 2;          // LDS read instructions per fragment
+  struct Raw { u32x4_t q; u32x2_t lo, hi; };                // q: k-contiguous tile; lo, hi: transposing reads
+  // per-lane byte offsets inside a tile: LAYOUT 0: v[kk] for the lane's first fragment at k step kk
+  // (the swizzle depends on kk; fragment i sits i * 32 rows further); LAYOUT 1: v[i] for fragment i
+  // at k step 0 (k step kk sits 16 kk rows further)
+  struct FragAddr { uint32_t v[4]; };
+  template <int NF>
+  static __device__ __forceinline__ FragAddr frag_addr(int r0, int lane) {
+    static_assert(NF <= 4 && BKT / 16 <= 4, "at most four fragments per wave and four k steps per tile");
+    FragAddr f;
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      if constexpr (LAYOUT == 0) {
+        const int row = r0 + (lane & 31);
+        const int c = (2 * x + (lane >> 5)) ^ ((row / RPB) % CPR);
+        f.v[x] = (uint32_t)((row * BKT + c * 8) * 2);
+      } else {
+        const int grp = lane >> 4, j = lane & 15;
+        const int cl = ((r0 + 32 * x) >> 3) + 2 * (grp & 1) + ((j & 3) >> 1);
+        const int chunk = POW2 ? cl ^ ((j >> 2) << 2) : (cl + 4 * (j >> 2)) % CPR;
+        f.v[x] = x < NF ? (uint32_t)(((8 * (grp >> 1) + (j >> 2)) * ROWS + chunk * 8 + 4 * (j & 1)) * 2) : 0u;
+      }
     }
     return f;
   }
-  static __device__ __forceinline__ bf16x8_t frag(const bf16_t *S, const Frag &f, int kk, int lane) {
+  // tile: LDS byte address of the tile; kk, i: compile-time constants at every call site
+  static __device__ __forceinline__ Raw read(uint32_t tile, const FragAddr &f, int kk, int i) {
+    Raw r;
     if constexpr (LAYOUT == 0) {
-      const int c = (2 * kk + (lane >> 5)) ^ f.sw;
-      return *(const bf16x8_t *)(S + f.base + c * 8);
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r.q) : "v"(tile + f.v[kk]), "i"(i * 32 * BKT * 2));
     } else {
-      const bf16_t *p = S + f.base + kk * 16 * ROWS;
-      const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)p);
-      const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t *)(p + 4 * ROWS));
-      typedef __attribute__((ext_vector_type(8))) short s16x8_t;
-      const s16x8_t v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r.lo) : "v"(tile + f.v[i]), "i"(kk * 16 * ROWS * 2));
+      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r.hi) : "v"(tile + f.v[i]), "i"(kk * 16 * ROWS * 2 + 4 * ROWS * 2));
+    }
+    return r;
+  }
+  static __device__ __forceinline__ bf16x8_t cook(const Raw &r) {
+    if constexpr (LAYOUT == 0) {
+      return __builtin_bit_cast(bf16x8_t, r.q);
+    } else {
+      const u32x4_t v = {r.lo[0], r.lo[1], r.hi[0], r.hi[1]};
       return __builtin_bit_cast(bf16x8_t, v);
     }
   }
 };
+
+template <int N>
+__device__ __forceinline__ void wait_lgkmcnt() {   // lgkmcnt <= N, no wait on the other counters
+  static_assert(N >= 0 && N <= 15, "4-bit counter");
+  __builtin_amdgcn_s_waitcnt(15 | (7 << 4) | (N << 8) | (3 << 14));
+}
 
 template <int BM, int BN, int WGM, int WGN, int LA, int LB, int BKT, int NST>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(const GemmParams p) {
@@ -254,12 +280,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(const Gemm
   u32x4_t offB;
   if constexpr (LB == 0) offB = swiglu ? SB::lane_offsets_gu(ldb, n0, N, wave) : SB::lane_offsets(ldb, n0, N, wave);
   else offB = SB::lane_offsets(ldb, n0, N, wave);
-  typename SA::Frag fa[TM];
-  typename SB::Frag fb[TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i) fa[i] = SA::frag_init(wm * WTM + i * 32, lane);
-#pragma unroll
-  for (int j = 0; j < TN; ++j) fb[j] = SB::frag_init(wn * WTN + j * 32, lane);
+  const typename SA::FragAddr fa = SA::template frag_addr<TM>(wm * WTM, lane);
+  const typename SB::FragAddr fb = SB::template frag_addr<TN>(wn * WTN, lane);
+  const uint32_t lds_addr = (uint32_t)(uintptr_t)(lds_void_t *)lds;      // LDS byte address of stage 0
+  constexpr int RPS = TM * SA::RPF + TN * SB::RPF;                       // LDS read instructions per k step
+  static_assert(RPS <= 15, "the reads of one k step must fit the 4-bit LDS counter");
 
   // One loop requests and multiplies: iteration `it` first waits for tile `it`, then requests tile
   // it + P into the stage that tile it - 1 has just left, then multiplies tile `it`.  The first P
@@ -309,26 +334,35 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(const Gemm
       }
     }
     if (it < 0) continue;
-    const bf16_t *Ac = lds + st_cur * STAGE, *Bc = Ac + SA::ELEMS;
-    bf16x8_t af[2][TM], bfr[2][TN];
+    const uint32_t Ac = lds_addr + st_cur * (STAGE * 2), Bc = Ac + SA::ELEMS * 2;
+    typename SA::Raw ra[2][TM];
+    typename SB::Raw rb[2][TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) af[0][i] = SA::frag(Ac, fa[i], 0, lane);
+    for (int i = 0; i < TM; ++i) ra[0][i] = SA::read(Ac, fa, 0, i);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) bfr[0][j] = SB::frag(Bc, fb[j], 0, lane);
+    for (int j = 0; j < TN; ++j) rb[0][j] = SB::read(Bc, fb, 0, j);
 #pragma unroll
     for (int kk = 0; kk < NKK; ++kk) {
       if (kk + 1 < NKK) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) af[(kk + 1) & 1][i] = SA::frag(Ac, fa[i], kk + 1, lane);
+        for (int i = 0; i < TM; ++i) ra[(kk + 1) & 1][i] = SA::read(Ac, fa, kk + 1, i);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) bfr[(kk + 1) & 1][j] = SB::frag(Bc, fb[j], kk + 1, lane);
+        for (int j = 0; j < TN; ++j) rb[(kk + 1) & 1][j] = SB::read(Bc, fb, kk + 1, j);
+        wait_lgkmcnt<RPS>();          // the fragments of step kk are in; those of step kk + 1 may be in flight
+      } else {
+        wait_lgkmcnt<0>();
       }
       __builtin_amdgcn_sched_barrier(0);
+      bf16x8_t af[TM], bfr[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) af[i] = SA::cook(ra[kk & 1][i]);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) bfr[j] = SB::cook(rb[kk & 1][j]);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
     st_cur = st_cur == NST - 1 ? 0 : st_cur + 1;
