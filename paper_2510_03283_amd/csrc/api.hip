@@ -228,7 +228,7 @@ BwdWs plan_bwd(const Dims &D, size_t Tf, Bump &w) {
   B.dv = w.take<float>(Tf * D.kd);
   B.dqkv = w.take<bf16_t>(Tf * D.nqkv);
   B.da = w.take<float>(Tf * D.d);
-  B.dg_part = w.take<float>((size_t)DG_PARTS * D.d);
+  B.dg_part = w.take<float>((size_t)(DG_PARTS + COLSUM_SLICES) * D.d);     // partial rows + scratch of their column sum
   return B;
 }
 
@@ -335,7 +335,7 @@ DpoWs plan_dpo(const Dims &D, size_t R, size_t n_seq, Bump &w) {
   P.dl = w.take<bf16_t>(R * D.V);
   P.dn = w.take<float>(R * D.d);
   P.dn_part = w.take<float>(R * D.d * (size_t)(gemm_suggest_k_splits((int)R, D.d, D.V) > 1 ? gemm_suggest_k_splits((int)R, D.d, D.V) : 0));
-  P.dg_part = w.take<float>((size_t)DG_PARTS * D.d);
+  P.dg_part = w.take<float>((size_t)(DG_PARTS + COLSUM_SLICES) * D.d);
   if (!D.bf) {
     P.e_hi = w.take<bf16_t>((size_t)D.V * D.d);
     P.e_lo = w.take<bf16_t>((size_t)D.V * D.d);
@@ -980,7 +980,7 @@ static int layer_bwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
   // RMSNorm (MLP) backward: dx1 = dy + ...
   prof_mark(h, st, T_RMSNORM);
   HIP_TRY(launch_rmsnorm_bwd(B.db, S.x1, false, nullptr, w->g_mlp, D.bf, S.rstd2, dy_ft, Tf, D.d, B.dx1, B.dx1_bf, B.dg_part, n_part, st), "rmsnorm2 bwd");
-  if (grads->g_mlp) { prof_mark(h, st, T_MISC); HIP_TRY(launch_colsum(B.dg_part, n_part, D.d, grads->g_mlp, acc, st), "dg2");
+  if (grads->g_mlp) { prof_mark(h, st, T_MISC); HIP_TRY(launch_colsum(B.dg_part, n_part, D.d, B.dg_part + (size_t)DG_PARTS * D.d, grads->g_mlp, acc, st), "dg2");
   }
   // attention output projection.  Adapter variant: dt = dx1 (s B_o) is a skinny product that runs
   // beside the main one; then dattn += dt A_o ; dB_o = dx1^T (s t) with the saved s t ; dA_o = dt^T o.
@@ -1120,7 +1120,7 @@ static int layer_bwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
   // RMSNorm (attention) backward: dx = dx1 + ...
   prof_mark(h, st, T_RMSNORM);
   HIP_TRY(launch_rmsnorm_bwd(B.da, (const char *)x + (size_t)I.Ti * D.d * es, D.bf, nullptr, w->g_attn, D.bf, S.rstd1, B.dx1, Tf, D.d, dx_ft, nullptr, B.dg_part, n_part, st), "rmsnorm1 bwd");
-  if (grads->g_attn) { prof_mark(h, st, T_MISC); HIP_TRY(launch_colsum(B.dg_part, n_part, D.d, grads->g_attn, acc, st), "dg1");
+  if (grads->g_attn) { prof_mark(h, st, T_MISC); HIP_TRY(launch_colsum(B.dg_part, n_part, D.d, B.dg_part + (size_t)DG_PARTS * D.d, grads->g_attn, acc, st), "dg1");
   }
   prof_mark(h, st, -1);
   HIP_TRY(side_join(h, st), "join side stream");
@@ -1252,7 +1252,7 @@ static int dpo_impl(mace_handle_t h, const float *h_ft, const void *g_final, con
       }
     } else
     HIP_TRY(launch_rmsnorm_bwd(P.dn, h_ft, false, P.row_idx, g_final, D.bf, P.rstd, nullptr, Ri, D.d, dx_dst, nullptr, P.dg_part, n_part, st), "final rmsnorm bwd");
-    if (dg_final) { prof_mark(h, st, T_MISC); HIP_TRY(launch_colsum(P.dg_part, n_part, D.d, dg_final, acc, st), "dg_final");
+    if (dg_final) { prof_mark(h, st, T_MISC); HIP_TRY(launch_colsum(P.dg_part, n_part, D.d, P.dg_part + (size_t)DG_PARTS * D.d, dg_final, acc, st), "dg_final");
     }
   }
   prof_mark(h, st, -1);

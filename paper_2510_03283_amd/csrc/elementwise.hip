@@ -113,33 +113,24 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const float *dy, const
   }
 }
 
-// 32 columns per block; the 32 thread rows of a block stride over the partial rows with eight
-// independent loads in flight each (the kernel is latency-bound: a few MB spread over few blocks),
-// then reduce in LDS.  Fixed summation order: deterministic.
-__global__ __launch_bounds__(1024) void colsum_kernel(const float *part, int n_part, int d, float *out, int accumulate) {
-  constexpr int RG = 32;
-  __shared__ float red[RG][33];
-  const int c = threadIdx.x & 31, rg = threadIdx.x >> 5;
-  const int j = blockIdx.x * 32 + c;
-  float s = 0.f;
-  if (j < d) {
-    float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    int i = rg;
-    for (; i + 7 * RG < n_part; i += 8 * RG) {
+// Column sums of the partial rows in two launches: slice y of COLSUM_SLICES sums the rows y, y + S,
+// y + 2S, ... of 256 adjacent columns (1 KB contiguous per row, eight loads in flight per thread) into
+// row y of a scratch buffer; the second launch (n_slices rows, slices == 1) adds those rows in a fixed
+// order: deterministic.  (A block that walks many rows of a narrow column strip puts all its loads, a
+// power-of-two stride apart, on the same memory channel.)
+__global__ __launch_bounds__(256) void colsum_kernel(const float *part, int n_part, int d, int slices, float *out, int accumulate) {
+  const int j = blockIdx.x * 256 + threadIdx.x, y = blockIdx.y;
+  if (j >= d) return;
+  float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  int i = y;
+  for (; i + 7 * slices < n_part; i += 8 * slices) {
 #pragma unroll
-      for (int u = 0; u < 8; ++u) a[u] += part[(size_t)(i + RG * u) * d + j];
-    }
-    for (; i < n_part; i += RG) a[0] += part[(size_t)i * d + j];
-    s = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
+    for (int u = 0; u < 8; ++u) a[u] += part[(size_t)(i + slices * u) * d + j];
   }
-  red[rg][c] = s;
-  __syncthreads();
-  if (rg == 0 && j < d) {
-    float t = 0.f;
-#pragma unroll
-    for (int k = 0; k < RG; ++k) t += red[k][c];
-    out[j] = accumulate ? out[j] + t : t;
-  }
+  for (; i < n_part; i += slices) a[0] += part[(size_t)i * d + j];
+  const float t = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
+  float *o = out + (size_t)y * d + j;
+  *o = accumulate ? *o + t : t;
 }
 
 // ------------------------------------------------------------------ rotary embedding
@@ -317,8 +308,17 @@ hipError_t launch_rmsnorm_bwd(const float *dy, const void *x, bool x_bf16, const
   return hipGetLastError();
 }
 
-hipError_t launch_colsum(const float *part, int n_part, int d, float *out, int accumulate, hipStream_t st) {
-  hipLaunchKernelGGL(colsum_kernel, dim3(cdiv(d, 32)), dim3(1024), 0, st, part, n_part, d, out, accumulate);
+hipError_t launch_colsum(const float *part, int n_part, int d, float *scratch, float *out, int accumulate, hipStream_t st) {
+  const int slices = n_part >= 4 * COLSUM_SLICES ? COLSUM_SLICES : 1;
+  const dim3 blk(256);
+  if (slices > 1) {
+    hipLaunchKernelGGL(colsum_kernel, dim3(cdiv(d, 256), slices), blk, 0, st, part, n_part, d, slices, scratch, 0);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    part = scratch;
+    n_part = slices;
+  }
+  hipLaunchKernelGGL(colsum_kernel, dim3(cdiv(d, 256), 1), blk, 0, st, part, n_part, d, 1, out, accumulate);
   return hipGetLastError();
 }
 

@@ -20,8 +20,9 @@ hipError_t launch_rmsnorm_bwd(const float *dy, const void *x, bool x_bf16, const
                               bool g_bf16, const float *rstd, const float *resid, int rows, int d,
                               float *dx_out, bf16_t *dx_bf, float *dg_partial, int n_part, hipStream_t st,
                               int dense_out = 0);
-// out[j] (+)= sum_i part[i, j]
-hipError_t launch_colsum(const float *part, int n_part, int d, float *out, int accumulate, hipStream_t st);
+// out[j] (+)= sum over the n_part rows of part[:, j]; scratch: COLSUM_SLICES * d floats.
+constexpr int COLSUM_SLICES = 32;
+hipError_t launch_colsum(const float *part, int n_part, int d, float *scratch, float *out, int accumulate, hipStream_t st);
 // Rotary embedding of q and k inside qkv fp32 [rows, (Hq+2Hkv)*hd], split into head-major bf16
 // outputs q [rows, Hq*hd], k, v [rows, Hkv*hd]; optionally scatter k, v (rounded to the cache
 // type) into the paged cache at slot_mapping (null = no cache write).
