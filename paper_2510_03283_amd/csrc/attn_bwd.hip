@@ -6,7 +6,8 @@
 //  * dkdv kernel: a wave owns 32 keys (a lane owns one key column of S = Q K^T and dP = dO V^T),
 //    walks the queries of every query head of its GQA group, and accumulates
 //    dV^T = dO^T P and dK^T = Q^T dS.
-// P is recomputed from the saved log-sum-exp; D = rowsum(dO * O) comes from a small pre-kernel.
+// P is recomputed from the saved log-sum-exp; D = rowsum(dO * O) is formed by the dq kernel from the
+// fragments it loads anyway and handed to the dk/dv kernel through memory.
 // Tiles of 64 rows go global -> LDS directly in their memory layout, two stages deep; the same
 // tile feeds the products that reduce over the head dimension (16-byte reads) and those that
 // reduce over the tile rows (transposing reads), see attn_tile.h.
@@ -25,24 +26,12 @@ __device__ __forceinline__ bf16x8_t pack8(const float *v) {
   return as_bf8(make_uint4(cvt_pk_bf16(v[0], v[1]), cvt_pk_bf16(v[2], v[3]), cvt_pk_bf16(v[4], v[5]), cvt_pk_bf16(v[6], v[7])));
 }
 
-// ------------------------------------------------------------------ D = rowsum(dO * O)
-__global__ __launch_bounds__(256) void attn_dvec_kernel(const bf16_t *__restrict__ o, const bf16_t *__restrict__ d_o,
-                                                        int Hq, int hd, float *__restrict__ dvec) {
-  const int r = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  for (int h = wave; h < Hq; h += 4) {
-    const size_t b = ((size_t)r * Hq + h) * hd;
-    float s = 0.f;
-    for (int e = lane; e < hd; e += 64) s += bf2f(o[b + e]) * bf2f(d_o[b + e]);
-    s = wave_sum(s);
-    if (lane == 0) dvec[(size_t)r * Hq + h] = s;
-  }
-}
-
 // ------------------------------------------------------------------ dQ
 template <int HD>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
-                                                          const bf16_t *__restrict__ v, const bf16_t *__restrict__ d_o,
-                                                          const float *__restrict__ lse, const float *__restrict__ dvec,
+                                                          const bf16_t *__restrict__ v, const bf16_t *__restrict__ o,
+                                                          const bf16_t *__restrict__ d_o,
+                                                          const float *__restrict__ lse, float *__restrict__ dvec,
                                                           const int32_t *__restrict__ seg, int row_base, int Hq, int Hkv,
                                                           float *__restrict__ dq, const int32_t *__restrict__ excl_lo,
                                                           const int32_t *__restrict__ excl_hi) {
@@ -69,23 +58,33 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16_t *__res
   };
   issue_tile(0);
 
+  // q and dO fragments of this lane's query; D = rowsum(dO * O) is formed on the way (each lane of the pair
+  // (j, j + 32) holds half of the row) and written out for the dk/dv kernel
   bf16x8_t qf[NKK], dof[NKK];
+  float dpart = 0.f;
 #pragma unroll
   for (int kk = 0; kk < NKK; ++kk) {
-    uint4 a = make_uint4(0, 0, 0, 0), b = make_uint4(0, 0, 0, 0);
+    uint4 a = make_uint4(0, 0, 0, 0), b = make_uint4(0, 0, 0, 0), c = make_uint4(0, 0, 0, 0);
     if (qi < L) {
-      const size_t o = (size_t)(r0 + qi) * qld + (size_t)h * HD + kk * 16 + g * 8;
-      a = *(const uint4 *)(q + o);
-      b = *(const uint4 *)(d_o + o);
+      const size_t off = (size_t)(r0 + qi) * qld + (size_t)h * HD + kk * 16 + g * 8;
+      a = *(const uint4 *)(q + off);
+      b = *(const uint4 *)(d_o + off);
+      c = *(const uint4 *)(o + off);
     }
     qf[kk] = as_bf8(a);
     dof[kk] = as_bf8(b);
+    const uint32_t bw[4] = {b.x, b.y, b.z, b.w}, cw[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      dpart += __uint_as_float(bw[e] << 16) * __uint_as_float(cw[e] << 16) +
+               __uint_as_float(bw[e] & 0xffff0000u) * __uint_as_float(cw[e] & 0xffff0000u);
   }
+  const float dv_ = dpart + __shfl_xor(dpart, 32);
   const float sc = 1.4426950408889634f / sqrtf((float)HD), rs = 1.0f / sqrtf((float)HD);
-  float lse2 = 0.f, dv_ = 0.f;
+  float lse2 = 0.f;
   if (qi < L) {
     lse2 = lse[(size_t)(r0 + qi) * Hq + h] * 1.4426950408889634f;
-    dv_ = dvec[(size_t)(r0 + qi) * Hq + h];
+    if (g == 0) dvec[(size_t)(r0 + qi) * Hq + h] = dv_;
   }
   // MFMA row j reads tile row swap23(j): register r = 8*mm + e then holds key 16*mm + 8*g + e
   const typename T::FragK fk = T::frag_k_init(swap23(j));
@@ -295,12 +294,9 @@ hipError_t launch_t(const bf16_t *q, const bf16_t *k, const bf16_t *v, const bf1
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL(attn_dvec_kernel, dim3(rows), dim3(256), 0, st, o, d_o, Hq, HD, dvec);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
   dim3 grid_q(cdiv(max_len, 128), n_seq, Hq), grid_k(cdiv(max_len, 128), n_seq, Hkv);
-  hipLaunchKernelGGL((attn_bwd_dq_kernel<HD>), grid_q, dim3(256), lds_q, st, q, k, v, d_o, lse, dvec, seg, row_base, Hq, Hkv, dq, excl_lo, excl_hi);
-  e = hipGetLastError();
+  hipLaunchKernelGGL((attn_bwd_dq_kernel<HD>), grid_q, dim3(256), lds_q, st, q, k, v, o, d_o, lse, dvec, seg, row_base, Hq, Hkv, dq, excl_lo, excl_hi);
+  hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((attn_bwd_dkdv_kernel<HD>), grid_k, dim3(256), lds_k, st, q, k, v, d_o, lse, dvec, seg, row_base, Hq, Hkv, dk, dv, excl_lo, excl_hi);
   return hipGetLastError();

@@ -99,7 +99,7 @@ hipError_t launch_head_norm_stats(const float *norms, const int32_t *t_count, in
                                   int window, float tau, int32_t *prune, hipStream_t st);
 // ---- attn_bwd.hip ----------------------------------------------------------------------------
 // Backward of the varlen causal attention of the fine-tune sequences (bf16 operands, fp32 out).
-// dvec: fp32 scratch [rows, Hq].
+// dvec: fp32 scratch [rows, Hq] (rowsum(dO * O), written by the dq kernel, read by the dk/dv kernel).
 hipError_t launch_attn_bwd(const bf16_t *q, const bf16_t *k, const bf16_t *v, const bf16_t *o, const bf16_t *d_o,
                            const float *lse, const int32_t *seg, int row_base, int n_seq, int max_len, int rows,
                            int Hq, int Hkv, int hd, float *dvec, float *dq, float *dk, float *dv, hipStream_t st,
