@@ -40,9 +40,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16_t *__res
   constexpr int STAGE = 2 * T::ELEMS;       // K tile, V tile
   extern __shared__ __align__(16) unsigned char smem_raw[];
   bf16_t *lds = (bf16_t *)smem_raw;         // [2][STAGE]
-  const int s = blockIdx.y, h = blockIdx.z, kvh = h / (Hq / Hkv);
+  const int h = blockIdx.x, s = blockIdx.y, kvh = h / (Hq / Hkv);
   const int r0 = seg[s] - row_base, L = seg[s + 1] - seg[s];
-  const int q0 = (gridDim.x - 1 - blockIdx.x) * 128;
+  const int q0 = (gridDim.z - 1 - blockIdx.z) * 128;
   if (q0 >= L) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, j = lane & 31;
   const int qw0 = q0 + wave * 32, qi = qw0 + j;
@@ -162,9 +162,9 @@ __global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(co
   constexpr int STAGE = 2 * T::ELEMS + 4 * TB;    // Q tile, dO tile, lse[TB] and D[TB] as fp32 (2 bf16 slots each)
   extern __shared__ __align__(16) unsigned char smem_raw[];
   bf16_t *lds = (bf16_t *)smem_raw;               // [2][STAGE]
-  const int s = blockIdx.y, kvh = blockIdx.z, grp = Hq / Hkv;
+  const int kvh = blockIdx.x, s = blockIdx.y, grp = Hq / Hkv;
   const int r0 = seg[s] - row_base, L = seg[s + 1] - seg[s];
-  const int k0 = blockIdx.x * 128;
+  const int k0 = blockIdx.z * 128;
   if (k0 >= L) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, j = lane & 31;
   const int kw0 = k0 + wave * 32, ki = kw0 + j;      // this lane's key
@@ -294,7 +294,7 @@ hipError_t launch_t(const bf16_t *q, const bf16_t *k, const bf16_t *v, const bf1
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  dim3 grid_q(cdiv(max_len, 128), n_seq, Hq), grid_k(cdiv(max_len, 128), n_seq, Hkv);
+  dim3 grid_q(Hq, n_seq, cdiv(max_len, 128)), grid_k(Hkv, n_seq, cdiv(max_len, 128));
   hipLaunchKernelGGL((attn_bwd_dq_kernel<HD>), grid_q, dim3(256), lds_q, st, q, k, v, o, d_o, lse, dvec, seg, row_base, Hq, Hkv, dq, excl_lo, excl_hi);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -309,7 +309,7 @@ hipError_t launch_attn_bwd(const bf16_t *q, const bf16_t *k, const bf16_t *v, co
                            int Hq, int Hkv, int hd, float *dvec, float *dq, float *dk, float *dv, hipStream_t st,
                            const int32_t *excl_lo, const int32_t *excl_hi) {
   if (n_seq <= 0 || rows <= 0) return hipSuccess;
-  if (n_seq > 65535 || Hq > 65535 || ((excl_lo == nullptr) != (excl_hi == nullptr))) return hipErrorInvalidValue;
+  if (n_seq > 65535 || max_len > 65535 * 64 || ((excl_lo == nullptr) != (excl_hi == nullptr))) return hipErrorInvalidValue;
   if (hd == 64) return launch_t<64>(q, k, v, o, d_o, lse, seg, row_base, n_seq, max_len, rows, Hq, Hkv, dvec, dq, dk, dv, st, excl_lo, excl_hi);
   if (hd == 128) return launch_t<128>(q, k, v, o, d_o, lse, seg, row_base, n_seq, max_len, rows, Hq, Hkv, dvec, dq, dk, dv, st, excl_lo, excl_hi);
   return hipErrorInvalidValue;

@@ -48,9 +48,9 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_fwd_kernel(cons
   extern __shared__ __align__(16) unsigned char smem_raw[];
   bf16_t *lds = (bf16_t *)smem_raw;                // [2][STAGE]
 
-  const int s = blockIdx.y, h = blockIdx.z, kvh = h / (Hq / Hkv);
+  const int h = blockIdx.x, s = blockIdx.y, kvh = h / (Hq / Hkv);
   const int r0 = seg[s] - row_base, L = seg[s + 1] - seg[s];
-  const int q0 = (gridDim.x - 1 - blockIdx.x) * QB;      // long tiles first
+  const int q0 = (gridDim.z - 1 - blockIdx.z) * QB;      // long tiles first
   if (q0 >= L) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, j = lane & 31;
   const int qw0 = q0 + wave * 32;                        // first query of this wave
@@ -231,7 +231,7 @@ hipError_t launch_t(const bf16_t *q_hi, const bf16_t *k_hi, const bf16_t *v_hi, 
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  dim3 grid(cdiv(max_len, 32 * NW), n_seq, Hq);
+  dim3 grid(Hq, n_seq, cdiv(max_len, 32 * NW));
   hipLaunchKernelGGL((attn_fwd_kernel<HD, SPLIT, NW, PAGED>), grid, dim3(64 * NW), lds, st, q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, Hq, Hkv, o_hi, o_lo, lse, pg, excl_lo, excl_hi);
   return hipGetLastError();
 }
@@ -243,7 +243,7 @@ hipError_t launch_attn_fwd(const bf16_t *q_hi, const bf16_t *k_hi, const bf16_t 
                            int max_len, int Hq, int Hkv, int hd, bf16_t *o_hi, bf16_t *o_lo, float *lse,
                            hipStream_t st, const int32_t *excl_lo, const int32_t *excl_hi) {
   if (n_seq <= 0 || max_len <= 0) return hipSuccess;
-  if (n_seq > 65535 || Hq > 65535 || ((excl_lo == nullptr) != (excl_hi == nullptr))) return hipErrorInvalidValue;
+  if (n_seq > 65535 || max_len > 65535 * 64 || ((excl_lo == nullptr) != (excl_hi == nullptr))) return hipErrorInvalidValue;
   const bool split = q_lo != nullptr;
   if (split && (!k_lo || !v_lo)) return hipErrorInvalidValue;
   // two-term operands at head dim 128 need 128 KB of LDS per block: 8 waves share it
@@ -258,7 +258,7 @@ hipError_t launch_attn_fwd_paged(const bf16_t *q, const void *cache_k, const voi
                                  const int32_t *block_tables, int max_blocks, const int32_t *prefix_lens, const int32_t *seg,
                                  int row_base, int n_seq, int max_len, int Hq, int Hkv, int hd, bf16_t *o, hipStream_t st) {
   if (n_seq <= 0 || max_len <= 0) return hipSuccess;
-  if (n_seq > 65535 || Hq > 65535 || block_size <= 0 || (block_size & (block_size - 1)) || max_blocks <= 0) return hipErrorInvalidValue;
+  if (n_seq > 65535 || max_len > 65535 * 64 || block_size <= 0 || (block_size & (block_size - 1)) || max_blocks <= 0) return hipErrorInvalidValue;
   int bshift = 0;
   while ((1 << bshift) < block_size) ++bshift;
   const PagedKV pg{(const bf16_t *)cache_k, (const bf16_t *)cache_v, block_tables, prefix_lens, num_blocks, max_blocks, bshift};
