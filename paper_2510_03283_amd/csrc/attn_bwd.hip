@@ -40,7 +40,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16_t *__res
   constexpr int STAGE = 2 * T::ELEMS;       // K tile, V tile
   extern __shared__ __align__(16) unsigned char smem_raw[];
   bf16_t *lds = (bf16_t *)smem_raw;         // [2][STAGE]
-  const int h = blockIdx.x, s = blockIdx.y, kvh = h / (Hq / Hkv);
+  // blocks are dealt to the XCDs round-robin: block x takes head (x % Hkv) * group + x / Hkv, so the query heads
+  // of one kv head (and all their row tiles) run on one XCD and its K and V stay in that XCD's L2
+  const int kvh = blockIdx.x % Hkv, h = kvh * (Hq / Hkv) + blockIdx.x / Hkv, s = blockIdx.y;
   const int r0 = seg[s] - row_base, L = seg[s + 1] - seg[s];
   const int q0 = (gridDim.z - 1 - blockIdx.z) * 128;
   if (q0 >= L) return;
