@@ -148,6 +148,18 @@ def test_block_sizes(torch_mod, bs):
     check_iteration(torch_mod, wl, f"block_size {bs}")
 
 
+@pytest.mark.parametrize("chunk", [512, 1024, 2048, 4096])
+@pytest.mark.parametrize("hq,hkv,hd", [(4, 2, 64), (2, 2, 128)])
+def test_decode_chunk_lengths(torch_mod, monkeypatch, chunk, hq, hkv, hd):
+    """Every tokens-per-block setting of the decode kernel (the launcher picks one from the batch
+    size; the environment override pins it) on contexts below, on and across the chunk edges:
+    the partial soft-max states of one, two and several chunks must merge to the same result."""
+    monkeypatch.setenv("MACE_DECODE_CHUNK", str(chunk))
+    dims = synth.ModelDims(n_q_heads=hq, n_kv_heads=hkv, head_dim=hd, **SMALL)
+    wl = custom_workload("chunks", dims, prefill=[5], decode=[0, 511, 512, 1023, 2047, 2048, 4100, 5000], n_pairs=1, prompt=3, resp=(2, 9))
+    check_iteration(torch_mod, wl, f"decode chunk {chunk} Hq{hq} Hkv{hkv} hd{hd}")
+
+
 @pytest.mark.parametrize("prefill,decode,pairs", [([], [], 2), ([50, 3], [], 0), ([], [40, 2], 0), ([9], [5], 1)])
 def test_empty_classes(torch_mod, prefill, decode, pairs):
     dims = synth.ModelDims(n_q_heads=4, n_kv_heads=4, head_dim=64, **SMALL)
