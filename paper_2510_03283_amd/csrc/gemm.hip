@@ -23,7 +23,8 @@ typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;   // per-lane byte offsets of up to four tile loads
 
-constexpr int GROUP_M = 8;   // m tiles per swizzle group (L2 reuse of the B tiles)
+constexpr int GROUP_M = 8;         // m tiles per swizzle group (L2 reuse of the B tiles)
+constexpr int GROUP_M_MULTI = 4;   // the same for row groups with two-term operands (twice the A bytes per m tile)
 
 // Operand tiles go global -> LDS directly (global_load_lds_dwordx4): no staging registers and no
 // LDS store instructions.  A wave-wide load writes 64 consecutive 16-byte chunks, so LDS tiles
@@ -221,7 +222,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(const Gemm
   // Block -> tile.  Row groups are laid out one after the other in block-id order (the launcher
   // sorts the multi-pass groups first, so the long tiles start first).  Inside a group, the blocks
   // that land on XCD x (block id % 8) take a contiguous chunk of the group's tile list, ordered in
-  // bands of GROUP_M m-tiles, so the tiles resident on one XCD share A and B panels in its L2 and
+  // bands of GROUP_M (GROUP_M_MULTI) m-tiles, so the tiles resident on one XCD share A and B panels in its L2 and
   // every XCD gets the same mix of long and short tiles.
   const int n_ns_eff = p.swiglu ? 1 : p.n_ns;      // SwiGLU mode: one logical column range of F hidden units
   const int total_nt = p.nt_start[n_ns_eff];
@@ -240,9 +241,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(const Gemm
     }
     v += ((int)blockIdx.x - first_blk - ((x - first_blk) & 7)) >> 3;
   }
-  const int grp_sz = GROUP_M * total_nt;
-  const int first_m = (v / grp_sz) * GROUP_M;
-  const int gm = min(mtc - first_m, GROUP_M);
+  const int band = p.mg[g].npass >= 2 ? GROUP_M_MULTI : GROUP_M;
+  const int grp_sz = band * total_nt;
+  const int first_m = (v / grp_sz) * band;
+  const int gm = min(mtc - first_m, band);
   const int mt_l = first_m + (v % grp_sz) % gm, nt_g = (v % grp_sz) / gm;
   int s = 0;
   while (s + 1 < n_ns_eff && nt_g >= p.nt_start[s + 1]) ++s;
