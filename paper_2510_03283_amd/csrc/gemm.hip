@@ -512,8 +512,12 @@ double tile_cost(const GemmParams &p, int slots, double slot_share, double eff) 
   const int ks = p.k_splits > 1 ? p.k_splits : 1;
   int nt = 0;
   for (int s = 0; s < p.n_ns; ++s) nt += cdiv(p.ns[s].N, BN);
-  for (int g = 0; g < p.n_mg; ++g) w += (double)cdiv(p.mg[g].M, BM) * nt * p.mg[g].npass * ks;
-  return std::ceil(w / slots) * BM * BN * slot_share / eff;
+  int longest = 1;                 // a tile's passes run on one CU: no schedule is shorter than the longest tile
+  for (int g = 0; g < p.n_mg; ++g) {
+    w += (double)cdiv(p.mg[g].M, BM) * nt * p.mg[g].npass * ks;
+    if (p.mg[g].M > 0) longest = std::max(longest, p.mg[g].npass);
+  }
+  return std::max(std::ceil(w / slots), (double)longest) * BM * BN * slot_share / eff;
 }
 
 template <int LA, int LB>
