@@ -12,6 +12,7 @@
 #include <cmath>
 #include <cstring>
 #include <utility>
+#include <vector>
 
 namespace {
 
@@ -504,20 +505,33 @@ int g_force_tile = -1;
 // Tile choice.  256x256 tiles (8 waves, one block per CU) do 0.75 LDS fragment reads per MFMA and
 // half the L2 traffic of 128x128 tiles (4 waves, two blocks per CU), but quantise worse on small
 // problems; 192x256 (8 waves) sits between.  Each candidate is priced as
-//   rounds over its (CU x resident block) slots  x  tile area  /  measured relative efficiency,
-// a tile of a row group with p passes counting p times, and the cheapest is launched.
+//   length of its schedule over the (CU x resident block) slots  x  tile area  /  measured relative efficiency,
+// a tile of a row group with p passes taking p time units on its slot, and the cheapest is launched.
 template <int BM, int BN>
 double tile_cost(const GemmParams &p, int slots, double slot_share, double eff) {
-  double w = 0;
   const int ks = p.k_splits > 1 ? p.k_splits : 1;
   int nt = 0;
   for (int s = 0; s < p.n_ns; ++s) nt += cdiv(p.ns[s].N, BN);
-  int longest = 1;                 // a tile's passes run on one CU: no schedule is shorter than the longest tile
+  // The dispatcher hands the next block to whichever slot is free, in block-id order (row groups one
+  // after the other, multi-pass groups first).  Time in passes of one tile: free_at[t] slots fall free at t.
+  double w = 0;
+  for (int g = 0; g < p.n_mg; ++g) w += (double)cdiv(p.mg[g].M, BM) * nt * p.mg[g].npass * ks;
+  std::vector<int> free_at((size_t)(w / slots) + 8, 0);
+  free_at[0] = slots;
+  size_t t = 0, end = 0;
   for (int g = 0; g < p.n_mg; ++g) {
-    w += (double)cdiv(p.mg[g].M, BM) * nt * p.mg[g].npass * ks;
-    if (p.mg[g].M > 0) longest = std::max(longest, p.mg[g].npass);
+    long long n = (long long)cdiv(p.mg[g].M, BM) * nt * ks;
+    const size_t c = (size_t)p.mg[g].npass;
+    while (n > 0) {
+      if (free_at[t] == 0) { ++t; continue; }
+      const int k = (int)std::min<long long>(n, free_at[t]);
+      free_at[t] -= k;
+      free_at[t + c] += k;
+      n -= k;
+      end = std::max(end, t + c);
+    }
   }
-  return std::max(std::ceil(w / slots), (double)longest) * BM * BN * slot_share / eff;
+  return (double)end * BM * BN * slot_share / eff;
 }
 
 template <int LA, int LB>
