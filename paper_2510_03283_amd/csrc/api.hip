@@ -1207,9 +1207,13 @@ static int dpo_impl(mace_handle_t h, const float *h_ft, const void *g_final, con
     prof_mark(h, st, T_RMSNORM);
     HIP_TRY(launch_rmsnorm_fwd(h_ft, false, P.row_idx, g_final, D.bf, Ri, D.d, h->m.rms_eps, P.n_hi, P.n_lo, P.rstd, st), "final rmsnorm");
     GemmParams p = gp_init(D.d, D.d, D.d, D.V);
-    gp_group(p, P.n_hi, P.n_lo, P.logits, nullptr, Ri, D.bf ? 2 : 3);
+    // bf16 weights: one pass over the vocabulary plus the label's logit from the two-term activations
+    // (see label_logit_kernel); fp32 weights keep the three-product form
+    gp_group(p, P.n_hi, P.n_lo, P.logits, nullptr, Ri, D.bf ? 1 : 3);
     gp_seg(p, e_hi, e_lo, D.V, 0);
     TRY(run_gemm(h, 0, 0, p, st, "lm head gemm"));
+    if (D.bf) { prof_mark(h, st, T_MISC); HIP_TRY(launch_label_logit(P.n_hi, P.n_lo, e_hi, P.label, Ri, D.d, D.V, P.logits, st), "label logits");
+    }
     prof_mark(h, st, T_LOGSOFTMAX, 0.0, (double)Ri * D.V * 4.0);
     HIP_TRY(launch_logsoftmax_gather(P.logits, Ri, D.V, P.label, P.logp_t, P.lse, st), "log-softmax");
   }

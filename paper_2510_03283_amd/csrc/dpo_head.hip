@@ -61,6 +61,33 @@ __global__ __launch_bounds__(256) void scatter_rows_kernel(const float *__restri
   }
 }
 
+// The logit of the label, recomputed from the two-term activations: one wave per loss row forms
+// sum_k (n_hi + n_lo)[r, k] * E[label, k] in fp32 and overwrites logits[r, label].  With it the LM
+// head runs one bf16 pass: the rounding of n to bf16 moves every logit of a row by a few 1e-4, which
+// the log-sum-exp averages out (it enters as the rounding error times the soft-max mean of the
+// embeddings), but which would enter the label's own logit - and so log p(label) - at full size.
+__global__ __launch_bounds__(256) void label_logit_kernel(const bf16_t *__restrict__ n_hi, const bf16_t *__restrict__ n_lo,
+                                                          const bf16_t *__restrict__ e, const int32_t *__restrict__ label,
+                                                          int rows, int d, int V, float *__restrict__ logits) {
+  const int lane = threadIdx.x & 63, r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  const int lab = label[r];
+  if (lab < 0 || lab >= V) return;
+  const bf16_t *a = n_hi + (size_t)r * d, *b = n_lo + (size_t)r * d, *w = e + (size_t)lab * d;
+  float s = 0.f;
+  for (int k = lane * 8; k < d; k += 512) {        // d % 8 == 0
+    const uint4 ua = *(const uint4 *)(a + k), ub = *(const uint4 *)(b + k), uw = *(const uint4 *)(w + k);
+    const uint32_t wa[4] = {ua.x, ua.y, ua.z, ua.w}, wb[4] = {ub.x, ub.y, ub.z, ub.w}, ww[4] = {uw.x, uw.y, uw.z, uw.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      s += (__uint_as_float(wa[i] << 16) + __uint_as_float(wb[i] << 16)) * __uint_as_float(ww[i] << 16);
+      s += (__uint_as_float(wa[i] & 0xffff0000u) + __uint_as_float(wb[i] & 0xffff0000u)) * __uint_as_float(ww[i] & 0xffff0000u);
+    }
+  }
+  s = wave_sum(s);
+  if (lane == 0) logits[(size_t)r * V + lab] = s;
+}
+
 // One block per loss row: single pass over the V logits with an online (max, sum) pair.
 __global__ __launch_bounds__(256) void logsoftmax_gather_kernel(const float *__restrict__ logits, int V,
                                                                 const int32_t *__restrict__ label,
@@ -168,6 +195,13 @@ hipError_t launch_logsoftmax_gather(const float *logits, int rows, int V, const 
                                     float *lse, hipStream_t st) {
   if (rows <= 0) return hipSuccess;
   hipLaunchKernelGGL(logsoftmax_gather_kernel, dim3(rows), dim3(256), 0, st, logits, V, label, logp_t, lse);
+  return hipGetLastError();
+}
+
+hipError_t launch_label_logit(const bf16_t *n_hi, const bf16_t *n_lo, const bf16_t *e, const int32_t *label, int rows, int d,
+                              int V, float *logits, hipStream_t st) {
+  if (rows <= 0) return hipSuccess;
+  hipLaunchKernelGGL(label_logit_kernel, dim3(cdiv(rows, 4)), dim3(256), 0, st, n_hi, n_lo, e, label, rows, d, V, logits);
   return hipGetLastError();
 }
 

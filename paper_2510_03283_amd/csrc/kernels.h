@@ -123,6 +123,9 @@ hipError_t launch_loss_rows_shared(const int32_t *pair_offsets, const int32_t *p
 hipError_t launch_scatter_rows(const float *src, const int32_t *row_idx, const int32_t *partner, int rows, int d, float *dst,
                                hipStream_t st);
 // logp_t[r] = logits[r, label[r]] - logsumexp(logits[r, :]); lse[r] kept.
+// logits[r, label[r]] = sum_k (n_hi + n_lo)[r, k] * e[label[r], k] (fp32), for the rows whose label is in range
+hipError_t launch_label_logit(const bf16_t *n_hi, const bf16_t *n_lo, const bf16_t *e, const int32_t *label, int rows, int d,
+                              int V, float *logits, hipStream_t st);
 hipError_t launch_logsoftmax_gather(const float *logits, int rows, int V, const int32_t *label, float *logp_t,
                                     float *lse, hipStream_t st);
 // Per-sequence sums, pair losses, metrics and dloss_mean/dlogp per sequence.
