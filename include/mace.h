@@ -206,8 +206,8 @@ int mace_hybrid_layer_bwd_lora(mace_handle_t h, const mace_layer_w_t *w, const m
  * (dh_ft is always overwritten).
  * Precision: with bf16 weights the vocabulary product takes plain bf16 operands and the logit of each
  * row's label is recomputed from two-term activations (about 16 significand bits), which is the term
- * through which operand rounding reaches log pi(y|x); with fp32 weights every logit is formed from
- * two-term operands. */
+ * through which operand rounding reaches log pi(y|x); with fp32 weights, or with MACE_HEAD_TWO_PASS=1
+ * in the environment at mace_create, every logit is formed from two-term operands. */
 int mace_dpo_logprob_loss(mace_handle_t h, const float *h_ft, const void *g_final, const void *w_lm,
                           const int32_t *token_ids, const int32_t *ft_seq_offsets,
                           const int32_t *ft_seq_offsets_host, const int32_t *prompt_lens,

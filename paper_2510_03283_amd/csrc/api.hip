@@ -30,6 +30,7 @@ struct mace_ctx {
   hipStream_t side = nullptr;
   hipEvent_t ev_fork[N_FORK_EVENTS] = {}, ev_join = nullptr;
   int n_fork = 0;          // forks issued in the current call
+  bool head_two_pass = false;   // MACE_HEAD_TWO_PASS=1 at creation: every logit of the DPO head from two-term activations
   bool prof_on = false;
   unsigned prof_mask = ~0u;        // kernel classes that are timed
   bool prof_open[2] = {false, false};   // per chain: the last mark opened an interval
@@ -489,6 +490,7 @@ int mace_create(mace_handle_t *out, const mace_model_t *model) {
     delete c;
     return hip_fail(e, "mace_create");
   }
+  if (const char *tp = getenv("MACE_HEAD_TWO_PASS")) c->head_two_pass = tp[0] == '1';
   const char *single = getenv("MACE_SINGLE_STREAM");
   if (!(single && single[0] == '1')) {
     e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
@@ -1208,11 +1210,12 @@ static int dpo_impl(mace_handle_t h, const float *h_ft, const void *g_final, con
     HIP_TRY(launch_rmsnorm_fwd(h_ft, false, P.row_idx, g_final, D.bf, Ri, D.d, h->m.rms_eps, P.n_hi, P.n_lo, P.rstd, st), "final rmsnorm");
     GemmParams p = gp_init(D.d, D.d, D.d, D.V);
     // bf16 weights: one pass over the vocabulary plus the label's logit from the two-term activations
-    // (see label_logit_kernel); fp32 weights keep the three-product form
-    gp_group(p, P.n_hi, P.n_lo, P.logits, nullptr, Ri, D.bf ? 1 : 3);
+    // (see label_logit_kernel) unless the context asks for two passes; fp32 weights keep the three-product form
+    const bool one_pass = D.bf && !h->head_two_pass;
+    gp_group(p, P.n_hi, P.n_lo, P.logits, nullptr, Ri, one_pass ? 1 : (D.bf ? 2 : 3));
     gp_seg(p, e_hi, e_lo, D.V, 0);
     TRY(run_gemm(h, 0, 0, p, st, "lm head gemm"));
-    if (D.bf) { prof_mark(h, st, T_MISC); HIP_TRY(launch_label_logit(P.n_hi, P.n_lo, e_hi, P.label, Ri, D.d, D.V, P.logits, st), "label logits");
+    if (one_pass) { prof_mark(h, st, T_MISC); HIP_TRY(launch_label_logit(P.n_hi, P.n_lo, e_hi, P.label, Ri, D.d, D.V, P.logits, st), "label logits");
     }
     prof_mark(h, st, T_LOGSOFTMAX, 0.0, (double)Ri * D.V * 4.0);
     HIP_TRY(launch_logsoftmax_gather(P.logits, Ri, D.V, P.label, P.logp_t, P.lse, st), "log-softmax");

@@ -96,3 +96,12 @@ def test_graph_replay_matches_eager(torch_mod):
             assert torch.equal(it.cache_k, cache0[0]) and torch.equal(it.cache_v, cache0[1])
     finally:
         it.close()
+
+
+def test_two_pass_head_switch(torch_mod, monkeypatch):
+    """MACE_HEAD_TWO_PASS=1 at context creation: every logit of the DPO head is formed from two-term
+    activations (the form with the wider loss margin); same bars, and a loss error well under the
+    default head's."""
+    from test_gpu_parity import check_iteration
+    monkeypatch.setenv("MACE_HEAD_TWO_PASS", "1")
+    check_iteration(torch_mod, synth.make_workload("edge", n_prefill=1, n_decode=2), "edge ft rows, two-pass head")
