@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0
 # rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, scaled by a plain copy, bytes per launch averaged over one step's
 # launches of the class: (workload, kernel class) -> bytes, from the two committed counter summaries
 # (edge GEMM NT class, decode-heavy attention).  Not measured -> null.
-TRAFFIC_BYTES_PER_LAUNCH = {("edge", "gemm_nt"): 6.409e8, ("7b_decode", "attn_decode"): 2.2027e10}
+TRAFFIC_BYTES_PER_LAUNCH = {("edge", "gemm_nt"): 5.735e8, ("7b_decode", "attn_decode"): 2.2027e10}
 
 
 def cpu_baseline(wl, lora=None):
