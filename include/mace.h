@@ -11,9 +11,25 @@
  * Conventions
  *  - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
  *    host memory.  The library never frees or keeps a caller pointer after a call returns.
- *  - All device work is enqueued on the `stream` argument (a hipStream_t passed as void*, NULL =
+ *  - All device work is ordered on the `stream` argument (a hipStream_t passed as void*, NULL =
  *    the default stream).  Calls do not synchronise with the host; outputs are valid once the
- *    caller has synchronised the stream.
+ *    caller has synchronised the stream.  Inside a call, products that nothing later in the call
+ *    depends on (weight gradients, adapter products) may run on one internal stream of the handle,
+ *    forked from `stream` and joined back into it with events before the call returns (also on
+ *    every error return), so the caller sees plain stream order; MACE_OPT_SINGLE_STREAM keeps
+ *    everything on `stream`.
+ *  - A handle carries per-call state (the internal stream, its fork/join events, the launch-plan
+ *    and timing records), so it supports ONE call in flight: calls on one handle must be issued
+ *    from one thread at a time and on one stream (or on streams the caller has ordered against
+ *    each other); use one handle per concurrent stream.  The three iteration calls of a step share
+ *    the caller's workspace and must be issued in stream order.
+ *  - Device memory: the caller owns every buffer.  The only device allocations of the library are
+ *    made in mace_create (rotary frequency table, a few hundred bytes) and released in
+ *    mace_destroy; no entry point allocates or frees device memory otherwise, and none issues a
+ *    memset, so the iteration calls may be captured into a HIP graph.
+ *  - Device-side descriptors (slots, block ids, labels, positions) are bounds-checked by the
+ *    kernels: an out-of-range value never causes a wild access, but the affected row's result is
+ *    then unspecified (see the preconditions at each entry point).
  *  - Every entry point returns MACE_OK (0) or a negative mace_status_t.  Arguments are validated
  *    on the host before anything is launched; mace_last_error() returns a message for the last
  *    failure on the calling thread.  No C++ exception crosses this boundary.
@@ -80,7 +96,8 @@ typedef struct {
   const int32_t *seg_offsets_host; /* host   [n_prefill+n_decode+n_ft_seq+1] first row of every request, last = n_tokens */
   const int32_t *seg_offsets;      /* device copy of the same array */
   const int32_t *positions;        /* device [n_tokens] rotary position of every row */
-  const int32_t *slot_mapping;     /* device [T_p+T_d] cache slot of every inference row, -1 = do not store */
+  const int32_t *slot_mapping;     /* device [T_p+T_d] cache slot of every inference row, -1 = do not store (prefill rows
+                                      only: a decode row reads its own K, V back from the cache, so it must store them) */
   const int32_t *block_tables;     /* device [n_decode, max_blocks_per_req] block ids of the decode requests */
   const int32_t *context_lens_host;/* host   [n_decode] tokens already cached (the new token is not counted) */
   const int32_t *context_lens;     /* device copy of the same array */
@@ -90,7 +107,10 @@ typedef struct {
    * sit at positions prefix.., are appended behind the prefix (slot_mapping computed with
    * start_pos = prefix) and attend to the cached rows through prefill_block_tables[i], which
    * covers prefix + new tokens.  Requests below one node list the same leading blocks.  All three
-   * pointers NULL = no request has a prefix.  Needs a bf16 cache (io_dtype MACE_BF16). */
+   * pointers NULL = no request has a prefix.  Needs a bf16 cache (io_dtype MACE_BF16).
+   * Precondition (not checkable here, block tables live on the device): a block that two requests of
+   * one batch share must be full of prefix tokens, i.e. a shared prefix ends on a block boundary;
+   * otherwise both requests append into that block. */
   const int32_t *prefill_block_tables;      /* device [n_prefill, max_blocks_per_prefill] */
   const int32_t *prefill_prefix_lens_host;  /* host   [n_prefill] */
   const int32_t *prefill_prefix_lens;       /* device copy of the same array */
@@ -108,9 +128,22 @@ typedef struct {
                                       norm-based cache pruning of Section 4.3; NULL = not wanted */
 } mace_batch_t;
 
-/* Create / destroy a handle.  The handle owns a few KB of device tables (rotary frequencies). */
+/* Create / destroy a handle for the device that is current at the call.  The handle owns a few
+ * hundred bytes of device tables (rotary frequencies), one non-blocking stream of default priority
+ * and ten events. */
 int mace_create(mace_handle_t *out, const mace_model_t *model);
 void mace_destroy(mace_handle_t h);
+
+/* Options of a handle; every option is 0 after mace_create.  MACE_INVALID_ARG for an unknown option
+ * or a value outside its range.  Set between calls, never while a call of the handle is in flight.
+ *   MACE_OPT_HEAD_TWO_PASS  1: the DPO head forms every logit from two-term activations (two passes
+ *                           over the vocabulary for bf16 weights); 0: the default head described
+ *                           at mace_dpo_logprob_loss.
+ *   MACE_OPT_SINGLE_STREAM  1: never use the internal stream (bitwise the same results).
+ *   MACE_OPT_DECODE_CHUNK   tokens of context per decode-attention block: 0 = chosen per launch,
+ *                           else a power of two in 512..4096. */
+enum { MACE_OPT_HEAD_TWO_PASS = 1, MACE_OPT_SINGLE_STREAM = 2, MACE_OPT_DECODE_CHUNK = 3 };
+int mace_set_option(mace_handle_t h, int32_t option, int32_t value);
 
 /* Message for the last error on this thread ("" if none). */
 const char *mace_last_error(void);
@@ -136,8 +169,9 @@ int mace_kv_slot_mapping(const int32_t *block_table, int32_t table_len, int32_t 
 int mace_kv_cache_append(mace_handle_t h, mace_kv_cache_t *cache, const void *k_new, const void *v_new,
                          const int32_t *slot_mapping, int32_t n, void *stream);
 
-/* Gather the rows of positions 0..ctx_len-1 of one request, in order, into k_out, v_out
- * [ctx_len, Hkv, hd] (device, io_dtype; bit-exact copies).  block_table: device
+/* The read side of the paged cache of Section 5 (the engine's PagedAttention-style cache; "KV cache
+ * accumulation" over the decode steps, Section 3.2): gather the rows of positions 0..ctx_len-1 of
+ * one request, in order, into k_out, v_out [ctx_len, Hkv, hd] (device, io_dtype; bit-exact copies).  block_table: device
  * [ceil(ctx_len/B)].  slots_out: optional device int64 [ctx_len], the slot of every row. */
 int mace_kv_cache_gather(mace_handle_t h, const mace_kv_cache_t *cache, const int32_t *block_table,
                          int32_t ctx_len, void *k_out, void *v_out, int64_t *slots_out, void *stream);
@@ -149,12 +183,18 @@ int mace_kv_cache_gather(mace_handle_t h, const mace_kv_cache_t *cache, const in
  * rows attend to context_lens[r] cached tokens plus their own.  Fine-tune rows cache nothing;
  * their activations go to `saved` (mace_fwd_saved_bytes) for mace_hybrid_layer_bwd.
  * Fine-tune rows are computed with two-term bf16 operands (about 16 significand bits) so that
- * the DPO loss meets its 1e-3 tolerance; inference rows use plain bf16 operands. */
+ * the DPO loss meets its 1e-3 tolerance; inference rows use plain bf16 operands.
+ * Preconditions on device data: slots and block ids inside the cache, positions >= 0; a decode
+ * row's slot_mapping entry is the slot of position context_lens[r] in its block table. */
 int mace_hybrid_layer_fwd(mace_handle_t h, const mace_layer_w_t *w, const mace_batch_t *batch,
                           mace_kv_cache_t *cache, const void *x, float *y, void *saved,
                           void *workspace, size_t workspace_bytes, void *stream);
 
-/* Backward of the fine-tune rows.  dy_ft device fp32 [T_f, d_model] (dL/dy of the fine-tune rows,
+/* Backward of the fine-tune rows: the retraining half of the colocated iteration (Fig. 1 and
+ * Section 3.2: the fine-tune worker's backward pass runs in the same iteration as prefill and decode;
+ * Section 3.1: the gradient is that of the DPO objective, handed in as dy_ft).  Produces dL/dx of
+ * the fine-tune rows and dL/dW of all seven matrices and both gains of the layer.
+ * dy_ft device fp32 [T_f, d_model] (dL/dy of the fine-tune rows,
  * e.g. dh_ft of mace_dpo_logprob_loss); x the same x as in the forward; dx_ft device fp32
  * [T_f, d_model].  grads: fp32 weight gradients, summed over all fine-tune rows; overwritten, or
  * added to when accumulate != 0. */
@@ -194,7 +234,8 @@ int mace_hybrid_layer_bwd_lora(mace_handle_t h, const mace_layer_w_t *w, const m
  * loss_per_pair[i] = -log sigmoid(z), loss_mean = mean over pairs.
  *   h_ft            device fp32 [T_f, d_model]  (rows of y of the fine-tune sequences)
  *   g_final, w_lm   device io_dtype
- *   token_ids       device int32 [T_f]
+ *   token_ids       device int32 [T_f], every id in [0, vocab) (a label outside the range contributes
+ *                   -logsumexp to its sequence and no one-hot term to the gradient)
  *   ft_seq_offsets  device and host int32 [n_seq+1], relative to the first fine-tune row
  *   prompt_lens     device and host int32 [n_seq]; 1 <= P_s <= L_s
  *   ref_logp        device fp32 [n_seq] (log pi_ref of each sequence, pre-computed)
@@ -264,7 +305,8 @@ int mace_adamw_step(mace_handle_t h, void *param, float *master, const float *gr
  *   prune[r,h]  =  (t_count[r] - last_used[r,h] > window)  or  (norm[r,h] < tau)
  *   last_used[r,h]  <-  t_count[r] where norm[r,h] >= tau                (reading: "last used" = last iteration at
  *                                                                       which the head's norm reached tau)
- * abar fp32 in/out, t_count int32, last_used int32 in/out and prune int32 out (0/1) are device
+ * abar fp32 in/out, t_count int32 (every entry >= 1; an entry < 1 leaves that request's abar, last_used
+ * and prune untouched), last_used int32 in/out and prune int32 out (0/1) are device
  * arrays; last_used and prune may both be NULL (running mean only).
  * mace_kv_head_budget (host, pure): w_h = abar_h / sum_j abar_j, C_h = floor(w_h * c_total) in
  * double precision, and what the floors leave over goes one unit each to the heads of largest w_h
@@ -297,6 +339,21 @@ typedef struct {
 } mace_profile_entry_t;
 int mace_profile_enable(mace_handle_t h, int on);
 int mace_profile_collect(mace_handle_t h, mace_profile_entry_t *out, int32_t max_entries, int32_t *n_out);
+
+/* Launch plan of the dense contractions (host-side record, for tests and benchmarks; not part of the
+ * paper's method).  Every iteration call clears the record of the handle and then notes, for each
+ * GEMM it launches in order, the decisions its launcher took from the problem sizes: block tile,
+ * number of k slices, and whether the product ran on the internal stream.  A test at a reduced batch
+ * compares these with the full-size launch to show that it exercises the same code path. */
+typedef struct {
+  char name[32];           /* which product: "qkv gemm", "dWd gemm", ... */
+  int32_t layout;          /* 0 = NT (x W^T), 1 = NN (dy W), 2 = TN (dy^T x) */
+  int32_t tile_m, tile_n;  /* block tile */
+  int32_t k_splits;        /* k slices (1 = none) */
+  int32_t on_side_stream;  /* 1 = issued on the internal stream */
+  int64_t m, n, k;         /* rows summed over row groups, columns summed over segments, reduction length */
+} mace_gemm_plan_t;
+int mace_launch_plan(mace_handle_t h, mace_gemm_plan_t *out, int32_t max_entries, int32_t *n_out);
 
 #ifdef __cplusplus
 }

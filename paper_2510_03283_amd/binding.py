@@ -20,7 +20,9 @@ EXPORTS = [
     "mace_kv_slot_mapping", "mace_kv_cache_append", "mace_kv_cache_gather", "mace_hybrid_layer_fwd",
     "mace_hybrid_layer_bwd", "mace_hybrid_layer_fwd_lora", "mace_hybrid_layer_bwd_lora", "mace_dpo_logprob_loss", "mace_dpo_logprob_loss_shared",
     "mace_next_token_logits", "mace_adamw_step", "mace_head_norm_stats", "mace_kv_head_budget", "mace_profile_enable", "mace_profile_collect",
+    "mace_set_option", "mace_launch_plan",
 ]
+MACE_OPT_HEAD_TWO_PASS, MACE_OPT_SINGLE_STREAM, MACE_OPT_DECODE_CHUNK = 1, 2, 3
 
 
 class MaceError(RuntimeError):
@@ -63,6 +65,11 @@ class BatchT(C.Structure):
                 ("context_lens", C.c_void_p), ("max_blocks_per_req", C.c_int32), ("prefill_block_tables", C.c_void_p),
                 ("prefill_prefix_lens_host", C.c_void_p), ("prefill_prefix_lens", C.c_void_p), ("max_blocks_per_prefill", C.c_int32),
                 ("ft_excl_lo", C.c_void_p), ("ft_excl_hi", C.c_void_p), ("decode_head_norms", C.c_void_p)]
+
+
+class GemmPlanT(C.Structure):
+    _fields_ = [("name", C.c_char * 32), ("layout", C.c_int32), ("tile_m", C.c_int32), ("tile_n", C.c_int32), ("k_splits", C.c_int32),
+                ("on_side_stream", C.c_int32), ("m", C.c_int64), ("n", C.c_int64), ("k", C.c_int64)]
 
 
 class ProfileEntryT(C.Structure):
@@ -123,6 +130,10 @@ def load():
     lib.mace_profile_enable.restype = C.c_int
     lib.mace_profile_collect.argtypes = [vp, C.POINTER(ProfileEntryT), i32, C.POINTER(i32)]
     lib.mace_profile_collect.restype = C.c_int
+    lib.mace_set_option.argtypes = [vp, i32, i32]
+    lib.mace_set_option.restype = C.c_int
+    lib.mace_launch_plan.argtypes = [vp, C.POINTER(GemmPlanT), i32, C.POINTER(i32)]
+    lib.mace_launch_plan.restype = C.c_int
     _lib = lib
     return lib
 
@@ -160,6 +171,20 @@ def mace_create(d_model, n_q_heads, n_kv_heads, head_dim, d_ff, vocab, rms_eps, 
 
 def mace_destroy(h):
     load().mace_destroy(h)
+
+
+def mace_set_option(h, option: int, value: int):
+    _check(load().mace_set_option(h, int(option), int(value)), "mace_set_option")
+
+
+def mace_launch_plan(h) -> list:
+    """GEMM launch decisions of the last iteration call on this handle, in launch order."""
+    arr = (GemmPlanT * 256)()
+    n = C.c_int32(0)
+    _check(load().mace_launch_plan(h, arr, 256, C.byref(n)), "mace_launch_plan")
+    return [dict(name=arr[i].name.decode(), layout=int(arr[i].layout), tile=(int(arr[i].tile_m), int(arr[i].tile_n)),
+                 k_splits=int(arr[i].k_splits), on_side_stream=int(arr[i].on_side_stream), m=int(arr[i].m), n=int(arr[i].n),
+                 k=int(arr[i].k)) for i in range(min(n.value, 256))]
 
 
 def mace_fwd_saved_bytes(h, n_ft_tokens: int) -> int:

@@ -21,8 +21,8 @@ struct ProfMark {
 // The weight-gradient GEMMs of the backward pass depend on nothing that follows them, so they run
 // on a side stream of the context (same priority, non-blocking) forked from and joined back into
 // the caller's stream with events inside each call: they fill the CUs that the small dX GEMMs and
-// the elementwise kernels of the main chain leave idle.  MACE_SINGLE_STREAM=1 in the environment
-// keeps everything on the caller's stream.
+// the elementwise kernels of the main chain leave idle.  MACE_OPT_SINGLE_STREAM keeps everything on
+// the caller's stream.
 constexpr int N_FORK_EVENTS = 8;
 struct mace_ctx {
   mace_model_t m;
@@ -30,7 +30,10 @@ struct mace_ctx {
   hipStream_t side = nullptr;
   hipEvent_t ev_fork[N_FORK_EVENTS] = {}, ev_join = nullptr;
   int n_fork = 0;          // forks issued in the current call
-  bool head_two_pass = false;   // MACE_HEAD_TWO_PASS=1 at creation: every logit of the DPO head from two-term activations
+  bool head_two_pass = false;   // MACE_OPT_HEAD_TWO_PASS: every logit of the DPO head from two-term activations
+  bool single_stream = false;   // MACE_OPT_SINGLE_STREAM
+  int decode_chunk = 0;         // MACE_OPT_DECODE_CHUNK
+  std::vector<mace_gemm_plan_t> plan;   // launch decisions of the GEMMs of the last iteration call
   bool prof_on = false;
   unsigned prof_mask = ~0u;        // kernel classes that are timed
   bool prof_open[2] = {false, false};   // per chain: the last mark opened an interval
@@ -60,7 +63,7 @@ void prof_mark(mace_ctx *h, hipStream_t st, int tag, double flops = 0.0, double 
 // Side stream on which work may start once everything issued so far on `st` is done; returns `st`
 // itself when the context has no side stream.
 hipStream_t side_fork(mace_ctx *h, hipStream_t st) {
-  if (!h->side || h->n_fork >= N_FORK_EVENTS) return st;
+  if (!h->side || h->single_stream || h->n_fork >= N_FORK_EVENTS) return st;
   hipEvent_t ev = h->ev_fork[h->n_fork];
   if (hipEventRecord(ev, st) != hipSuccess || hipStreamWaitEvent(h->side, ev, 0) != hipSuccess) return st;
   ++h->n_fork;
@@ -74,6 +77,15 @@ hipError_t side_join(mace_ctx *h, hipStream_t st) {
   if (e != hipSuccess) return e;
   return hipStreamWaitEvent(st, h->ev_join, 0);
 }
+
+// Joins the side stream back into the caller's stream on every way out of an iteration call, error
+// returns included: work that was forked must not outlive the call (it reads the caller's workspace).
+struct SideGuard {
+  mace_ctx *h;
+  hipStream_t st;
+  SideGuard(mace_ctx *h_, hipStream_t st_) : h(h_), st(st_) { (void)side_join(h, st); h->plan.clear(); }
+  ~SideGuard() { (void)side_join(h, st); }
+};
 
 thread_local std::string g_err;
 
@@ -367,6 +379,19 @@ int run_gemm(mace_ctx *h, int LA, int LB, GemmParams &p, hipStream_t st, const c
   const char *why = nullptr;
   hipError_t e = gemm_launch(LA, LB, p, st, &why);
   if (e != hipSuccess) return fail(why ? MACE_BAD_SHAPE : MACE_HIP_ERROR, std::string(where) + ": " + (why ? why : hipGetErrorString(e)));
+  if (h->plan.size() < 256) {
+    mace_gemm_plan_t r;
+    memset(&r, 0, sizeof(r));
+    snprintf(r.name, sizeof(r.name), "%s", where);
+    r.layout = LA == 1 ? 2 : (LB == 1 ? 1 : 0);
+    r.tile_m = p.tile_m; r.tile_n = p.tile_n;
+    r.k_splits = p.k_splits > 1 ? p.k_splits : 1;
+    r.on_side_stream = h->side && st == h->side ? 1 : 0;
+    for (int g = 0; g < p.n_mg; ++g) r.m += p.mg[g].M;
+    for (int sg = 0; sg < p.n_ns; ++sg) r.n += p.ns[sg].N;
+    r.k = p.K;
+    h->plan.push_back(r);
+  }
   return MACE_OK;
 }
 // A weight-gradient GEMM ([M, N] out of K rows) that nothing later in the call depends on: issued on
@@ -490,18 +515,42 @@ int mace_create(mace_handle_t *out, const mace_model_t *model) {
     delete c;
     return hip_fail(e, "mace_create");
   }
-  if (const char *tp = getenv("MACE_HEAD_TWO_PASS")) c->head_two_pass = tp[0] == '1';
-  const char *single = getenv("MACE_SINGLE_STREAM");
-  if (!(single && single[0] == '1')) {
-    e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
-    for (int i = 0; i < N_FORK_EVENTS && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&c->ev_fork[i], hipEventDisableTiming);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming);
-    if (e != hipSuccess) {
-      mace_destroy(c);
-      return hip_fail(e, "mace_create: side stream");
-    }
+  e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
+  for (int i = 0; i < N_FORK_EVENTS && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&c->ev_fork[i], hipEventDisableTiming);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming);
+  if (e != hipSuccess) {
+    mace_destroy(c);
+    return hip_fail(e, "mace_create: side stream");
   }
   *out = c;
+  return MACE_OK;
+}
+
+int mace_set_option(mace_handle_t h, int32_t option, int32_t value) {
+  if (!h) return fail(MACE_INVALID_ARG, "handle is null");
+  switch (option) {
+    case MACE_OPT_HEAD_TWO_PASS:
+      if (value != 0 && value != 1) return fail(MACE_INVALID_ARG, "MACE_OPT_HEAD_TWO_PASS takes 0 or 1");
+      h->head_two_pass = value != 0;
+      return MACE_OK;
+    case MACE_OPT_SINGLE_STREAM:
+      if (value != 0 && value != 1) return fail(MACE_INVALID_ARG, "MACE_OPT_SINGLE_STREAM takes 0 or 1");
+      h->single_stream = value != 0;
+      return MACE_OK;
+    case MACE_OPT_DECODE_CHUNK:
+      if (value != 0 && (value < 512 || value > 4096 || (value & (value - 1)))) return fail(MACE_INVALID_ARG, "MACE_OPT_DECODE_CHUNK takes 0 or a power of two in 512..4096");
+      h->decode_chunk = value;
+      return MACE_OK;
+    default:
+      return fail(MACE_INVALID_ARG, "unknown option");
+  }
+}
+
+int mace_launch_plan(mace_handle_t h, mace_gemm_plan_t *out, int32_t max_entries, int32_t *n_out) {
+  if (!h || !n_out || max_entries < 0 || (max_entries > 0 && !out)) return fail(MACE_INVALID_ARG, "mace_launch_plan: bad argument");
+  const int32_t n = (int32_t)std::min<size_t>(h->plan.size(), (size_t)max_entries);
+  for (int32_t i = 0; i < n; ++i) out[i] = h->plan[i];
+  *n_out = (int32_t)h->plan.size();
   return MACE_OK;
 }
 
@@ -595,20 +644,14 @@ size_t mace_workspace_bytes(mace_handle_t h, int32_t n_tokens, int32_t n_ft_toke
   return align_up(m, 256) + 256;
 }
 
-int mace_next_token_logits(mace_handle_t h, const float *y, const int32_t *row_idx, int32_t n, const void *g_final, const void *w_lm,
-                           float *logits_out, int32_t *next_token, void *workspace, size_t workspace_bytes, void *stream) {
-  if (!h || !y || !g_final || !w_lm || !logits_out || n < 0) return fail(MACE_INVALID_ARG, "mace_next_token_logits: bad argument");
-  if (n == 0) return MACE_OK;
-  if (!workspace || ((uintptr_t)workspace & 255)) return fail(MACE_INVALID_ARG, "workspace must be non-null and 256-byte aligned");
+static int next_token_logits_impl(mace_handle_t h, const float *y, const int32_t *row_idx, int32_t n, const void *g_final, const void *w_lm,
+                                  float *logits_out, int32_t *next_token, void *workspace, size_t workspace_bytes, void *stream) {
   const Dims D(h->m);
   hipStream_t st = (hipStream_t)stream;
-  {
-    Bump m(nullptr);
-    plan_logits(D, (size_t)n, m);
-    if (m.off > workspace_bytes) return fail(MACE_WORKSPACE_TOO_SMALL, "next-token workspace too small");
-  }
+  h->plan.clear();
   Bump wsb(workspace);
   LogitWs P = plan_logits(D, (size_t)n, wsb);
+  if (wsb.off > workspace_bytes) return fail(MACE_WORKSPACE_TOO_SMALL, "next-token workspace too small");
   const bf16_t *e_hi = (const bf16_t *)w_lm;
   if (!D.bf) {
     prof_mark(h, st, T_MISC);
@@ -629,6 +672,14 @@ int mace_next_token_logits(mace_handle_t h, const float *y, const int32_t *row_i
   }
   prof_mark(h, st, -1);
   return MACE_OK;
+}
+
+int mace_next_token_logits(mace_handle_t h, const float *y, const int32_t *row_idx, int32_t n, const void *g_final, const void *w_lm,
+                           float *logits_out, int32_t *next_token, void *workspace, size_t workspace_bytes, void *stream) {
+  if (!h || !y || !g_final || !w_lm || !logits_out || n < 0) return fail(MACE_INVALID_ARG, "mace_next_token_logits: bad argument");
+  if (n == 0) return MACE_OK;
+  if (!workspace || ((uintptr_t)workspace & 255)) return fail(MACE_INVALID_ARG, "workspace must be non-null and 256-byte aligned");
+  return next_token_logits_impl(h, y, row_idx, n, g_final, w_lm, logits_out, next_token, workspace, workspace_bytes, stream);
 }
 
 int mace_adamw_step(mace_handle_t h, void *param, float *master, const float *grad, float *m, float *v, int64_t n, float lr,
@@ -761,6 +812,7 @@ static int layer_fwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
     if (lora) plan_lora(D, (size_t)I.T, false, m);
     if (m.off > workspace_bytes) return fail(MACE_WORKSPACE_TOO_SMALL, "forward workspace too small");
   }
+  SideGuard side_guard(h, st);      // waits for side-stream work an earlier failed call may have left; joins on every return
   Bump wsb(workspace), svb(saved);
   TRY(prepare_weights(D, w, wsb, true, true, st, W));
   FwdWs F = plan_fwd(D, I.Ti, I.Tf, I.Td, I.max_ctx, wsb);
@@ -834,7 +886,7 @@ static int layer_fwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
     for (int i = 0; i < I.Td; ++i) kv_tokens += (double)batch->context_lens_host[i] + 1.0;
     prof_mark(h, st, T_ATTN_DECODE, 4.0 * kv_tokens * D.Hq * D.hd, kv_tokens * 2.0 * D.Hkv * D.hd * (D.bf ? 2.0 : 4.0));
     HIP_TRY(launch_attn_decode(F.q_i + (size_t)I.Tp * D.qd, cache->k, cache->v, D.bf, cache->num_blocks, cache->block_size, batch->block_tables, batch->max_blocks_per_req,
-                               batch->context_lens, I.Td, I.max_ctx, D.Hq, D.Hkv, D.hd, F.dec_partial, F.o_i + (size_t)I.Tp * D.qd, batch->decode_head_norms, st), "decode attention");
+                               batch->context_lens, I.Td, I.max_ctx, D.Hq, D.Hkv, D.hd, F.dec_partial, F.o_i + (size_t)I.Tp * D.qd, batch->decode_head_norms, st, h->decode_chunk), "decode attention");
   }
   prof_mark(h, st, T_ATTN_FT, 4.0 * D.hd * D.Hq * I.pairs_ft);
   HIP_TRY(launch_attn_fwd(S.q, S.k, S.v, F.q_lo, F.k_lo, F.v_lo, batch->seg_offsets + batch->n_prefill + batch->n_decode, I.Ti, batch->n_ft_seq, I.max_ft, D.Hq, D.Hkv, D.hd, S.o, F.o_lo, S.lse, st, batch->ft_excl_lo, batch->ft_excl_hi), "ft attention");
@@ -933,6 +985,7 @@ static int layer_bwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
     if (lora) plan_lora(D, (size_t)I.Tf, true, m);
     if (m.off > workspace_bytes) return fail(MACE_WORKSPACE_TOO_SMALL, "backward workspace too small");
   }
+  SideGuard side_guard(h, st);
   Bump wsb(workspace), svb((void *)saved);
   WSplit W;
   TRY(prepare_weights(D, w, wsb, false, true, st, W));
@@ -949,7 +1002,6 @@ static int layer_bwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
   const int acc = accumulate ? 1 : 0;
   const int n_part = Tf < DG_PARTS ? Tf : DG_PARTS;
 
-  HIP_TRY(side_join(h, st), "join side stream");      // no-op unless an earlier call failed between fork and join
   prof_mark(h, st, T_MISC);
   HIP_TRY(launch_split_f32(dy_ft, (size_t)Tf * D.d, B.dy_bf, nullptr, st), "cast dy");
   // MLP: dHm = dY Wd ; SwiGLU backward ; dWd = dY^T Hm
@@ -1189,6 +1241,7 @@ static int dpo_impl(mace_handle_t h, const float *h_ft, const void *g_final, con
     if (m.off > workspace_bytes) return fail(MACE_WORKSPACE_TOO_SMALL, "DPO workspace too small");
   }
   hipStream_t st = (hipStream_t)stream;
+  SideGuard side_guard(h, st);
   Bump wsb(workspace);
   DpoWs P = plan_dpo(D, (size_t)R, n_seq, wsb);
   const bf16_t *e_hi = (const bf16_t *)w_lm, *e_lo = nullptr;
@@ -1236,8 +1289,9 @@ static int dpo_impl(mace_handle_t h, const float *h_ft, const void *g_final, con
     prof_mark(h, st, -1);
     return MACE_OK;
   }
-  if (dg_final && !dh_ft && (size_t)Tf * D.d > (size_t)Ri * D.V) return fail(MACE_INVALID_ARG, "dg_final without dh_ft needs T_f*d <= R*V");
-  HIP_TRY(side_join(h, st), "join side stream");      // no-op unless an earlier call failed between fork and join
+  // without dh_ft the two-sequence layout writes the row gradients over the logits buffer (the shared layout
+  // writes them densely over dn and needs no such room)
+  if (dg_final && !dh_ft && !shared && (size_t)Tf * D.d > (size_t)Ri * D.V) return fail(MACE_INVALID_ARG, "dg_final without dh_ft needs T_f*d <= R*V");
   prof_mark(h, st, T_DLOGITS, 0.0, (double)Ri * D.V * 6.0);
   HIP_TRY(launch_dlogits(P.logits, Ri, D.V, P.label, P.seq_id, P.lse, P.dlogp, P.dl, st), "dlogits");
   if (dw_lm) {

@@ -287,14 +287,13 @@ hipError_t launch_t(const bf16_t *q, const bf16_t *k, const bf16_t *v, const bf1
                     const int32_t *excl_hi) {
   constexpr size_t lds_q = (size_t)2 * (2 * TB * HD) * sizeof(bf16_t);
   constexpr size_t lds_k = (size_t)2 * (2 * TB * HD + 4 * TB) * sizeof(bf16_t);
-  static bool attr_flags[16] = {};
-  bool &attr_done = device_once(attr_flags);
-  if (!attr_done) {
+  static DeviceOnce attr_done;
+  if (!attr_done.test()) {
     hipError_t e = hipFuncSetAttribute((const void *)attn_bwd_dq_kernel<HD>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_q);
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute((const void *)attn_bwd_dkdv_kernel<HD>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_k);
     if (e != hipSuccess) return e;
-    attr_done = true;
+    attr_done.set();
   }
   dim3 grid_q(Hq, n_seq, cdiv(max_len, 128)), grid_k(Hkv, n_seq, cdiv(max_len, 128));
   hipLaunchKernelGGL((attn_bwd_dq_kernel<HD>), grid_q, dim3(256), lds_q, st, q, k, v, o, d_o, lse, dvec, seg, row_base, Hq, Hkv, dq, excl_lo, excl_hi);

@@ -266,7 +266,7 @@ size_t decode_partial_floats(int n_decode, int Hq, int hd, int max_context) {
 hipError_t launch_attn_decode(const bf16_t *q, const void *cache_k, const void *cache_v, bool cache_bf16,
                               long long num_blocks, int block_size, const int32_t *block_tables, int max_blocks_per_req,
                               const int32_t *ctx_lens, int n_decode, int max_context, int Hq, int Hkv, int hd,
-                              float *partial, bf16_t *out, float *norms, hipStream_t st) {
+                              float *partial, bf16_t *out, float *norms, hipStream_t st, int chunk_tokens) {
   if (n_decode <= 0) return hipSuccess;
   if (n_decode > 65535 || Hkv > 65535 || Hq > 65535) return hipErrorInvalidValue;
   int bshift = 0;
@@ -277,9 +277,9 @@ hipError_t launch_attn_decode(const bf16_t *q, const void *cache_k, const void *
   // 256-request, 32-head batch), as long as the grid still fills the chip several times over.
   int chunk = MIN_CHUNK;
   while (chunk < MAX_CHUNK && (long long)Hkv * n_decode * cdiv(max_context + 1, 2 * chunk) >= 8192) chunk *= 2;
-  if (const char *e = getenv("MACE_DECODE_CHUNK")) {      // development override
-    const int c = atoi(e);
-    if (c >= MIN_CHUNK && c <= MAX_CHUNK && (c & (c - 1)) == 0) chunk = c;
+  if (chunk_tokens) {                                       // pinned by the caller
+    if (chunk_tokens < MIN_CHUNK || chunk_tokens > MAX_CHUNK || (chunk_tokens & (chunk_tokens - 1))) return hipErrorInvalidValue;
+    chunk = chunk_tokens;
   }
   const int nsplit = cdiv(max_context + 1, chunk);
   if (nsplit > 65535) return hipErrorInvalidValue;

@@ -226,12 +226,11 @@ hipError_t launch_t(const bf16_t *q_hi, const bf16_t *k_hi, const bf16_t *v_hi, 
                     const int32_t *excl_lo = nullptr, const int32_t *excl_hi = nullptr) {
   constexpr int NT = SPLIT ? 2 : 1;
   constexpr size_t lds = (size_t)2 * 2 * NT * KB * HD * sizeof(bf16_t);
-  static bool attr_flags[16] = {};
-  bool &attr_done = device_once(attr_flags);
-  if (!attr_done) {
+  static DeviceOnce attr_done;
+  if (!attr_done.test()) {
     hipError_t e = hipFuncSetAttribute((const void *)attn_fwd_kernel<HD, SPLIT, NW, PAGED>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    attr_done = true;
+    attr_done.set();
   }
   dim3 grid(Hq, n_seq, cdiv(max_len, 32 * NW));
   hipLaunchKernelGGL((attn_fwd_kernel<HD, SPLIT, NW, PAGED>), grid, dim3(64 * NW), lds, st, q_hi, k_hi, v_hi, q_lo, k_lo, v_lo, seg, row_base, Hq, Hkv, o_hi, o_lo, lse, pg, excl_lo, excl_hi);

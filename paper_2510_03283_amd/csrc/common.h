@@ -92,16 +92,27 @@ __device__ __forceinline__ float block_max(float v, float *red) {
   return t;
 }
 
-// Per-device "done once" flag for launch attributes that HIP keeps per device (dynamic LDS limit).
-// Returns the flag of the current device; for a device beyond the table the flag always reads
-// false, which only costs a repeated (idempotent) attribute call.
-static inline bool &device_once(bool (&flags)[16]) {
-  static thread_local bool never;
-  never = false;
-  int dev = 0;
-  (void)hipGetDevice(&dev);
-  return dev >= 0 && dev < 16 ? flags[dev] : never;
-}
+// Per-device "done once" flag for launch attributes that HIP keeps per device (dynamic LDS limit):
+// one bit per device, set after the attribute call succeeded.  Safe to use from several host
+// threads (two threads that race only repeat an idempotent call); a device beyond bit 31 always
+// reads false, which costs a repeated call and nothing else.
+#include <atomic>
+struct DeviceOnce {
+  std::atomic<uint32_t> mask{0};
+  static int dev() {
+    int d = 0;
+    (void)hipGetDevice(&d);
+    return d;
+  }
+  bool test() const {
+    const int d = dev();
+    return d >= 0 && d < 32 && ((mask.load(std::memory_order_acquire) >> d) & 1u);
+  }
+  void set() {
+    const int d = dev();
+    if (d >= 0 && d < 32) mask.fetch_or(1u << d, std::memory_order_release);
+  }
+};
 
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline int cdiv(int a, int b) { return (a + b - 1) / b; }

@@ -363,6 +363,7 @@ __global__ __launch_bounds__(256) void head_norm_stats_kernel(const float *__res
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i >= n * H) return;
   const int t = t_count[i / H];
+  if (t < 1) return;              // a request that has had no decode iteration: nothing to average over
   const float v = norms[i], a = abar[i];
   abar[i] = a + (v - a) / (float)t;
   if (prune) {

@@ -52,6 +52,7 @@ struct GemmParams {
   long long c_split_stride;   // elements
   int mt_start[4];  // filled by gemm_launch
   int nt_start[4];
+  int tile_m, tile_n;   // filled by gemm_launch: the block tile its cost model chose
 };
 
 // Number of k slices worth using for a single-group, single-segment problem (1 = none): small

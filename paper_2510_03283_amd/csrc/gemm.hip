@@ -486,21 +486,19 @@ hipError_t launch_dl(GemmParams &p, hipStream_t stream) {
   constexpr int NTHR = 64 * WGM * WGN;
   constexpr size_t lds = (size_t)NST * (BM + BN) * BKT * sizeof(bf16_t);
   static_assert(lds <= 160 * 1024, "LDS budget of a gfx950 CU");
-  static bool attr_flags[16] = {};
-  bool &attr_done = device_once(attr_flags);
-  if (!attr_done) {
+  static DeviceOnce attr_done;
+  if (!attr_done.test()) {
     hipError_t e = hipFuncSetAttribute((const void *)gemm_bf16_dl_kernel<BM, BN, WGM, WGN, LA, LB, BKT, NST>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    attr_done = true;
+    attr_done.set();
   }
+  p.tile_m = BM; p.tile_n = BN;
   hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, LA, LB, BKT, NST>), dim3((unsigned)tiles, (unsigned)(p.k_splits > 1 ? p.k_splits : 1)), dim3(NTHR), lds, stream, p);
   return hipGetLastError();
 }
 
 bool aligned16(const void *q) { return ((uintptr_t)q & 15) == 0; }
-
-int g_force_tile = -1;
 
 // Tile choice.  256x256 tiles (8 waves, one block per CU) do 0.75 LDS fragment reads per MFMA and
 // half the L2 traffic of 128x128 tiles (4 waves, two blocks per CU), but quantise worse on small
@@ -536,22 +534,16 @@ double tile_cost(const GemmParams &p, int slots, double slot_share, double eff) 
 
 template <int LA, int LB>
 hipError_t launch_layout(GemmParams &p, hipStream_t stream) {
-  int tile = g_force_tile;
-  if (tile < 0) {
-    const double c256 = tile_cost<256, 256>(p, 256, 1.0, 1.0);
-    const double c192 = tile_cost<192, 256>(p, 256, 1.0, 0.92);
-    const double c128 = tile_cost<128, 128>(p, 512, 2.0, 0.83);
-    tile = c256 <= c192 && c256 <= c128 ? 1 : (c192 <= c128 ? 2 : 0);
-  }
+  const double c256 = tile_cost<256, 256>(p, 256, 1.0, 1.0);
+  const double c192 = tile_cost<192, 256>(p, 256, 1.0, 0.92);
+  const double c128 = tile_cost<128, 128>(p, 512, 2.0, 0.83);
+  const int tile = c256 <= c192 && c256 <= c128 ? 1 : (c192 <= c128 ? 2 : 0);
   if (tile == 1) return launch_dl<256, 256, 2, 4, LA, LB, BK, NSTAGES>(p, stream);
   if (tile == 2) return launch_dl<192, 256, 2, 4, LA, LB, BK, NSTAGES>(p, stream);
   return launch_dl<128, 128, 2, 2, LA, LB, BK, NSTAGES>(p, stream);
 }
 
 }  // namespace
-
-// development hook: pin the tile configuration (0 = 128x128, 1 = 256x256, 2 = 192x256, -1 = automatic)
-void gemm_force_tile(int id) { g_force_tile = id; }
 
 hipError_t gemm_launch(int LA, int LB, GemmParams &p, hipStream_t stream, const char **why) {
   *why = nullptr;

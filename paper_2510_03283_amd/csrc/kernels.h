@@ -93,7 +93,8 @@ size_t decode_partial_floats(int n_decode, int Hq, int hd, int max_context);
 hipError_t launch_attn_decode(const bf16_t *q, const void *cache_k, const void *cache_v, bool cache_bf16,
                               long long num_blocks, int block_size, const int32_t *block_tables, int max_blocks_per_req,
                               const int32_t *ctx_lens, int n_decode, int max_context, int Hq, int Hkv, int hd,
-                              float *partial, bf16_t *out, float *norms, hipStream_t st);
+                              float *partial, bf16_t *out, float *norms, hipStream_t st, int chunk_tokens = 0);
+// chunk_tokens: context tokens per block, 0 = chosen from the grid size, else a power of two in 512..4096.
 // Running mean of the head norms, prune predicate and last-used bookkeeping (elementwise, n x H).
 hipError_t launch_head_norm_stats(const float *norms, const int32_t *t_count, int n, int H, float *abar, int32_t *last_used,
                                   int window, float tau, int32_t *prune, hipStream_t st);

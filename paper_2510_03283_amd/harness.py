@@ -15,8 +15,10 @@ _WNAMES = ("g1", "wq", "wk", "wv", "wo", "g2", "wg", "wu", "wd")
 
 
 class DeviceIteration:
-    def __init__(self, wl: Workload, device: str = "cuda:0", load_cache: bool = True, device_cache_seed=None, lora=None):
-        """lora: adapter dict of synth.make_lora - the iteration then runs the adapter variant (base
+    def __init__(self, wl: Workload, device: str = "cuda:0", load_cache: bool = True, device_cache_seed=None, lora=None,
+                 options=None):
+        """options: {binding.MACE_OPT_*: value} set on the handle right after it is created.
+        lora: adapter dict of synth.make_lora - the iteration then runs the adapter variant (base
         model frozen, adapter gradients only).
         device_cache_seed: fill the cached contexts with N(0,1) values drawn on the GPU (torch
         generator) instead of uploading wl.ctx_k / ctx_v - for benchmark workloads whose cache
@@ -27,6 +29,8 @@ class DeviceIteration:
         self.io_dtype = torch.bfloat16 if m.io_bf16 else torch.float32
         self.h = B.mace_create(m.d_model, m.n_q_heads, m.n_kv_heads, m.head_dim, m.d_ff, m.vocab, m.rms_eps,
                                m.rope_theta, B.MACE_BF16 if m.io_bf16 else B.MACE_F32)
+        for opt, val in (options or {}).items():
+            B.mace_set_option(self.h, opt, val)
         up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(self.dev)
         upio = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.dev).to(self.io_dtype).contiguous()
         self.w = {k: upio(wl.weights[k]) for k in _WNAMES}
@@ -200,6 +204,18 @@ class DeviceIteration:
         if self.n_pairs:
             self.dpo(True)
             self.backward()
+
+    def step_with_plans(self):
+        """One step; returns the GEMM launch plans (binding.mace_launch_plan) of the three calls."""
+        plans = {}
+        self.forward()
+        plans["fwd"] = B.mace_launch_plan(self.h)
+        if self.n_pairs:
+            self.dpo(True)
+            plans["dpo"] = B.mace_launch_plan(self.h)
+            self.backward()
+            plans["bwd"] = B.mace_launch_plan(self.h)
+        return plans
 
     def close(self):
         if self.h is not None:

@@ -374,6 +374,22 @@ def to_shared_prompt(wl: Workload) -> Workload:
     return dataclasses.replace(wl, batch=nb, x=wl.x[keep])
 
 
+def ft_slice(wl: Workload, p0: int, p1: int) -> Workload:
+    """The fine-tune-only batch made of pairs p0 .. p1-1 of `wl` (two-sequence layout): the same rows,
+    tokens, positions and reference log-probabilities, no inference rows and an empty cache.  Pure
+    index slicing; used to run a part of a large batch on its own."""
+    b = wl.batch
+    assert b.ft_chosen_lens is None and 0 <= p0 < p1 <= b.n_ft_seq // 2
+    base = b.n_prefill + b.n_decode
+    seg = b.seg_offsets
+    o0, o1 = int(seg[base + 2 * p0]), int(seg[base + 2 * p1])
+    nb = Batch(np.zeros(0, np.int64), np.zeros(0, np.int64), b.ft_lens[2 * p0:2 * p1], b.ft_prompt_lens[2 * p0:2 * p1],
+               (seg[base + 2 * p0:base + 2 * p1 + 1] - o0).astype(np.int32), b.positions[o0:o1], b.token_ids[o0:o1],
+               b.block_size, 4, [], np.full((0, 1), -1, dtype=np.int32), 1)
+    return dataclasses.replace(wl, batch=nb, x=wl.x[o0:o1], ctx_k=None, ctx_v=None, ref_logp=wl.ref_logp[2 * p0:2 * p1],
+                               pre_k=None, pre_v=None)
+
+
 def make_upstream_grad(spec: ConfigSpec, n_rows: int, scale: float = 1e-3) -> np.ndarray:
     """A synthetic dL/dY for tests that drive the layer backward on its own."""
     m = spec.dims

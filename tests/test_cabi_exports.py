@@ -32,6 +32,16 @@ def test_every_declared_symbol_is_exported(lib):
     assert sorted(binding.EXPORTS) == syms
 
 
+def test_nothing_but_the_declared_entry_points_is_exported(lib):
+    """The dynamic symbol table of the library holds the mace_* functions of the header and no internal
+    launcher, hook or global."""
+    import subprocess
+    from paper_2510_03283_amd import binding
+    out = subprocess.run(["nm", "-D", "--defined-only", binding.lib_path()], capture_output=True, text=True, check=True).stdout
+    funcs = sorted(l.split()[-1] for l in out.splitlines() if l.split()[1] in "TtWw")
+    assert funcs == declared_symbols(), set(funcs) ^ set(declared_symbols())
+
+
 def test_slot_mapping_matches_oracle_bit_exactly(lib):
     from oracle import mace_oracle as O
     from paper_2510_03283_amd import binding as B

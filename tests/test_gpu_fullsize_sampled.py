@@ -2,7 +2,10 @@
 times (whole batch in one call, cache drawn on the GPU), checked on sampled requests: requests are
 independent in the forward and in dx, so the oracle runs a sampled request alone and must
 reproduce that request's rows of the full-batch result.  Weight gradients are sums over all pairs
-and are covered by the request-subsampled tests instead."""
+and are covered by test_gpu_fullsize_backward.py.
+
+The loss of a sampled pair is held to TOL_LOSS_7B, five times under the 1e-3 bar: a sample can only
+stand for the pairs that were not drawn if it clears the bar with room."""
 import types
 
 import numpy as np
@@ -11,9 +14,11 @@ import pytest
 from helpers import max_abs_norm_err, rel_fro_err
 from oracle import mace_oracle as O
 from paper_2510_03283_amd import synth
-from test_gpu_parity import TOL_GRAD, TOL_LOSS, TOL_OUT, torch_mod, weights_7b  # noqa: F401  (fixtures)
+from test_gpu_parity import TOL_GRAD, TOL_LOSS, TOL_OUT
 
 pytestmark = pytest.mark.gpu
+
+TOL_LOSS_7B = 2e-4
 
 
 def _ns(b, **kw):
@@ -30,7 +35,8 @@ def _gather_ctx(cache, table, n, B):
     return rows.float().cpu().numpy().astype(np.float64)
 
 
-def _run_full(torch, name, weights, prefill_ids, decode_ids, pair_ids, pair_backward):
+def _run_full(torch, name, weights, prefill_ids, decode_ids, pair_ids, backward_pairs):
+    """pair_ids: pairs whose forward and loss are checked; backward_pairs: the subset whose dh and dx are checked too."""
     from paper_2510_03283_amd.harness import DeviceIteration
     wl = synth.make_workload(name, with_cache=False, weights=weights)
     m, b = wl.dims, wl.batch
@@ -79,12 +85,13 @@ def _run_full(torch, name, weights, prefill_ids, decode_ids, pair_ids, pair_back
             sb = _ns(b, ft_lens=b.ft_lens[2 * p:2 * p + 2], ft_prompt_lens=b.ft_prompt_lens[2 * p:2 * p + 2],
                      seg_offsets=np.array([0, o1 - o0, o2 - o0], np.int32), positions=b.positions[o0:o2], token_ids=b.token_ids[o0:o2])
             ck = O.new_cache(1, m.n_kv_heads, B, m.head_dim)
+            pair_backward = p in backward_pairs
             out = O.hybrid_iteration(m, wl.weights, sb, wl.x[o0:o2], ck, ck.copy(), wl.ref_logp[2 * p:2 * p + 2], wl.beta, backward=pair_backward)
             e = max_abs_norm_err(y[o0:o2], out["y"])
             lp = it.logp.cpu().numpy()[2 * p:2 * p + 2].astype(np.float64)
             dl = abs(float(it.loss_pair.cpu().numpy()[p]) - out["head"]["loss_per_pair"][0])
             print(f"[{name} full] pair {p} ({o2 - o0} rows): y {e:.2e}, |dloss| {dl:.2e}, max |dlogp| {np.abs(lp - out['head']['logp']).max():.2e}", flush=True)
-            assert e <= TOL_OUT and dl <= TOL_LOSS
+            assert e <= TOL_OUT and dl <= TOL_LOSS_7B
             if pair_backward:      # the pair alone has n_pairs = 1; in the batch its gradients carry 1 / n_pairs
                 scale = 1.0 / it.n_pairs
                 rows = slice(o0 - it.Ti, o2 - it.Ti)
@@ -98,14 +105,14 @@ def _run_full(torch, name, weights, prefill_ids, decode_ids, pair_ids, pair_back
 
 def test_7b_full_size_sampled(torch_mod, weights_7b):
     b = synth.make_batch(synth.CONFIGS["7b"])
-    _run_full(torch_mod, "7b", weights_7b, prefill_ids=[1], decode_ids=[int(np.argmax(b.decode_ctx))], pair_ids=[3], pair_backward=True)
+    _run_full(torch_mod, "7b", weights_7b, prefill_ids=[1], decode_ids=[int(np.argmax(b.decode_ctx))], pair_ids=list(range(8)), backward_pairs=[3])
 
 
 def test_7b_decode_full_size_sampled(torch_mod, weights_7b):
     b = synth.make_batch(synth.CONFIGS["7b_decode"])
     _run_full(torch_mod, "7b_decode", weights_7b, prefill_ids=[], decode_ids=[int(np.argmax(b.decode_ctx)), int(np.argmin(b.decode_ctx)), 100],
-              pair_ids=[1], pair_backward=True)
+              pair_ids=[0, 1], backward_pairs=[1])
 
 
 def test_7b_ft_full_size_sampled(torch_mod, weights_7b):
-    _run_full(torch_mod, "7b_ft", weights_7b, prefill_ids=[0], decode_ids=[5], pair_ids=[17], pair_backward=False)
+    _run_full(torch_mod, "7b_ft", weights_7b, prefill_ids=[0], decode_ids=[5], pair_ids=[9, 17, 25, 31], backward_pairs=[17])

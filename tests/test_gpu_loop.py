@@ -6,7 +6,7 @@ import pytest
 from helpers import max_abs_norm_err, run_oracle
 from oracle import mace_oracle as O
 from paper_2510_03283_amd import synth
-from test_gpu_parity import custom_workload, torch_mod  # noqa: F401  (fixture)
+from test_gpu_parity import custom_workload
 
 pytestmark = pytest.mark.gpu
 

@@ -4,7 +4,7 @@ full-weight tests."""
 import pytest
 
 from paper_2510_03283_amd import synth
-from test_gpu_parity import check_iteration, custom_workload, torch_mod  # noqa: F401  (fixture)
+from test_gpu_parity import check_iteration, custom_workload
 
 pytestmark = pytest.mark.gpu
 

@@ -1,13 +1,11 @@
 """Execution modes of the library that must not change results: gradient accumulation, the
-single-stream switch, and replay of the three calls from a captured HIP graph (fork/join of the
+single-stream option, and replay of the three calls from a captured HIP graph (fork/join of the
 internal side stream included)."""
-import os
-
 import numpy as np
 import pytest
 
 from paper_2510_03283_amd import synth
-from test_gpu_parity import custom_workload, torch_mod  # noqa: F401  (fixture)
+from test_gpu_parity import custom_workload
 
 pytestmark = pytest.mark.gpu
 
@@ -47,19 +45,22 @@ def test_accumulate_adds_to_existing_gradients(torch_mod):
 
 def test_single_stream_switch_is_bitwise_identical(torch_mod):
     import torch
+    from paper_2510_03283_amd import binding as B
     from paper_2510_03283_amd.harness import DeviceIteration
     wl = _workload()
     a = DeviceIteration(wl)
-    os.environ["MACE_SINGLE_STREAM"] = "1"
-    try:
-        b = DeviceIteration(wl)          # the switch is read when the handle is created
-    finally:
-        del os.environ["MACE_SINGLE_STREAM"]
+    b = DeviceIteration(wl, options={B.MACE_OPT_SINGLE_STREAM: 1})
     try:
         a.step(); b.step()
         torch.cuda.synchronize()
+        assert any(r["on_side_stream"] for r in B.mace_launch_plan(a.h))          # the default does use the side stream here
+        assert not any(r["on_side_stream"] for r in B.mace_launch_plan(b.h))
         for u, v in zip(_outputs(a), _outputs(b)):
             assert torch.equal(u, v)
+        with pytest.raises(B.MaceError):
+            B.mace_set_option(a.h, 99, 1)
+        with pytest.raises(B.MaceError):
+            B.mace_set_option(a.h, B.MACE_OPT_DECODE_CHUNK, 1000)
     finally:
         a.close(); b.close()
 
@@ -98,10 +99,10 @@ def test_graph_replay_matches_eager(torch_mod):
         it.close()
 
 
-def test_two_pass_head_switch(torch_mod, monkeypatch):
-    """MACE_HEAD_TWO_PASS=1 at context creation: every logit of the DPO head is formed from two-term
-    activations (the form with the wider loss margin); same bars, and a loss error well under the
-    default head's."""
+def test_two_pass_head_switch(torch_mod):
+    """MACE_OPT_HEAD_TWO_PASS: every logit of the DPO head is formed from two-term activations;
+    same bars as the default head."""
+    from paper_2510_03283_amd import binding as B
     from test_gpu_parity import check_iteration
-    monkeypatch.setenv("MACE_HEAD_TWO_PASS", "1")
-    check_iteration(torch_mod, synth.make_workload("edge", n_prefill=1, n_decode=2), "edge ft rows, two-pass head")
+    check_iteration(torch_mod, synth.make_workload("edge", n_prefill=1, n_decode=2), "edge ft rows, two-pass head",
+                    options={B.MACE_OPT_HEAD_TWO_PASS: 1})

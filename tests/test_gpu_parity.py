@@ -13,21 +13,14 @@ pytestmark = pytest.mark.gpu
 TOL_OUT, TOL_LOSS, TOL_GRAD = 1e-2, 1e-3, 2e-2
 
 
-@pytest.fixture(scope="module")
-def torch_mod():
-    import torch
-    assert torch.cuda.is_available(), "GPU tests need a GPU"
-    from paper_2510_03283_amd import binding
-    binding.load()          # no fallback: a missing library is an error
-    return torch
-
-
-def check_iteration(torch, wl, label, check_grads=True, lora=None):
+def check_iteration(torch, wl, label, check_grads=True, lora=None, options=None, tol_loss=TOL_LOSS):
     """Run forward + DPO head + backward on the GPU and compare everything with the oracle.
-    lora: adapter dict - both sides then run the adapter variant (frozen base, adapter gradients)."""
+    lora: adapter dict - both sides then run the adapter variant (frozen base, adapter gradients).
+    options: handle options (binding.MACE_OPT_*) of the GPU side.
+    tol_loss: bar on |loss - oracle| (mean and every pair); callers tighten it to assert a margin."""
     from paper_2510_03283_amd.harness import DeviceIteration
     ref = run_oracle(wl, backward=check_grads, lora=lora)
-    it = DeviceIteration(wl, lora=lora)
+    it = DeviceIteration(wl, lora=lora, options=options)
     try:
         print(f"[{label}] T={it.T} (prefill {it.Tp}, decode {it.Td}, ft {it.Tf}), loss rows {it.R}", flush=True)
         it.forward()
@@ -57,7 +50,7 @@ def check_iteration(torch, wl, label, check_grads=True, lora=None):
         dl = abs(it.loss_mean.item() - head["loss_mean"])
         dlp = np.abs(it.loss_pair.cpu().numpy()[:it.n_pairs] - head["loss_per_pair"]).max()
         print(f"[{label}] |dloss| {dl:.2e}, worst pair {dlp:.2e}, max |dlogp| {np.abs(logp - head['logp']).max():.2e}", flush=True)
-        assert dl <= TOL_LOSS and dlp <= TOL_LOSS, (label, dl, dlp)
+        assert dl <= tol_loss and dlp <= tol_loss, (label, dl, dlp)
         clpd = it.clpd.cpu().numpy()[:it.n_pairs]
         assert np.allclose(clpd, logp[0::2] - logp[1::2], rtol=1e-6, atol=1e-4)
         assert np.array_equal(it.win.cpu().numpy()[:it.n_pairs], (clpd > 0).astype(np.int32))
@@ -110,11 +103,6 @@ def test_edge_iteration_full_size(torch_mod):
     check_iteration(torch_mod, synth.make_workload("edge"), "edge")
 
 
-@pytest.fixture(scope="module")
-def weights_7b():
-    return synth.make_weights(synth.CONFIGS["7b"])
-
-
 def test_7b_subsampled(torch_mod, weights_7b):
     """7B-class layer (hd 128, MHA, d 4096): one prefill request, two decode requests and one pair
     with their full per-request shapes."""
@@ -150,14 +138,14 @@ def test_block_sizes(torch_mod, bs):
 
 @pytest.mark.parametrize("chunk", [512, 1024, 2048, 4096])
 @pytest.mark.parametrize("hq,hkv,hd", [(4, 2, 64), (2, 2, 128)])
-def test_decode_chunk_lengths(torch_mod, monkeypatch, chunk, hq, hkv, hd):
+def test_decode_chunk_lengths(torch_mod, chunk, hq, hkv, hd):
     """Every tokens-per-block setting of the decode kernel (the launcher picks one from the batch
-    size; the environment override pins it) on contexts below, on and across the chunk edges:
+    size; MACE_OPT_DECODE_CHUNK pins it) on contexts below, on and across the chunk edges:
     the partial soft-max states of one, two and several chunks must merge to the same result."""
-    monkeypatch.setenv("MACE_DECODE_CHUNK", str(chunk))
+    from paper_2510_03283_amd import binding as B
     dims = synth.ModelDims(n_q_heads=hq, n_kv_heads=hkv, head_dim=hd, **SMALL)
     wl = custom_workload("chunks", dims, prefill=[5], decode=[0, 511, 512, 1023, 2047, 2048, 4100, 5000], n_pairs=1, prompt=3, resp=(2, 9))
-    check_iteration(torch_mod, wl, f"decode chunk {chunk} Hq{hq} Hkv{hkv} hd{hd}")
+    check_iteration(torch_mod, wl, f"decode chunk {chunk} Hq{hq} Hkv{hkv} hd{hd}", options={B.MACE_OPT_DECODE_CHUNK: chunk})
 
 
 @pytest.mark.parametrize("prefill,decode,pairs", [([], [], 2), ([50, 3], [], 0), ([], [40, 2], 0), ([9], [5], 1)])

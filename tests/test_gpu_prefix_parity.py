@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 
 from paper_2510_03283_amd import synth
-from test_gpu_parity import check_iteration, torch_mod  # noqa: F401  (fixture)
+from test_gpu_parity import check_iteration
 
 pytestmark = pytest.mark.gpu
 
