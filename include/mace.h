@@ -245,10 +245,12 @@ int mace_hybrid_layer_bwd_lora(mace_handle_t h, const mace_layer_w_t *w, const m
  * done): dh_ft fp32 [T_f, d_model] (zero on rows that carry no loss), dw_lm fp32 [vocab, d_model]
  * (head contribution only), dg_final fp32 [d_model]; overwritten, or added to when accumulate != 0
  * (dh_ft is always overwritten).
- * Precision: with bf16 weights the vocabulary product takes plain bf16 operands and the logit of each
- * row's label is recomputed from two-term activations (about 16 significand bits), which is the term
- * through which operand rounding reaches log pi(y|x); with fp32 weights, or with MACE_HEAD_TWO_PASS=1
- * in the environment at mace_create, every logit is formed from two-term operands. */
+ * Precision: the normalised rows n are held as two bf16 terms n_hi + n_lo (about 16 significand bits).
+ * fp32 weights: every logit from two-term operands on both sides (three products).  bf16 weights, when a
+ * gradient is requested: ONE pass over the vocabulary with n_hi, and the first-order effect of the dropped
+ * n_lo on each row's log-probability, n_lo . (E_label - sum_j p_j E_j), is added back from the product
+ * dlogits E that the backward forms anyway; the remainder is second order in n_lo (about 1e-7 per row).
+ * bf16 weights without gradients, or with MACE_OPT_HEAD_TWO_PASS: two passes (n_hi, then n_lo). */
 int mace_dpo_logprob_loss(mace_handle_t h, const float *h_ft, const void *g_final, const void *w_lm,
                           const int32_t *token_ids, const int32_t *ft_seq_offsets,
                           const int32_t *ft_seq_offsets_host, const int32_t *prompt_lens,

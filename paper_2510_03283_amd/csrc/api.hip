@@ -1252,6 +1252,16 @@ static int dpo_impl(mace_handle_t h, const float *h_ft, const void *g_final, con
   }
   const int Ri = (int)R;
   const bool want_grad = dh_ft || dw_lm || dg_final;
+  const int acc = accumulate ? 1 : 0;
+  // Head precision.  fp32 weights: three-product form.  bf16 weights, MACE_OPT_HEAD_TWO_PASS or no gradient
+  // wanted: two passes over the vocabulary (two-term activations).  bf16 weights with gradients (the default
+  // of a training step): ONE pass with n_hi, and the first-order term of the dropped n_lo is added to every
+  // row's log-probability from u = dl E, the product the backward pass forms anyway (logp_correct_kernel).
+  const bool one_pass = D.bf && !h->head_two_pass && want_grad;
+  // without dh_ft the two-sequence layout writes the row gradients over the logits buffer (the shared layout
+  // writes them densely over dn and needs no such room)
+  if (dg_final && !dh_ft && !shared && (size_t)Tf * D.d > (size_t)Ri * D.V) return fail(MACE_INVALID_ARG, "dg_final without dh_ft needs T_f*d <= R*V");
+  const bool need_u = Ri > 0 && want_grad && (dh_ft || dg_final || one_pass);
   if (Ri > 0) {
     prof_mark(h, st, T_MISC);
     if (shared)
@@ -1262,21 +1272,27 @@ static int dpo_impl(mace_handle_t h, const float *h_ft, const void *g_final, con
     prof_mark(h, st, T_RMSNORM);
     HIP_TRY(launch_rmsnorm_fwd(h_ft, false, P.row_idx, g_final, D.bf, Ri, D.d, h->m.rms_eps, P.n_hi, P.n_lo, P.rstd, st), "final rmsnorm");
     GemmParams p = gp_init(D.d, D.d, D.d, D.V);
-    // bf16 weights: one pass over the vocabulary plus the label's logit from the two-term activations
-    // (see label_logit_kernel) unless the context asks for two passes; fp32 weights keep the three-product form
-    const bool one_pass = D.bf && !h->head_two_pass;
     gp_group(p, P.n_hi, P.n_lo, P.logits, nullptr, Ri, one_pass ? 1 : (D.bf ? 2 : 3));
     gp_seg(p, e_hi, e_lo, D.V, 0);
     TRY(run_gemm(h, 0, 0, p, st, "lm head gemm"));
-    if (one_pass) { prof_mark(h, st, T_MISC); HIP_TRY(launch_label_logit(P.n_hi, P.n_lo, e_hi, P.label, Ri, D.d, D.V, P.logits, st), "label logits");
+    // log-soft-max and, for the backward, dl = onehot - softmax (without the sequence factor) in one pass over the logits
+    prof_mark(h, st, T_LOGSOFTMAX, 0.0, (double)Ri * D.V * (want_grad ? 6.0 : 4.0));
+    HIP_TRY(launch_logsoftmax_dl(P.logits, Ri, D.V, P.label, P.logp_t, P.lse, want_grad ? P.dl : nullptr, st), "log-softmax");
+    if (need_u) {
+      // u = dl E: small output, reduction over the whole vocabulary: slice k so that every CU has work
+      const int ks = gemm_suggest_k_splits(Ri, D.d, D.V);
+      GemmParams q = gp_init(D.V, D.V, D.d, D.d);
+      gp_group(q, P.dl, nullptr, ks > 1 ? P.dn_part : P.dn, nullptr, Ri, 1);
+      gp_seg(q, e_hi, nullptr, D.d, 0);
+      if (ks > 1) { q.k_splits = ks; q.c_split_stride = (long long)Ri * D.d; }
+      TRY(run_gemm(h, 0, 1, q, st, "dn gemm"));
+      if (ks > 1) { prof_mark(h, st, T_MISC); HIP_TRY(launch_sum_partials(P.dn_part, ks, (size_t)Ri * D.d, P.dn, st), "dn partial sums"); }
+      if (one_pass) { prof_mark(h, st, T_MISC); HIP_TRY(launch_logp_correct(P.n_lo, P.dn, Ri, D.d, P.logp_t, st), "log-probability correction"); }
     }
-    prof_mark(h, st, T_LOGSOFTMAX, 0.0, (double)Ri * D.V * 4.0);
-    HIP_TRY(launch_logsoftmax_gather(P.logits, Ri, D.V, P.label, P.logp_t, P.lse, st), "log-softmax");
   }
   prof_mark(h, st, T_MISC);
   HIP_TRY(launch_dpo_pairs(P.logp_t, shared ? P.vseq_off : ft_seq_offsets, shared ? P.vprompt : prompt_lens, n_seq, ref_logp, beta, logp_out, loss_per_pair, loss_mean, clpd_out, win_out, P.dlogp, st), "dpo pairs");
   if (!want_grad) { prof_mark(h, st, -1); return MACE_OK; }
-  const int acc = accumulate ? 1 : 0;
   if (dh_ft) { prof_mark(h, st, T_MISC); HIP_TRY(launch_fill_f32(dh_ft, (size_t)Tf * D.d, 0.f, st), "zero dh");
   }
   if (Ri == 0) {
@@ -1289,27 +1305,18 @@ static int dpo_impl(mace_handle_t h, const float *h_ft, const void *g_final, con
     prof_mark(h, st, -1);
     return MACE_OK;
   }
-  // without dh_ft the two-sequence layout writes the row gradients over the logits buffer (the shared layout
-  // writes them densely over dn and needs no such room)
-  if (dg_final && !dh_ft && !shared && (size_t)Tf * D.d > (size_t)Ri * D.V) return fail(MACE_INVALID_ARG, "dg_final without dh_ft needs T_f*d <= R*V");
-  prof_mark(h, st, T_DLOGITS, 0.0, (double)Ri * D.V * 6.0);
-  HIP_TRY(launch_dlogits(P.logits, Ri, D.V, P.label, P.seq_id, P.lse, P.dlogp, P.dl, st), "dlogits");
+  // the sequence factor c = dL/dlog p, known now: dn = c u; dE = dl^T (c n_hi), the scaled rows take the place of n_lo
+  bf16_t *n_c = dw_lm ? P.n_lo : nullptr;
+  prof_mark(h, st, T_MISC);
+  HIP_TRY(launch_scale_rows(dh_ft || dg_final ? P.dn : nullptr, P.n_hi, n_c, P.seq_id, P.dlogp, Ri, D.d, st), "sequence factors");
   if (dw_lm) {
     GemmParams p = gp_init(Ri, D.V, D.d, D.d);
     p.resid_kind = acc;
     gp_group(p, P.dl, nullptr, dw_lm, dw_lm, D.V, 1);
-    gp_seg(p, P.n_hi, nullptr, D.d, 0);
+    gp_seg(p, n_c, nullptr, D.d, 0);
     TRY(run_gemm_side(h, 1, 1, p, st, "dE gemm"));
   }
   if (dh_ft || dg_final) {
-    // small output, reduction over the whole vocabulary: slice k so that every CU has work
-    const int ks = gemm_suggest_k_splits(Ri, D.d, D.V);
-    GemmParams p = gp_init(D.V, D.V, D.d, D.d);
-    gp_group(p, P.dl, nullptr, ks > 1 ? P.dn_part : P.dn, nullptr, Ri, 1);
-    gp_seg(p, e_hi, nullptr, D.d, 0);
-    if (ks > 1) { p.k_splits = ks; p.c_split_stride = (long long)Ri * D.d; }
-    TRY(run_gemm(h, 0, 1, p, st, "dn gemm"));
-    if (ks > 1) { prof_mark(h, st, T_MISC); HIP_TRY(launch_sum_partials(P.dn_part, ks, (size_t)Ri * D.d, P.dn, st), "dn partial sums"); }
     const int n_part = Ri < DG_PARTS ? Ri : DG_PARTS;
     // without dh_ft the row gradients still have to land somewhere: reuse the logits buffer
     float *dx_dst = dh_ft ? dh_ft : P.logits;

@@ -61,55 +61,113 @@ __global__ __launch_bounds__(256) void scatter_rows_kernel(const float *__restri
   }
 }
 
-// The logit of the label, recomputed from the two-term activations: one wave per loss row forms
-// sum_k (n_hi + n_lo)[r, k] * E[label, k] in fp32 and overwrites logits[r, label].  With it the LM
-// head runs one bf16 pass: the rounding of n to bf16 moves every logit of a row by a few 1e-4, which
-// the log-sum-exp averages out (it enters as the rounding error times the soft-max mean of the
-// embeddings), but which would enter the label's own logit - and so log p(label) - at full size.
-__global__ __launch_bounds__(256) void label_logit_kernel(const bf16_t *__restrict__ n_hi, const bf16_t *__restrict__ n_lo,
-                                                          const bf16_t *__restrict__ e, const int32_t *__restrict__ label,
-                                                          int rows, int d, int V, float *__restrict__ logits) {
-  const int lane = threadIdx.x & 63, r = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (r >= rows) return;
-  const int lab = label[r];
-  if (lab < 0 || lab >= V) return;
-  const bf16_t *a = n_hi + (size_t)r * d, *b = n_lo + (size_t)r * d, *w = e + (size_t)lab * d;
-  float s = 0.f;
-  for (int k = lane * 8; k < d; k += 512) {        // d % 8 == 0
-    const uint4 ua = *(const uint4 *)(a + k), ub = *(const uint4 *)(b + k), uw = *(const uint4 *)(w + k);
-    const uint32_t wa[4] = {ua.x, ua.y, ua.z, ua.w}, wb[4] = {ub.x, ub.y, ub.z, ub.w}, ww[4] = {uw.x, uw.y, uw.z, uw.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      s += (__uint_as_float(wa[i] << 16) + __uint_as_float(wb[i] << 16)) * __uint_as_float(ww[i] << 16);
-      s += (__uint_as_float(wa[i] & 0xffff0000u) + __uint_as_float(wb[i] & 0xffff0000u)) * __uint_as_float(ww[i] & 0xffff0000u);
-    }
-  }
-  s = wave_sum(s);
-  if (lane == 0) logits[(size_t)r * V + lab] = s;
-}
-
-// One block per loss row: single pass over the V logits with an online (max, sum) pair.
-__global__ __launch_bounds__(256) void logsoftmax_gather_kernel(const float *__restrict__ logits, int V,
-                                                                const int32_t *__restrict__ label,
-                                                                float *__restrict__ logp_t, float *__restrict__ lse) {
-  __shared__ float red[4];
+// One block of 1024 threads per loss row.  The V logits of the row are read once into registers
+// (NCH float4 per thread), reduced to (max, sum) and, when dl is wanted, turned into
+//   dl[r, j] = [j == label[r]] - exp(logits[r, j] - lse[r])        (bf16)
+// i.e. d log p(label) / d logits, WITHOUT the factor dL/dlog p of the row's sequence: that factor
+// depends on the pair loss, which is known only after every row of the pair is done; it is applied
+// to the (much smaller) products of dl afterwards (scale_rows_kernel).  NCH == 0: rows longer than
+// the register budget are read twice.
+template <int NCH>
+__global__ __launch_bounds__(1024) void logsoftmax_dl_kernel(const float *__restrict__ logits, int V,
+                                                             const int32_t *__restrict__ label, float *__restrict__ logp_t,
+                                                             float *__restrict__ lse, bf16_t *__restrict__ dl) {
+  __shared__ float red[16];
   const int r = blockIdx.x;
   const float *row = logits + (size_t)r * V;
+  const int lab = label[r];
+  float4 v[NCH > 0 ? NCH : 1];
   float m = -INFINITY, s = 0.f;
-  for (int k = 4 * threadIdx.x; k < V; k += 1024) {       // V % 4 == 0
-    const float4 v = *(const float4 *)(row + k);
-    const float mx = fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w));
-    if (mx > m) { s *= expf(m - mx); m = mx; }
-    s += expf(v.x - m) + expf(v.y - m) + expf(v.z - m) + expf(v.w - m);
+  if constexpr (NCH > 0) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int k = 4 * (threadIdx.x + 1024 * i);             // V % 4 == 0
+      v[i] = k < V ? *(const float4 *)(row + k) : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+      m = fmaxf(m, fmaxf(fmaxf(v[i].x, v[i].y), fmaxf(v[i].z, v[i].w)));
+    }
+    if (m > -INFINITY) {
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) s += expf(v[i].x - m) + expf(v[i].y - m) + expf(v[i].z - m) + expf(v[i].w - m);
+    }
+  } else {
+    for (int k = 4 * threadIdx.x; k < V; k += 4096) {
+      const float4 w = *(const float4 *)(row + k);
+      const float mx = fmaxf(fmaxf(w.x, w.y), fmaxf(w.z, w.w));
+      if (mx > m) { s *= expf(m - mx); m = mx; }
+      s += expf(w.x - m) + expf(w.y - m) + expf(w.z - m) + expf(w.w - m);
+    }
   }
-  const float mb = block_max<256>(m, red);
+  const float mb = block_max<1024>(m, red);
   s = (m == -INFINITY) ? 0.f : s * expf(m - mb);
-  const float sb = block_sum<256>(s, red);
+  const float sb = block_sum<1024>(s, red);
+  const float l = mb + logf(sb);
   if (threadIdx.x == 0) {
-    const float l = mb + logf(sb);
     lse[r] = l;
-    const int lab = label[r];
     logp_t[r] = (lab >= 0 && lab < V ? row[lab] : 0.f) - l;
+  }
+  if (!dl) return;
+  bf16_t *out = dl + (size_t)r * V;
+  auto emit = [&](int k, const float4 &w) {
+    float o[4] = {-expf(w.x - l), -expf(w.y - l), -expf(w.z - l), -expf(w.w - l)};
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (k + j == lab) o[j] += 1.0f;
+    *(uint2 *)(out + k) = make_uint2(cvt_pk_bf16(o[0], o[1]), cvt_pk_bf16(o[2], o[3]));
+  };
+  if constexpr (NCH > 0) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int k = 4 * (threadIdx.x + 1024 * i);
+      if (k < V) emit(k, v[i]);
+    }
+  } else {
+    for (int k = 4 * threadIdx.x; k < V; k += 4096) emit(k, *(const float4 *)(row + k));
+  }
+}
+
+// First-order correction of log p(label) for the rounding of the normalised rows to bf16 in a ONE-PASS
+// head.  With n = n_hi + n_lo and logits formed from n_hi alone, every logit of the row is short of
+// n_lo . E_j; to first order
+//   log p(label) - log p(label)|n_hi  =  n_lo . E_label - sum_j p_j (n_lo . E_j)  =  n_lo . u,
+//   u = E_label - sum_j p_j E_j = dl[r, :] E
+// and u is the product the backward pass forms anyway (the gradient with respect to the normalised
+// row, before its sequence factor).  What is left is second order in n_lo (about 1e-7 per row) and
+// nearly the same for the two sequences of a pair.  One wave per loss row.
+__global__ __launch_bounds__(256) void logp_correct_kernel(const bf16_t *__restrict__ n_lo, const float *__restrict__ u, int rows, int d,
+                                                           float *__restrict__ logp_t) {
+  const int lane = threadIdx.x & 63, r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= rows) return;
+  const bf16_t *a = n_lo + (size_t)r * d;
+  const float *b = u + (size_t)r * d;
+  float s = 0.f;
+  for (int k = lane * 4; k < d; k += 256) {        // d % 4 == 0
+    const uint2 ua = *(const uint2 *)(a + k);
+    const float4 ub = *(const float4 *)(b + k);
+    s += __uint_as_float(ua.x << 16) * ub.x + __uint_as_float(ua.x & 0xffff0000u) * ub.y +
+         __uint_as_float(ua.y << 16) * ub.z + __uint_as_float(ua.y & 0xffff0000u) * ub.w;
+  }
+  s = wave_sum(s);
+  if (lane == 0) logp_t[r] += s;
+}
+
+// After the pair losses: row r belongs to sequence seq_id[r], whose dL/dlog p is c = dlogp[seq_id[r]].
+//   dn[r, :] = c * u[r, :]  (in place, fp32; skipped when u is null)
+//   n_c[r, :] = bf16(c * n_hi[r, :])  (skipped when n_c is null), so that dE = dl^T n_c.
+__global__ __launch_bounds__(256) void scale_rows_kernel(float *__restrict__ u, const bf16_t *__restrict__ n_hi, bf16_t *__restrict__ n_c,
+                                                         const int32_t *__restrict__ seq_id, const float *__restrict__ dlogp, int d) {
+  const int r = blockIdx.x;
+  const float c = dlogp[seq_id[r]];
+  for (int k = 4 * threadIdx.x; k < d; k += 1024) {        // d % 4 == 0
+    if (u) {
+      float4 w = *(float4 *)(u + (size_t)r * d + k);
+      w.x *= c; w.y *= c; w.z *= c; w.w *= c;
+      *(float4 *)(u + (size_t)r * d + k) = w;
+    }
+    if (n_c) {
+      const uint2 a = *(const uint2 *)(n_hi + (size_t)r * d + k);
+      *(uint2 *)(n_c + (size_t)r * d + k) = make_uint2(cvt_pk_bf16(c * __uint_as_float(a.x << 16), c * __uint_as_float(a.x & 0xffff0000u)),
+                                                       cvt_pk_bf16(c * __uint_as_float(a.y << 16), c * __uint_as_float(a.y & 0xffff0000u)));
+    }
   }
 }
 
@@ -161,27 +219,6 @@ __global__ __launch_bounds__(256) void dpo_pairs_kernel(const float *__restrict_
   if (threadIdx.x == 0) *loss_mean = n_pairs > 0 ? (float)(total / (double)n_pairs) : 0.f;
 }
 
-__global__ __launch_bounds__(256) void dlogits_kernel(const float *__restrict__ logits, int V,
-                                                      const int32_t *__restrict__ label,
-                                                      const int32_t *__restrict__ seq_id, const float *__restrict__ lse,
-                                                      const float *__restrict__ dlogp, bf16_t *__restrict__ dl) {
-  const int r = blockIdx.x;
-  const float c = dlogp[seq_id[r]], l = lse[r];
-  const int lab = label[r];
-  const float *row = logits + (size_t)r * V;
-  bf16_t *out = dl + (size_t)r * V;
-  for (int k = 4 * threadIdx.x; k < V; k += 1024) {
-    const float4 v = *(const float4 *)(row + k);
-    float o[4] = {-expf(v.x - l), -expf(v.y - l), -expf(v.z - l), -expf(v.w - l)};
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      if (k + j == lab) o[j] += 1.0f;
-      o[j] *= c;
-    }
-    *(uint2 *)(out + k) = make_uint2(pack2(f2bf(o[0]), f2bf(o[1])), pack2(f2bf(o[2]), f2bf(o[3])));
-  }
-}
-
 }  // namespace
 
 hipError_t launch_loss_rows(const int32_t *ft_seq_offsets, const int32_t *prompt_lens, const int32_t *token_ids,
@@ -191,17 +228,26 @@ hipError_t launch_loss_rows(const int32_t *ft_seq_offsets, const int32_t *prompt
   return hipGetLastError();
 }
 
-hipError_t launch_logsoftmax_gather(const float *logits, int rows, int V, const int32_t *label, float *logp_t,
-                                    float *lse, hipStream_t st) {
+hipError_t launch_logsoftmax_dl(const float *logits, int rows, int V, const int32_t *label, float *logp_t, float *lse, bf16_t *dl,
+                               hipStream_t st) {
   if (rows <= 0) return hipSuccess;
-  hipLaunchKernelGGL(logsoftmax_gather_kernel, dim3(rows), dim3(256), 0, st, logits, V, label, logp_t, lse);
+  if (V % 4) return hipErrorInvalidValue;
+  if (V <= 4096 * 8) hipLaunchKernelGGL(logsoftmax_dl_kernel<8>, dim3(rows), dim3(1024), 0, st, logits, V, label, logp_t, lse, dl);
+  else if (V <= 4096 * 16) hipLaunchKernelGGL(logsoftmax_dl_kernel<16>, dim3(rows), dim3(1024), 0, st, logits, V, label, logp_t, lse, dl);
+  else hipLaunchKernelGGL(logsoftmax_dl_kernel<0>, dim3(rows), dim3(1024), 0, st, logits, V, label, logp_t, lse, dl);
   return hipGetLastError();
 }
 
-hipError_t launch_label_logit(const bf16_t *n_hi, const bf16_t *n_lo, const bf16_t *e, const int32_t *label, int rows, int d,
-                              int V, float *logits, hipStream_t st) {
+hipError_t launch_logp_correct(const bf16_t *n_lo, const float *u, int rows, int d, float *logp_t, hipStream_t st) {
   if (rows <= 0) return hipSuccess;
-  hipLaunchKernelGGL(label_logit_kernel, dim3(cdiv(rows, 4)), dim3(256), 0, st, n_hi, n_lo, e, label, rows, d, V, logits);
+  hipLaunchKernelGGL(logp_correct_kernel, dim3(cdiv(rows, 4)), dim3(256), 0, st, n_lo, u, rows, d, logp_t);
+  return hipGetLastError();
+}
+
+hipError_t launch_scale_rows(float *u, const bf16_t *n_hi, bf16_t *n_c, const int32_t *seq_id, const float *dlogp, int rows, int d,
+                             hipStream_t st) {
+  if (rows <= 0 || (!u && !n_c)) return hipSuccess;
+  hipLaunchKernelGGL(scale_rows_kernel, dim3(rows), dim3(256), 0, st, u, n_hi, n_c, seq_id, dlogp, d);
   return hipGetLastError();
 }
 
@@ -225,12 +271,5 @@ hipError_t launch_scatter_rows(const float *src, const int32_t *row_idx, const i
                                hipStream_t st) {
   if (rows <= 0) return hipSuccess;
   hipLaunchKernelGGL(scatter_rows_kernel, dim3(rows), dim3(256), 0, st, src, row_idx, partner, d, dst);
-  return hipGetLastError();
-}
-
-hipError_t launch_dlogits(const float *logits, int rows, int V, const int32_t *label, const int32_t *seq_id,
-                          const float *lse, const float *dlogp, bf16_t *dl, hipStream_t st) {
-  if (rows <= 0) return hipSuccess;
-  hipLaunchKernelGGL(dlogits_kernel, dim3(rows), dim3(256), 0, st, logits, V, label, seq_id, lse, dlogp, dl);
   return hipGetLastError();
 }

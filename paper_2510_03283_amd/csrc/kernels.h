@@ -123,16 +123,17 @@ hipError_t launch_loss_rows_shared(const int32_t *pair_offsets, const int32_t *p
 // dst[row_idx[r], :] = src[r, :] (+ src[partner[r], :] when partner[r] >= 0); rows with partner -2 are skipped.
 hipError_t launch_scatter_rows(const float *src, const int32_t *row_idx, const int32_t *partner, int rows, int d, float *dst,
                                hipStream_t st);
-// logp_t[r] = logits[r, label[r]] - logsumexp(logits[r, :]); lse[r] kept.
-// logits[r, label[r]] = sum_k (n_hi + n_lo)[r, k] * e[label[r], k] (fp32), for the rows whose label is in range
-hipError_t launch_label_logit(const bf16_t *n_hi, const bf16_t *n_lo, const bf16_t *e, const int32_t *label, int rows, int d,
-                              int V, float *logits, hipStream_t st);
-hipError_t launch_logsoftmax_gather(const float *logits, int rows, int V, const int32_t *label, float *logp_t,
-                                    float *lse, hipStream_t st);
+// logp_t[r] = logits[r, label[r]] - logsumexp(logits[r, :]); lse[r] kept.  dl (nullable) bf16 [rows, V]:
+// dl[r, j] = [j == label[r]] - exp(logits[r, j] - lse[r]), the gradient of log p(label) with respect to the
+// logits of the row, without the factor of the row's sequence (see launch_scale_rows).  V % 4 == 0.
+hipError_t launch_logsoftmax_dl(const float *logits, int rows, int V, const int32_t *label, float *logp_t, float *lse, bf16_t *dl,
+                               hipStream_t st);
+// logp_t[r] += n_lo[r, :] . u[r, :]  (first-order term of a head that formed its logits from n_hi alone; u = dl E)
+hipError_t launch_logp_correct(const bf16_t *n_lo, const float *u, int rows, int d, float *logp_t, hipStream_t st);
+// c = dlogp[seq_id[r]]:  u[r, :] *= c (u nullable);  n_c[r, :] = bf16(c * n_hi[r, :]) (n_c nullable)
+hipError_t launch_scale_rows(float *u, const bf16_t *n_hi, bf16_t *n_c, const int32_t *seq_id, const float *dlogp, int rows, int d,
+                             hipStream_t st);
 // Per-sequence sums, pair losses, metrics and dloss_mean/dlogp per sequence.
 hipError_t launch_dpo_pairs(const float *logp_t, const int32_t *ft_seq_offsets, const int32_t *prompt_lens, int n_seq,
                             const float *ref_logp, float beta, float *logp_out, float *loss_per_pair, float *loss_mean,
                             float *clpd, int32_t *win, float *dlogp, hipStream_t st);
-// dl[r, j] = dlogp[seq_id[r]] * ([j == label[r]] - exp(logits[r, j] - lse[r])) as bf16.
-hipError_t launch_dlogits(const float *logits, int rows, int V, const int32_t *label, const int32_t *seq_id,
-                          const float *lse, const float *dlogp, bf16_t *dl, hipStream_t st);
