@@ -287,6 +287,18 @@ int mace_next_token_logits(mace_handle_t h, const float *y, const int32_t *row_i
                            const void *w_lm, float *logits_out, int32_t *next_token, void *workspace,
                            size_t workspace_bytes, void *stream);
 
+/* mace_next_token_logits for callers that cannot allocate device memory or bring a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * without the workspace, same kernels, bit-identical results; the normalised rows go to a buffer
+ * built into the library (4 MiB of device memory per GPU, held until the process ends) instead.
+ * Limits: a bf16 model (MACE_BAD_SHAPE otherwise: fp32 weights would need a converted copy of the
+ * head), n * d_model * 2 <= 4 MiB, e.g. 512 rows at d_model 4096 (MACE_WORKSPACE_TOO_SMALL
+ * otherwise), and the device of mace_create must be current (MACE_INVALID_ARG otherwise).  The call
+ * allocates and frees nothing and issues no memset.  Every call on one GPU, from any handle, shares
+ * the one buffer: calls that overlap on a GPU (two streams, two threads) race; order them. */
+int mace_next_token_logits_static(mace_handle_t h, const float *y, const int32_t *row_idx, int32_t n, const void *g_final,
+                                  const void *w_lm, float *logits_out, int32_t *next_token, void *stream);
+
 /* AdamW step (decoupled weight decay) on one tensor of n elements: the optimizer step that turns
  * the gradients of an iteration into the weights the next iteration sees (Section 2.1).  The paper
  * names no optimizer; AdamW is the reading.  step counts from 1.

@@ -20,7 +20,7 @@ EXPORTS = [
     "mace_kv_slot_mapping", "mace_kv_cache_append", "mace_kv_cache_gather", "mace_hybrid_layer_fwd",
     "mace_hybrid_layer_bwd", "mace_hybrid_layer_fwd_lora", "mace_hybrid_layer_bwd_lora", "mace_dpo_logprob_loss", "mace_dpo_logprob_loss_shared",
     "mace_next_token_logits", "mace_adamw_step", "mace_head_norm_stats", "mace_kv_head_budget", "mace_profile_enable", "mace_profile_collect",
-    "mace_set_option", "mace_launch_plan",
+    "mace_set_option", "mace_launch_plan", "mace_next_token_logits_static",
 ]
 MACE_OPT_HEAD_TWO_PASS, MACE_OPT_SINGLE_STREAM, MACE_OPT_DECODE_CHUNK = 1, 2, 3
 
@@ -118,6 +118,8 @@ def load():
     lib.mace_dpo_logprob_loss.restype = C.c_int
     lib.mace_next_token_logits.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.mace_next_token_logits.restype = C.c_int
+    lib.mace_next_token_logits_static.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp]
+    lib.mace_next_token_logits_static.restype = C.c_int
     lib.mace_adamw_step.argtypes = [vp, vp, vp, vp, vp, vp, i64, f32, f32, f32, f32, f32, i32, vp]
     lib.mace_adamw_step.restype = C.c_int
     lib.mace_head_norm_stats.argtypes = [vp, vp, vp, i32, i32, vp, vp, i32, f32, vp, vp]
@@ -312,6 +314,11 @@ def mace_next_token_logits(h, y, row_idx, n, g_final, w_lm, logits_out, next_tok
     _check(load().mace_next_token_logits(h, _dev(y), _dev(row_idx), int(n), _dev(g_final), _dev(w_lm), _dev(logits_out), _dev(next_token),
                                          _dev(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
            "mace_next_token_logits")
+
+
+def mace_next_token_logits_static(h, y, row_idx, n, g_final, w_lm, logits_out, next_token, stream=None):
+    _check(load().mace_next_token_logits_static(h, _dev(y), _dev(row_idx), int(n), _dev(g_final), _dev(w_lm), _dev(logits_out),
+                                                _dev(next_token), _stream(stream)), "mace_next_token_logits_static")
 
 
 def mace_adamw_step(h, param, master, grad, m, v, lr, beta1, beta2, eps, weight_decay, step, stream=None):

@@ -34,12 +34,21 @@ struct mace_ctx {
   bool single_stream = false;   // MACE_OPT_SINGLE_STREAM
   int decode_chunk = 0;         // MACE_OPT_DECODE_CHUNK
   std::vector<mace_gemm_plan_t> plan;   // launch decisions of the GEMMs of the last iteration call
+  int device = 0;                       // the device that was current in mace_create
+  void *static_scratch = nullptr;       // device address of g_static_scratch on that device
   bool prof_on = false;
   unsigned prof_mask = ~0u;        // kernel classes that are timed
   bool prof_open[2] = {false, false};   // per chain: the last mark opened an interval
   std::vector<hipEvent_t> prof_events;
   std::vector<ProfMark> prof_marks;
 };
+
+// Scratch of mace_next_token_logits_static: the normalised rows (bf16) of one call.  One copy per GPU,
+// held until the process ends; every call on a GPU shares it (overlapping calls race).  Host code
+// never uses this name as an address: mace_create asks the runtime for the device address
+// (hipGetSymbolAddress, once per handle, with the handle's device current) and keeps it in the context.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)4 << 20;
+static __device__ __align__(256) unsigned char g_static_scratch[STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -515,6 +524,12 @@ int mace_create(mace_handle_t *out, const mace_model_t *model) {
     delete c;
     return hip_fail(e, "mace_create");
   }
+  e = hipGetDevice(&c->device);
+  if (e == hipSuccess) e = hipGetSymbolAddress(&c->static_scratch, HIP_SYMBOL(g_static_scratch));
+  if (e != hipSuccess || !c->static_scratch) {
+    mace_destroy(c);
+    return e != hipSuccess ? hip_fail(e, "mace_create: static scratch address") : fail(MACE_HIP_ERROR, "mace_create: static scratch address is null");
+  }
   e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
   for (int i = 0; i < N_FORK_EVENTS && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&c->ev_fork[i], hipEventDisableTiming);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming);
@@ -680,6 +695,28 @@ int mace_next_token_logits(mace_handle_t h, const float *y, const int32_t *row_i
   if (n == 0) return MACE_OK;
   if (!workspace || ((uintptr_t)workspace & 255)) return fail(MACE_INVALID_ARG, "workspace must be non-null and 256-byte aligned");
   return next_token_logits_impl(h, y, row_idx, n, g_final, w_lm, logits_out, next_token, workspace, workspace_bytes, stream);
+}
+
+int mace_next_token_logits_static(mace_handle_t h, const float *y, const int32_t *row_idx, int32_t n, const void *g_final,
+                                  const void *w_lm, float *logits_out, int32_t *next_token, void *stream) {
+  if (!h || !y || !g_final || !w_lm || !logits_out || n < 0) return fail(MACE_INVALID_ARG, "mace_next_token_logits_static: bad argument");
+  if (n == 0) return MACE_OK;
+  const Dims D(h->m);
+  if (!D.bf) return fail(MACE_BAD_SHAPE, "mace_next_token_logits_static needs a bf16 model (fp32 weights would need a converted copy of the head)");
+  {
+    Bump m(nullptr);
+    plan_logits(D, (size_t)n, m);
+    if (m.off > STATIC_SCRATCH_BYTES) {
+      char msg[160];
+      snprintf(msg, sizeof(msg), "mace_next_token_logits_static: %d rows of d_model %d need %zu bytes of scratch, the built-in buffer holds %zu",
+               n, D.d, m.off, STATIC_SCRATCH_BYTES);
+      return fail(MACE_WORKSPACE_TOO_SMALL, msg);
+    }
+  }
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev), "hipGetDevice");
+  if (dev != h->device) return fail(MACE_INVALID_ARG, "mace_next_token_logits_static: the handle was created on another device than the current one");
+  return next_token_logits_impl(h, y, row_idx, n, g_final, w_lm, logits_out, next_token, h->static_scratch, STATIC_SCRATCH_BYTES, stream);
 }
 
 int mace_adamw_step(mace_handle_t h, void *param, float *master, const float *grad, float *m, float *v, int64_t n, float lr,
