@@ -141,7 +141,8 @@ void mace_destroy(mace_handle_t h);
  *                           at mace_dpo_logprob_loss.
  *   MACE_OPT_SINGLE_STREAM  1: never use the internal stream (bitwise the same results).
  *   MACE_OPT_DECODE_CHUNK   tokens of context per decode-attention block: 0 = chosen per launch,
- *                           else a power of two in 512..4096. */
+ *                           else a power of two in 512..4096.  The size of the partial-state scratch
+ *                           depends on it: set it before mace_workspace_bytes is asked. */
 enum { MACE_OPT_HEAD_TWO_PASS = 1, MACE_OPT_SINGLE_STREAM = 2, MACE_OPT_DECODE_CHUNK = 3 };
 int mace_set_option(mace_handle_t h, int32_t option, int32_t value);
 

@@ -205,7 +205,7 @@ struct FwdWs {
   float *qkv_f;
   bf16_t *a_lo, *q_lo, *k_lo, *v_lo, *o_lo, *b_lo, *hm_hi, *hm_lo;
 };
-FwdWs plan_fwd(const Dims &D, size_t Ti, size_t Tf, int n_decode, int max_ctx, Bump &w) {
+FwdWs plan_fwd(const Dims &D, size_t Ti, size_t Tf, int n_decode, int max_ctx, int decode_chunk, Bump &w) {
   FwdWs F;
   F.a_i = w.take<bf16_t>(Ti * D.d);
   F.qkv_i = w.take<float>(Ti * D.nqkv);
@@ -216,7 +216,7 @@ FwdWs plan_fwd(const Dims &D, size_t Ti, size_t Tf, int n_decode, int max_ctx, B
   F.x1_i = w.take<float>(Ti * D.d);
   F.b_i = w.take<bf16_t>(Ti * D.d);
   F.hm_i = w.take<bf16_t>(Ti * D.F);
-  F.dec_partial = w.take<float>(decode_partial_floats(n_decode, D.Hq, D.hd, max_ctx));
+  F.dec_partial = w.take<float>(decode_partial_floats(n_decode, D.Hq, D.Hkv, D.hd, max_ctx, decode_chunk));
   F.qkv_f = w.take<float>(Tf * D.nqkv);
   F.a_lo = w.take<bf16_t>(Tf * D.d);
   F.q_lo = w.take<bf16_t>(Tf * D.qd);
@@ -645,7 +645,7 @@ size_t mace_workspace_bytes(mace_handle_t h, int32_t n_tokens, int32_t n_ft_toke
   WSplit ws;
   Bump f(nullptr), b(nullptr), p(nullptr);
   prepare_weights(D, nullptr, f, true, false, nullptr, ws);
-  plan_fwd(D, (size_t)(n_tokens - n_ft_tokens), (size_t)n_ft_tokens, n_decode, max_context, f);
+  plan_fwd(D, (size_t)(n_tokens - n_ft_tokens), (size_t)n_ft_tokens, n_decode, max_context, h->decode_chunk, f);
   plan_lora(D, (size_t)n_tokens, false, f);
   prepare_weights(D, nullptr, b, false, false, nullptr, ws);
   plan_bwd(D, (size_t)n_ft_tokens, b);
@@ -845,14 +845,14 @@ static int layer_fwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
     Bump m(nullptr);
     WSplit tmp;
     prepare_weights(D, w, m, true, false, st, tmp);
-    plan_fwd(D, I.Ti, I.Tf, I.Td, I.max_ctx, m);
+    plan_fwd(D, I.Ti, I.Tf, I.Td, I.max_ctx, h->decode_chunk, m);
     if (lora) plan_lora(D, (size_t)I.T, false, m);
     if (m.off > workspace_bytes) return fail(MACE_WORKSPACE_TOO_SMALL, "forward workspace too small");
   }
   SideGuard side_guard(h, st);      // waits for side-stream work an earlier failed call may have left; joins on every return
   Bump wsb(workspace), svb(saved);
   TRY(prepare_weights(D, w, wsb, true, true, st, W));
-  FwdWs F = plan_fwd(D, I.Ti, I.Tf, I.Td, I.max_ctx, wsb);
+  FwdWs F = plan_fwd(D, I.Ti, I.Tf, I.Td, I.max_ctx, h->decode_chunk, wsb);
   LoraWs L;
   if (lora) {
     L = plan_lora(D, (size_t)I.T, false, wsb);

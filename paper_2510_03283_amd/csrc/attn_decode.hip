@@ -258,8 +258,22 @@ bool launch_grp(int grp, const bf16_t *q, const void *ck, const void *cv, long l
 
 }  // namespace
 
-size_t decode_partial_floats(int n_decode, int Hq, int hd, int max_context) {
-  const size_t nsplit = (size_t)cdiv(max_context + 1, MIN_CHUNK);      // the smallest chunk gives the most splits
+// Tokens per block.  Long chunks mean fewer blocks that find nothing to do, fewer partial states to write
+// and merge and a longer stream per block (6.2 -> 6.6 TB/s from 512 to 2048 tokens on a 256-request,
+// 32-head batch) - as long as the grid still fills the chip several times over.  Shorter chunks than 512
+// tokens do not help small batches (32 requests x 8 kv heads of 4 query heads each: 41 us at 512, 49 us
+// at 128): with four query heads per kv head the per-token arithmetic, not the stream, sets the time.
+static int decode_chunk_tokens(int n_decode, int Hkv, int max_context, int chunk_tokens) {
+  if (chunk_tokens) return chunk_tokens >= MIN_CHUNK && chunk_tokens <= MAX_CHUNK && !(chunk_tokens & (chunk_tokens - 1)) ? chunk_tokens : -1;
+  int chunk = MIN_CHUNK;
+  while (chunk < MAX_CHUNK && (long long)Hkv * n_decode * cdiv(max_context + 1, 2 * chunk) >= 8192) chunk *= 2;
+  return chunk;
+}
+
+size_t decode_partial_floats(int n_decode, int Hq, int Hkv, int hd, int max_context, int chunk_tokens) {
+  int chunk = decode_chunk_tokens(n_decode, Hkv, max_context, chunk_tokens);
+  if (chunk < 0) chunk = MIN_CHUNK;                                    // an invalid override is rejected at launch; size for the worst case
+  const size_t nsplit = (size_t)cdiv(max_context + 1, chunk);
   return (size_t)n_decode * Hq * nsplit * (hd + 2);
 }
 
@@ -272,15 +286,8 @@ hipError_t launch_attn_decode(const bf16_t *q, const void *cache_k, const void *
   int bshift = 0;
   while ((1 << bshift) < block_size) ++bshift;
   if ((1 << bshift) != block_size) return hipErrorInvalidValue;
-  // Tokens per block: long chunks mean fewer blocks that find nothing to do, fewer partial states to
-  // write and merge and a longer stream per block (6.2 -> 6.6 TB/s from 512 to 2048 tokens on a
-  // 256-request, 32-head batch), as long as the grid still fills the chip several times over.
-  int chunk = MIN_CHUNK;
-  while (chunk < MAX_CHUNK && (long long)Hkv * n_decode * cdiv(max_context + 1, 2 * chunk) >= 8192) chunk *= 2;
-  if (chunk_tokens) {                                       // pinned by the caller
-    if (chunk_tokens < MIN_CHUNK || chunk_tokens > MAX_CHUNK || (chunk_tokens & (chunk_tokens - 1))) return hipErrorInvalidValue;
-    chunk = chunk_tokens;
-  }
+  const int chunk = decode_chunk_tokens(n_decode, Hkv, max_context, chunk_tokens);
+  if (chunk < 0) return hipErrorInvalidValue;
   const int nsplit = cdiv(max_context + 1, chunk);
   if (nsplit > 65535) return hipErrorInvalidValue;
   const int grp = Hq / Hkv;

@@ -89,7 +89,7 @@ hipError_t launch_attn_fwd_paged(const bf16_t *q, const void *cache_k, const voi
 // One query row per request against its paged context of ctx_len[r]+1 tokens.  q bf16
 // [n_decode, Hq*hd] (rows of the decode class), out bf16 same shape.  partial: fp32 scratch of
 // decode_partial_floats() floats.  norms (nullable): fp32 [n_decode, Hq], L2 norm of each head's output.
-size_t decode_partial_floats(int n_decode, int Hq, int hd, int max_context);
+size_t decode_partial_floats(int n_decode, int Hq, int Hkv, int hd, int max_context, int chunk_tokens);
 hipError_t launch_attn_decode(const bf16_t *q, const void *cache_k, const void *cache_v, bool cache_bf16,
                               long long num_blocks, int block_size, const int32_t *block_tables, int max_blocks_per_req,
                               const int32_t *ctx_lens, int n_decode, int max_context, int Hq, int Hkv, int hd,

@@ -145,7 +145,7 @@ def test_decode_chunk_lengths(torch_mod, chunk, hq, hkv, hd):
     the partial soft-max states of one, two and several chunks must merge to the same result."""
     from paper_2510_03283_amd import binding as B
     dims = synth.ModelDims(n_q_heads=hq, n_kv_heads=hkv, head_dim=hd, **SMALL)
-    wl = custom_workload("chunks", dims, prefill=[5], decode=[0, 511, 512, 1023, 2047, 2048, 4100, 5000], n_pairs=1, prompt=3, resp=(2, 9))
+    wl = custom_workload("chunks", dims, prefill=[5], decode=[0, 127, 128, 255, 511, 512, 1023, 2047, 2048, 4100, 5000], n_pairs=1, prompt=3, resp=(2, 9))
     check_iteration(torch_mod, wl, f"decode chunk {chunk} Hq{hq} Hkv{hkv} hd{hd}", options={B.MACE_OPT_DECODE_CHUNK: chunk})
 
 
