@@ -232,7 +232,8 @@ FwdWs plan_fwd(const Dims &D, size_t Ti, size_t Tf, int n_decode, int max_ctx, i
 // ---------------------------------------------------------------- backward scratch
 struct BwdWs {
   bf16_t *dy_bf, *dhm, *dgu, *hm, *dx1_bf, *dattn, *dqkv;
-  float *db, *dx1, *dvec, *dq, *dk, *dv, *da, *dg_part;
+  float *db, *dx1, *dvec, *da, *dg_part;
+  float2 *cs;      // rotary (cos, sin) of every fine-tune row, [Tf, hd/2]
 };
 BwdWs plan_bwd(const Dims &D, size_t Tf, Bump &w) {
   BwdWs B;
@@ -245,9 +246,7 @@ BwdWs plan_bwd(const Dims &D, size_t Tf, Bump &w) {
   B.dx1_bf = w.take<bf16_t>(Tf * D.d);
   B.dattn = w.take<bf16_t>(Tf * D.qd);
   B.dvec = w.take<float>(Tf * D.Hq);
-  B.dq = w.take<float>(Tf * D.qd);
-  B.dk = w.take<float>(Tf * D.kd);
-  B.dv = w.take<float>(Tf * D.kd);
+  B.cs = w.take<float2>(Tf * (D.hd / 2));
   B.dqkv = w.take<bf16_t>(Tf * D.nqkv);
   B.da = w.take<float>(Tf * D.d);
   B.dg_part = w.take<float>((size_t)(DG_PARTS + COLSUM_SLICES) * D.d);     // partial rows + scratch of their column sum
@@ -1137,12 +1136,13 @@ static int layer_bwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
       if (s2 != st) prof_mark(h, s2, -1);
     }
   }
-  // attention backward, RoPE backward
+  // attention backward; its epilogues rotate dq and dk back (RoPE backward) and write the bf16 operand of the
+  // projection backward directly
+  prof_mark(h, st, T_ROPE);
+  HIP_TRY(launch_rope_table(batch->positions + I.Ti, h->inv_freq, Tf, D.hd, B.cs, st), "rope table");
   prof_mark(h, st, T_ATTN_BWD, 10.0 * D.hd * D.Hq * I.pairs_ft);
   HIP_TRY(launch_attn_bwd(S.q, S.k, S.v, S.o, B.dattn, S.lse, batch->seg_offsets + batch->n_prefill + batch->n_decode, I.Ti, batch->n_ft_seq, I.max_ft, Tf,
-                          D.Hq, D.Hkv, D.hd, B.dvec, B.dq, B.dk, B.dv, st, batch->ft_excl_lo, batch->ft_excl_hi), "attention bwd");
-  prof_mark(h, st, T_ROPE);
-  HIP_TRY(launch_rope_bwd(B.dq, B.dk, B.dv, batch->positions + I.Ti, h->inv_freq, Tf, D.Hq, D.Hkv, D.hd, B.dqkv, st), "rope bwd");
+                          D.Hq, D.Hkv, D.hd, B.dvec, B.cs, B.dqkv, st, batch->ft_excl_lo, batch->ft_excl_hi), "attention bwd");
   // da = dq Wq + dk Wk + dv Wv ; dWq, dWk, dWv
   {
     const bf16_t *as[3] = {B.dqkv, B.dqkv + D.qd, B.dqkv + D.qd + D.kd};

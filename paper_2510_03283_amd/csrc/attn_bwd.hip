@@ -8,6 +8,10 @@
 //    dV^T = dO^T P and dK^T = Q^T dS.
 // P is recomputed from the saved log-sum-exp; D = rowsum(dO * O) is formed by the dq kernel from the
 // fragments it loads anyway and handed to the dk/dv kernel through memory.
+// The backward of the rotary embedding is part of both epilogues: the two halves (i, i + hd/2) of a
+// head row sit in one lane (accumulator tiles t and t + hd/64), so dq and dk are rotated back by the
+// row's angles (a per-row (cos, sin) table) and written, like dv, as bf16 straight into the
+// [rows, (Hq + 2 Hkv) hd] operand of the projection backward - no fp32 dq / dk / dv in memory.
 // Tiles of 64 rows go global -> LDS directly in their memory layout, two stages deep; the same
 // tile feeds the products that reduce over the head dimension (16-byte reads) and those that
 // reduce over the tile rows (transposing reads), see attn_tile.h.
@@ -26,6 +30,34 @@ __device__ __forceinline__ bf16x8_t pack8(const float *v) {
   return as_bf8(make_uint4(cvt_pk_bf16(v[0], v[1]), cvt_pk_bf16(v[2], v[3]), cvt_pk_bf16(v[4], v[5]), cvt_pk_bf16(v[6], v[7])));
 }
 
+// Epilogue of a gradient row held as NOT accumulator tiles of 32 head-dim indices (register 4*rq + e of
+// tile t = index 32 t + 8 rq + 4 g + e): rotate the pairs (i, i + HD/2) back by the row's angles
+// (cs = (cos, sin) of the row, HD/2 entries; null = no rotation) and store as bf16 at dst[0 .. HD).
+template <int HD>
+__device__ __forceinline__ void store_grad_row(const f32x16_t (&acc)[HD / 32], const float2 *__restrict__ cs, int g, bf16_t *__restrict__ dst) {
+  constexpr int NOT = HD / 32, HT = NOT / 2;
+#pragma unroll
+  for (int t = 0; t < HT; ++t)
+#pragma unroll
+    for (int rq = 0; rq < 4; ++rq) {
+      const int i = t * 32 + 8 * rq + 4 * g;
+      float a[4], b[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { a[e] = acc[t][4 * rq + e]; b[e] = acc[t + HT][4 * rq + e]; }
+      if (cs) {
+        const float4 c01 = *(const float4 *)(cs + i), c23 = *(const float4 *)(cs + i + 2);
+        const float co[4] = {c01.x, c01.z, c23.x, c23.z}, si[4] = {c01.y, c01.w, c23.y, c23.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float ra = a[e] * co[e] + b[e] * si[e], rb = b[e] * co[e] - a[e] * si[e];
+          a[e] = ra; b[e] = rb;
+        }
+      }
+      *(uint2 *)(dst + i) = make_uint2(cvt_pk_bf16(a[0], a[1]), cvt_pk_bf16(a[2], a[3]));
+      *(uint2 *)(dst + i + HD / 2) = make_uint2(cvt_pk_bf16(b[0], b[1]), cvt_pk_bf16(b[2], b[3]));
+    }
+}
+
 // ------------------------------------------------------------------ dQ
 template <int HD>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
@@ -33,7 +65,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16_t *__res
                                                           const bf16_t *__restrict__ d_o,
                                                           const float *__restrict__ lse, float *__restrict__ dvec,
                                                           const int32_t *__restrict__ seg, int row_base, int Hq, int Hkv,
-                                                          float *__restrict__ dq, const int32_t *__restrict__ excl_lo,
+                                                          const float2 *__restrict__ cs, bf16_t *__restrict__ dqkv,
+                                                          const int32_t *__restrict__ excl_lo,
                                                           const int32_t *__restrict__ excl_hi) {
   constexpr int NKK = HD / 16, NOT = HD / 32;
   using T = Tile<TB, HD, 256>;
@@ -141,14 +174,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16_t *__res
       }
     }
   }
-  if (qi < L) {
-    float *dst = dq + (size_t)(r0 + qi) * qld + (size_t)h * HD;
-#pragma unroll
-    for (int t = 0; t < NOT; ++t)
-#pragma unroll
-      for (int rq = 0; rq < 4; ++rq)
-        *(float4 *)(dst + t * 32 + 8 * rq + 4 * g) = make_float4(acc[t][4 * rq], acc[t][4 * rq + 1], acc[t][4 * rq + 2], acc[t][4 * rq + 3]);
-  }
+  if (qi < L)
+    store_grad_row<HD>(acc, cs + (size_t)(r0 + qi) * (HD / 2), g, dqkv + (size_t)(r0 + qi) * (qld + 2 * kld) + (size_t)h * HD);
 }
 
 // ------------------------------------------------------------------ dK, dV
@@ -157,7 +184,7 @@ __global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(co
                                                             const bf16_t *__restrict__ v, const bf16_t *__restrict__ d_o,
                                                             const float *__restrict__ lse, const float *__restrict__ dvec,
                                                             const int32_t *__restrict__ seg, int row_base, int Hq,
-                                                            int Hkv, float *__restrict__ dk, float *__restrict__ dv,
+                                                            int Hkv, const float2 *__restrict__ cs, bf16_t *__restrict__ dqkv,
                                                             const int32_t *__restrict__ excl_lo, const int32_t *__restrict__ excl_hi) {
   constexpr int NKK = HD / 16, NOT = HD / 32;
   using T = Tile<TB, HD, 256>;
@@ -269,21 +296,16 @@ __global__ __launch_bounds__(256, HD == 64 ? 2 : 1) void attn_bwd_dkdv_kernel(co
     }
   }
   if (ki < L) {
-    float *dkd = dk + (size_t)(r0 + ki) * kld + (size_t)kvh * HD, *dvd = dv + (size_t)(r0 + ki) * kld + (size_t)kvh * HD;
-#pragma unroll
-    for (int t = 0; t < NOT; ++t)
-#pragma unroll
-      for (int rq = 0; rq < 4; ++rq) {
-        *(float4 *)(dkd + t * 32 + 8 * rq + 4 * g) = make_float4(dka[t][4 * rq], dka[t][4 * rq + 1], dka[t][4 * rq + 2], dka[t][4 * rq + 3]);
-        *(float4 *)(dvd + t * 32 + 8 * rq + 4 * g) = make_float4(dva[t][4 * rq], dva[t][4 * rq + 1], dva[t][4 * rq + 2], dva[t][4 * rq + 3]);
-      }
+    bf16_t *row = dqkv + (size_t)(r0 + ki) * (qld + 2 * kld) + qld + (size_t)kvh * HD;     // dk of this kv head; dv sits kld further
+    store_grad_row<HD>(dka, cs + (size_t)(r0 + ki) * (HD / 2), g, row);
+    store_grad_row<HD>(dva, nullptr, g, row + kld);
   }
 }
 
 template <int HD>
 hipError_t launch_t(const bf16_t *q, const bf16_t *k, const bf16_t *v, const bf16_t *o, const bf16_t *d_o,
                     const float *lse, const int32_t *seg, int row_base, int n_seq, int max_len, int rows, int Hq,
-                    int Hkv, float *dvec, float *dq, float *dk, float *dv, hipStream_t st, const int32_t *excl_lo,
+                    int Hkv, float *dvec, const float2 *cs, bf16_t *dqkv, hipStream_t st, const int32_t *excl_lo,
                     const int32_t *excl_hi) {
   constexpr size_t lds_q = (size_t)2 * (2 * TB * HD) * sizeof(bf16_t);
   constexpr size_t lds_k = (size_t)2 * (2 * TB * HD + 4 * TB) * sizeof(bf16_t);
@@ -296,10 +318,10 @@ hipError_t launch_t(const bf16_t *q, const bf16_t *k, const bf16_t *v, const bf1
     attr_done.set();
   }
   dim3 grid_q(Hq, n_seq, cdiv(max_len, 128)), grid_k(Hkv, n_seq, cdiv(max_len, 128));
-  hipLaunchKernelGGL((attn_bwd_dq_kernel<HD>), grid_q, dim3(256), lds_q, st, q, k, v, o, d_o, lse, dvec, seg, row_base, Hq, Hkv, dq, excl_lo, excl_hi);
+  hipLaunchKernelGGL((attn_bwd_dq_kernel<HD>), grid_q, dim3(256), lds_q, st, q, k, v, o, d_o, lse, dvec, seg, row_base, Hq, Hkv, cs, dqkv, excl_lo, excl_hi);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((attn_bwd_dkdv_kernel<HD>), grid_k, dim3(256), lds_k, st, q, k, v, d_o, lse, dvec, seg, row_base, Hq, Hkv, dk, dv, excl_lo, excl_hi);
+  hipLaunchKernelGGL((attn_bwd_dkdv_kernel<HD>), grid_k, dim3(256), lds_k, st, q, k, v, d_o, lse, dvec, seg, row_base, Hq, Hkv, cs, dqkv, excl_lo, excl_hi);
   return hipGetLastError();
 }
 
@@ -307,11 +329,11 @@ hipError_t launch_t(const bf16_t *q, const bf16_t *k, const bf16_t *v, const bf1
 
 hipError_t launch_attn_bwd(const bf16_t *q, const bf16_t *k, const bf16_t *v, const bf16_t *o, const bf16_t *d_o,
                            const float *lse, const int32_t *seg, int row_base, int n_seq, int max_len, int rows,
-                           int Hq, int Hkv, int hd, float *dvec, float *dq, float *dk, float *dv, hipStream_t st,
+                           int Hq, int Hkv, int hd, float *dvec, const float2 *cs, bf16_t *dqkv, hipStream_t st,
                            const int32_t *excl_lo, const int32_t *excl_hi) {
   if (n_seq <= 0 || rows <= 0) return hipSuccess;
   if (n_seq > 65535 || max_len > 65535 * 64 || ((excl_lo == nullptr) != (excl_hi == nullptr))) return hipErrorInvalidValue;
-  if (hd == 64) return launch_t<64>(q, k, v, o, d_o, lse, seg, row_base, n_seq, max_len, rows, Hq, Hkv, dvec, dq, dk, dv, st, excl_lo, excl_hi);
-  if (hd == 128) return launch_t<128>(q, k, v, o, d_o, lse, seg, row_base, n_seq, max_len, rows, Hq, Hkv, dvec, dq, dk, dv, st, excl_lo, excl_hi);
+  if (hd == 64) return launch_t<64>(q, k, v, o, d_o, lse, seg, row_base, n_seq, max_len, rows, Hq, Hkv, dvec, cs, dqkv, st, excl_lo, excl_hi);
+  if (hd == 128) return launch_t<128>(q, k, v, o, d_o, lse, seg, row_base, n_seq, max_len, rows, Hq, Hkv, dvec, cs, dqkv, st, excl_lo, excl_hi);
   return hipErrorInvalidValue;
 }

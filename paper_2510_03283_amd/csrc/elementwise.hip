@@ -201,24 +201,13 @@ __global__ __launch_bounds__(256) void rope_split_kernel(const float *qkv, const
   }
 }
 
-__global__ __launch_bounds__(256) void rope_bwd_kernel(const float *dq, const float *dk, const float *dv,
-                                                       const int32_t *positions, const double *inv_freq, int Hq,
-                                                       int Hkv, int hd, bf16_t *dqkv) {
-  __shared__ float2 cs[64];
-  const int r = blockIdx.x, half = hd >> 1;
-  rope_table(cs, positions[r], inv_freq, half);
-  const int qd = Hq * hd, kd = Hkv * hd, nq = qd + 2 * kd;
-  bf16_t *out = dqkv + (size_t)r * nq;
-  const int npair = (Hq + Hkv) * half;
-  for (int idx = threadIdx.x; idx < npair; idx += 256) {
-    const int head = idx / half, i = idx - head * half;
-    const float *src = head < Hq ? dq + (size_t)r * qd + head * hd : dk + (size_t)r * kd + (head - Hq) * hd;
-    const float a = src[i], b = src[i + half];
-    const float2 t = cs[i];
-    out[head * hd + i] = f2bf(a * t.x + b * t.y);
-    out[head * hd + i + half] = f2bf(b * t.x - a * t.y);
-  }
-  for (int idx = threadIdx.x; idx < kd; idx += 256) out[qd + kd + idx] = f2bf(dv[(size_t)r * kd + idx]);
+__global__ __launch_bounds__(64) void rope_table_kernel(const int32_t *__restrict__ positions, const double *__restrict__ inv_freq,
+                                                        int half, float2 *__restrict__ cs) {
+  const int r = blockIdx.x, i = threadIdx.x;
+  if (i >= half) return;
+  double sn, c;
+  sincos((double)positions[r] * inv_freq[i], &sn, &c);
+  cs[(size_t)r * half + i] = make_float2((float)c, (float)sn);
 }
 
 // ------------------------------------------------------------------ SwiGLU
@@ -335,11 +324,10 @@ hipError_t launch_rope_split(const float *qkv, const int32_t *positions, const d
   return hipGetLastError();
 }
 
-hipError_t launch_rope_bwd(const float *dq, const float *dk, const float *dv, const int32_t *positions,
-                           const double *inv_freq, int rows, int Hq, int Hkv, int hd, bf16_t *dqkv, hipStream_t st) {
+hipError_t launch_rope_table(const int32_t *positions, const double *inv_freq, int rows, int hd, float2 *cs, hipStream_t st) {
   if (rows <= 0) return hipSuccess;
   if (hd > 128) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(rope_bwd_kernel, dim3(rows), dim3(256), 0, st, dq, dk, dv, positions, inv_freq, Hq, Hkv, hd, dqkv);
+  hipLaunchKernelGGL(rope_table_kernel, dim3(rows), dim3(64), 0, st, positions, inv_freq, hd >> 1, cs);
   return hipGetLastError();
 }
 

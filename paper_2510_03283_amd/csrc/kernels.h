@@ -30,10 +30,9 @@ hipError_t launch_rope_split(const float *qkv, const int32_t *positions, const d
                              int Hkv, int hd, bf16_t *q_hi, bf16_t *k_hi, bf16_t *v_hi, bf16_t *q_lo, bf16_t *k_lo,
                              bf16_t *v_lo, const int32_t *slot_mapping, void *cache_k, void *cache_v, bool cache_bf16,
                              long long num_slots, int block_size, hipStream_t st);
-// Transposed rotation of dq (fp32 [rows, Hq*hd]) and dk, copy of dv (fp32 [rows, Hkv*hd]) into
-// dqkv bf16 [rows, (Hq+2Hkv)*hd].
-hipError_t launch_rope_bwd(const float *dq, const float *dk, const float *dv, const int32_t *positions,
-                           const double *inv_freq, int rows, int Hq, int Hkv, int hd, bf16_t *dqkv, hipStream_t st);
+// cs[r, i] = (cos, sin) of positions[r] * inv_freq[i], i < hd/2 (angle formed and reduced in fp64): the
+// per-row rotary table the attention backward rotates dq and dk back with.
+hipError_t launch_rope_table(const int32_t *positions, const double *inv_freq, int rows, int hd, float2 *cs, hipStream_t st);
 // dU = dhm*silu(G), dG = dhm*U*sig(G)*(1+G*(1-sig(G))) -> dgu bf16 [rows, 2F]; hm (bf16) recomputed.
 // gu bf16 [rows, 2F] (G = columns [0,F), U = [F,2F)) as the gate/up GEMM left it.
 hipError_t launch_swiglu_bwd(const bf16_t *dhm, const bf16_t *gu, int rows, int F, bf16_t *dgu, bf16_t *hm, hipStream_t st);
@@ -99,11 +98,13 @@ hipError_t launch_attn_decode(const bf16_t *q, const void *cache_k, const void *
 hipError_t launch_head_norm_stats(const float *norms, const int32_t *t_count, int n, int H, float *abar, int32_t *last_used,
                                   int window, float tau, int32_t *prune, hipStream_t st);
 // ---- attn_bwd.hip ----------------------------------------------------------------------------
-// Backward of the varlen causal attention of the fine-tune sequences (bf16 operands, fp32 out).
+// Backward of the varlen causal attention of the fine-tune sequences (bf16 operands), rotary backward
+// included: dqkv bf16 [rows, (Hq+2Hkv)*hd] receives dq and dk rotated back by the rows' angles (cs: the
+// table of launch_rope_table, [rows, hd/2]) and dv, i.e. the gradient of the projection output.
 // dvec: fp32 scratch [rows, Hq] (rowsum(dO * O), written by the dq kernel, read by the dk/dv kernel).
 hipError_t launch_attn_bwd(const bf16_t *q, const bf16_t *k, const bf16_t *v, const bf16_t *o, const bf16_t *d_o,
                            const float *lse, const int32_t *seg, int row_base, int n_seq, int max_len, int rows,
-                           int Hq, int Hkv, int hd, float *dvec, float *dq, float *dk, float *dv, hipStream_t st,
+                           int Hq, int Hkv, int hd, float *dvec, const float2 *cs, bf16_t *dqkv, hipStream_t st,
                            const int32_t *excl_lo = nullptr, const int32_t *excl_hi = nullptr);
 
 // ---- dpo_head.hip ----------------------------------------------------------------------------
