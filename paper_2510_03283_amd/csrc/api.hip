@@ -175,6 +175,7 @@ int prepare_weights(const Dims &D, const mace_layer_w_t *w, Bump &ws, bool need_
 struct Saved {
   float *rstd1, *rstd2, *lse, *x1;
   bf16_t *a, *q, *k, *v, *o, *b, *gu;   // gu = [G | U] of the MLP, bf16
+  bf16_t *hm;                           // silu(G) * U rounded to bf16: A operand of the down projection, B operand of dWd
   bf16_t *tq, *to;   // adapter variant: scale * (a [A_q;A_k;A_v]^T) [Tf, 3*64] and scale * (o A_o^T) [Tf, 64]
 };
 constexpr int LR = 64;   // adapter rank as the GEMM sees it (zero-padded)
@@ -185,6 +186,7 @@ Saved plan_saved(const Dims &D, size_t Tf, Bump &s) {
   S.lse = s.take<float>(Tf * D.Hq);
   S.x1 = s.take<float>(Tf * D.d);
   S.gu = s.take<bf16_t>(Tf * 2 * D.F);
+  S.hm = s.take<bf16_t>(Tf * D.F);
   S.a = s.take<bf16_t>(Tf * D.d);
   S.q = s.take<bf16_t>(Tf * D.qd);
   S.k = s.take<bf16_t>(Tf * D.kd);
@@ -203,7 +205,7 @@ struct FwdWs {
   float *qkv_i, *x1_i, *dec_partial;
   // fine-tune rows
   float *qkv_f;
-  bf16_t *a_lo, *q_lo, *k_lo, *v_lo, *o_lo, *b_lo, *hm_hi, *hm_lo;
+  bf16_t *a_lo, *q_lo, *k_lo, *v_lo, *o_lo, *b_lo, *hm_lo;
 };
 FwdWs plan_fwd(const Dims &D, size_t Ti, size_t Tf, int n_decode, int max_ctx, int decode_chunk, Bump &w) {
   FwdWs F;
@@ -224,14 +226,13 @@ FwdWs plan_fwd(const Dims &D, size_t Ti, size_t Tf, int n_decode, int max_ctx, i
   F.v_lo = w.take<bf16_t>(Tf * D.kd);
   F.o_lo = w.take<bf16_t>(Tf * D.qd);
   F.b_lo = w.take<bf16_t>(Tf * D.d);
-  F.hm_hi = w.take<bf16_t>(Tf * D.F);
   F.hm_lo = w.take<bf16_t>(Tf * D.F);
   return F;
 }
 
 // ---------------------------------------------------------------- backward scratch
 struct BwdWs {
-  bf16_t *dy_bf, *dhm, *dgu, *hm, *dx1_bf, *dattn, *dqkv;
+  bf16_t *dy_bf, *dhm, *dgu, *dx1_bf, *dattn, *dqkv;
   float *db, *dx1, *dvec, *da, *dg_part;
   float2 *cs;      // rotary (cos, sin) of every fine-tune row, [Tf, hd/2]
 };
@@ -240,7 +241,6 @@ BwdWs plan_bwd(const Dims &D, size_t Tf, Bump &w) {
   B.dy_bf = w.take<bf16_t>(Tf * D.d);
   B.dhm = w.take<bf16_t>(Tf * D.F);
   B.dgu = w.take<bf16_t>(Tf * 2 * D.F);
-  B.hm = w.take<bf16_t>(Tf * D.F);
   B.db = w.take<float>(Tf * D.d);
   B.dx1 = w.take<float>(Tf * D.d);
   B.dx1_bf = w.take<bf16_t>(Tf * D.d);
@@ -966,7 +966,7 @@ static int layer_fwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
     // (two terms for the fine-tune rows, whose G and U are kept as bf16 for the backward pass)
     GemmParams p = gp_init(D.d, D.d, D.d, D.F);
     p.swiglu = 1; p.out_bf16 = 1;
-    gp_group(p, S.b, F.b_lo, F.hm_hi, nullptr, I.Tf, np_ft);
+    gp_group(p, S.b, F.b_lo, S.hm, nullptr, I.Tf, np_ft);
     if (I.Tf > 0) { p.mg[p.n_mg - 1].c_lo = F.hm_lo; p.mg[p.n_mg - 1].c_gu = S.gu; }
     gp_group(p, F.b_i, nullptr, F.hm_i, nullptr, I.Ti, 1);
     gp_seg(p, W.hi[W_G], W.lo[W_G], D.F, 0);
@@ -976,7 +976,7 @@ static int layer_fwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
   {
     GemmParams p = gp_init(D.F, D.F, D.F, D.d);
     p.resid_kind = 1; p.ldr = D.d;
-    gp_group(p, F.hm_hi, F.hm_lo, y + (size_t)I.Ti * D.d, S.x1, I.Tf, np_ft);
+    gp_group(p, S.hm, F.hm_lo, y + (size_t)I.Ti * D.d, S.x1, I.Tf, np_ft);
     gp_group(p, F.hm_i, nullptr, y, F.x1_i, I.Ti, 1);
     gp_seg(p, W.hi[W_D], W.lo[W_D], D.d, 0);
     TRY(run_gemm(h, 0, 0, p, st, "down gemm"));
@@ -1040,7 +1040,7 @@ static int layer_bwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
 
   prof_mark(h, st, T_MISC);
   HIP_TRY(launch_split_f32(dy_ft, (size_t)Tf * D.d, B.dy_bf, nullptr, st), "cast dy");
-  // MLP: dHm = dY Wd ; SwiGLU backward ; dWd = dY^T Hm
+  // MLP: dHm = dY Wd ; SwiGLU backward ; dWd = dY^T Hm with the Hm the forward kept
   {
     GemmParams p = gp_init(D.d, D.d, D.F, D.F);
     p.out_bf16 = 1;
@@ -1049,12 +1049,12 @@ static int layer_bwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
     TRY(run_gemm(h, 0, 1, p, st, "dhm gemm"));
   }
   prof_mark(h, st, T_SWIGLU);
-  HIP_TRY(launch_swiglu_bwd(B.dhm, S.gu, Tf, D.F, B.dgu, B.hm, st), "swiglu bwd");
+  HIP_TRY(launch_swiglu_bwd(B.dhm, S.gu, Tf, D.F, B.dgu, st), "swiglu bwd");
   if (grads->w_down) {
     GemmParams p = gp_init(Tf, D.d, D.F, D.F);
     p.resid_kind = acc;
     gp_group(p, B.dy_bf, nullptr, grads->w_down, grads->w_down, D.d, 1);
-    gp_seg(p, B.hm, nullptr, D.F, 0);
+    gp_seg(p, S.hm, nullptr, D.F, 0);
     TRY(run_gemm_side(h, 1, 1, p, st, "dWd gemm"));
   }
   // db = dG Wg + dU Wu ; dWg = dG^T b ; dWu = dU^T b

@@ -211,25 +211,33 @@ __global__ __launch_bounds__(64) void rope_table_kernel(const int32_t *__restric
 }
 
 // ------------------------------------------------------------------ SwiGLU
-__global__ __launch_bounds__(256) void swiglu_bwd_kernel(const bf16_t *dhm, const bf16_t *gu, int F, bf16_t *dgu, bf16_t *hm) {
+// 8 hidden units per thread (16-byte accesses); F % 8 == 0.
+__global__ __launch_bounds__(256) void swiglu_bwd_kernel(const bf16_t *__restrict__ dhm, const bf16_t *__restrict__ gu, int F,
+                                                         bf16_t *__restrict__ dgu) {
   const int r = blockIdx.x;
-  const int k = 4 * (blockIdx.y * 256 + threadIdx.x);
+  const int k = 8 * (blockIdx.y * 256 + threadIdx.x);
   if (k >= F) return;
-  float gv[4], uv[4], dh[4], dg[4], du[4], h[4];
-  ld4<true>(gu, (size_t)r * 2 * F + k, gv);
-  ld4<true>(gu, (size_t)r * 2 * F + F + k, uv);
-  ld4<true>(dhm, (size_t)r * F + k, dh);
+  const uint4 gq = *(const uint4 *)(gu + (size_t)r * 2 * F + k), uq = *(const uint4 *)(gu + (size_t)r * 2 * F + F + k);
+  const uint4 dq = *(const uint4 *)(dhm + (size_t)r * F + k);
+  const uint32_t gw[4] = {gq.x, gq.y, gq.z, gq.w}, uw[4] = {uq.x, uq.y, uq.z, uq.w}, dw[4] = {dq.x, dq.y, dq.z, dq.w};
+  uint32_t og[4], ou[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const float sg = 1.0f / (1.0f + expf(-gv[j]));
-    const float si = gv[j] * sg;
-    h[j] = si * uv[j];
-    du[j] = dh[j] * si;
-    dg[j] = dh[j] * uv[j] * sg * (1.0f + gv[j] * (1.0f - sg));
+    float dg[2], du[2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      const float g = e ? __uint_as_float(gw[j] & 0xffff0000u) : __uint_as_float(gw[j] << 16);
+      const float u = e ? __uint_as_float(uw[j] & 0xffff0000u) : __uint_as_float(uw[j] << 16);
+      const float dh = e ? __uint_as_float(dw[j] & 0xffff0000u) : __uint_as_float(dw[j] << 16);
+      const float sg = 1.0f / (1.0f + expf(-g));
+      du[e] = dh * g * sg;
+      dg[e] = dh * u * sg * (1.0f + g * (1.0f - sg));
+    }
+    og[j] = cvt_pk_bf16(dg[0], dg[1]);
+    ou[j] = cvt_pk_bf16(du[0], du[1]);
   }
-  st4_split(dgu, nullptr, (size_t)r * 2 * F + k, dg);
-  st4_split(dgu, nullptr, (size_t)r * 2 * F + F + k, du);
-  st4_split(hm, nullptr, (size_t)r * F + k, h);
+  *(uint4 *)(dgu + (size_t)r * 2 * F + k) = make_uint4(og[0], og[1], og[2], og[3]);
+  *(uint4 *)(dgu + (size_t)r * 2 * F + F + k) = make_uint4(ou[0], ou[1], ou[2], ou[3]);
 }
 
 __global__ __launch_bounds__(256) void split_f32_kernel(const float *src, size_t n, bf16_t *hi, bf16_t *lo) {
@@ -331,9 +339,10 @@ hipError_t launch_rope_table(const int32_t *positions, const double *inv_freq, i
   return hipGetLastError();
 }
 
-hipError_t launch_swiglu_bwd(const bf16_t *dhm, const bf16_t *gu, int rows, int F, bf16_t *dgu, bf16_t *hm, hipStream_t st) {
+hipError_t launch_swiglu_bwd(const bf16_t *dhm, const bf16_t *gu, int rows, int F, bf16_t *dgu, hipStream_t st) {
   if (rows <= 0) return hipSuccess;
-  hipLaunchKernelGGL(swiglu_bwd_kernel, dim3(rows, cdiv(F, 1024)), dim3(256), 0, st, dhm, gu, F, dgu, hm);
+  if (F % 8) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(swiglu_bwd_kernel, dim3(rows, cdiv(F, 2048)), dim3(256), 0, st, dhm, gu, F, dgu);
   return hipGetLastError();
 }
 

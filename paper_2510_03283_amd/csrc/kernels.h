@@ -33,9 +33,9 @@ hipError_t launch_rope_split(const float *qkv, const int32_t *positions, const d
 // cs[r, i] = (cos, sin) of positions[r] * inv_freq[i], i < hd/2 (angle formed and reduced in fp64): the
 // per-row rotary table the attention backward rotates dq and dk back with.
 hipError_t launch_rope_table(const int32_t *positions, const double *inv_freq, int rows, int hd, float2 *cs, hipStream_t st);
-// dU = dhm*silu(G), dG = dhm*U*sig(G)*(1+G*(1-sig(G))) -> dgu bf16 [rows, 2F]; hm (bf16) recomputed.
-// gu bf16 [rows, 2F] (G = columns [0,F), U = [F,2F)) as the gate/up GEMM left it.
-hipError_t launch_swiglu_bwd(const bf16_t *dhm, const bf16_t *gu, int rows, int F, bf16_t *dgu, bf16_t *hm, hipStream_t st);
+// dU = dhm*silu(G), dG = dhm*U*sig(G)*(1+G*(1-sig(G))) -> dgu bf16 [rows, 2F].
+// gu bf16 [rows, 2F] (G = columns [0,F), U = [F,2F)) as the gate/up GEMM left it.  F % 8 == 0.
+hipError_t launch_swiglu_bwd(const bf16_t *dhm, const bf16_t *gu, int rows, int F, bf16_t *dgu, hipStream_t st);
 // fp32 -> (hi, lo) bf16, n elements; lo nullable.
 hipError_t launch_split_f32(const float *src, size_t n, bf16_t *hi, bf16_t *lo, hipStream_t st);
 hipError_t launch_fill_f32(float *dst, size_t n, float v, hipStream_t st);
