@@ -149,6 +149,16 @@ def test_decode_chunk_lengths(torch_mod, chunk, hq, hkv, hd):
     check_iteration(torch_mod, wl, f"decode chunk {chunk} Hq{hq} Hkv{hkv} hd{hd}", options={B.MACE_OPT_DECODE_CHUNK: chunk})
 
 
+@pytest.mark.parametrize("hq,hkv,hd,bs", [(8, 2, 64, 16), (8, 1, 64, 4), (8, 2, 128, 16), (16, 2, 128, 1)])
+def test_grouped_query_decode(torch_mod, hq, hkv, hd, bs):
+    """Four and eight query heads per kv head (one pass over the cache serves the whole group): contexts from
+    the empty one to several chunks, on and around powers of two, several block sizes."""
+    dims = synth.ModelDims(n_q_heads=hq, n_kv_heads=hkv, head_dim=hd, **SMALL)
+    wl = custom_workload("gqa_decode", dims, prefill=[5], decode=[0, 1, 62, 63, 64, 127, 254, 255, 256, 257, 511, 512, 1000, 3000],
+                         n_pairs=1, prompt=3, resp=(2, 9), block_size=bs)
+    check_iteration(torch_mod, wl, f"grouped-query decode Hq{hq} Hkv{hkv} hd{hd} block {bs}")
+
+
 @pytest.mark.parametrize("prefill,decode,pairs", [([], [], 2), ([50, 3], [], 0), ([], [40, 2], 0), ([9], [5], 1)])
 def test_empty_classes(torch_mod, prefill, decode, pairs):
     dims = synth.ModelDims(n_q_heads=4, n_kv_heads=4, head_dim=64, **SMALL)
