@@ -23,15 +23,28 @@ def sources():
     return sorted(f for f in os.listdir(CSRC) if f.endswith(".hip"))
 
 
+# Sources whose generated code is checked after compilation: {source: checker script in csrc/}.  The
+# four-wave GEMM counts its own memory waits, so its build verifies that the compiler kept every register
+# with a load in flight untouched (hipcc -save-temps leaves the gfx950 assembly beside the object).
+ASM_CHECKS = {"gemm.hip": "check_w4_asm.py"}
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(BUILD_DIR, src[:-4] + ".o")
     cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    if src in ASM_CHECKS:
+        cmd.insert(1, "-save-temps=obj")
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{err}")
     if err.strip():
         sys.stderr.write(err + "\n")
+    if src in ASM_CHECKS:
+        asm = os.path.join(BUILD_DIR, src[:-4] + "-hip-amdgcn-amd-amdhsa-gfx950.s")
+        c = subprocess.run([sys.executable, os.path.join(CSRC, ASM_CHECKS[src]), asm], capture_output=True, text=True)
+        if c.returncode != 0:
+            raise RuntimeError(f"generated-code check failed for {src}:\n{c.stdout}{c.stderr}")
     return obj
 
 

@@ -11,6 +11,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <type_traits>
 #include <utility>
 #include <vector>
 
@@ -479,6 +480,8 @@ int count_tiles(GemmParams &p) {
   return mt * nt;
 }
 
+#include "gemm_w4.h"
+
 template <int BM, int BN, int WGM, int WGN, int LA, int LB, int BKT, int NST>
 hipError_t launch_dl(GemmParams &p, hipStream_t stream) {
   const int tiles = count_tiles<BM, BN>(p);
@@ -495,6 +498,22 @@ hipError_t launch_dl(GemmParams &p, hipStream_t stream) {
   }
   p.tile_m = BM; p.tile_n = BN;
   hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, LA, LB, BKT, NST>), dim3((unsigned)tiles, (unsigned)(p.k_splits > 1 ? p.k_splits : 1)), dim3(NTHR), lds, stream, p);
+  return hipGetLastError();
+}
+
+template <int LA, int LB>
+hipError_t launch_w4(GemmParams &p, hipStream_t stream) {
+  const int tiles = count_tiles<256, 256>(p);
+  if (tiles == 0) return hipSuccess;
+  constexpr size_t lds = (size_t)2 * (256 + 256) * BK * sizeof(bf16_t);
+  static DeviceOnce attr_done;
+  if (!attr_done.test()) {
+    hipError_t e = hipFuncSetAttribute((const void *)gemm_bf16_w4_kernel<LA, LB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_done.set();
+  }
+  p.tile_m = 256; p.tile_n = 256;
+  hipLaunchKernelGGL((gemm_bf16_w4_kernel<LA, LB>), dim3((unsigned)tiles, (unsigned)(p.k_splits > 1 ? p.k_splits : 1)), dim3(256), lds, stream, p);
   return hipGetLastError();
 }
 
@@ -538,7 +557,15 @@ hipError_t launch_layout(GemmParams &p, hipStream_t stream) {
   const double c192 = tile_cost<192, 256>(p, 256, 1.0, 0.92);
   const double c128 = tile_cost<128, 128>(p, 512, 2.0, 0.83);
   const int tile = c256 <= c192 && c256 <= c128 ? 1 : (c192 <= c128 ? 2 : 0);
-  if (tile == 1) return launch_dl<256, 256, 2, 4, LA, LB, BK, NSTAGES>(p, stream);
+  if (tile == 1) {
+    // the four-wave kernel where it is the faster one: both operands in the same layout (NT, TN) and a
+    // reduction long enough to pay for its longer start and end of a tile (measured: 8 - 12 % faster at
+    // K >= 4096, up to 14 % slower on the 2048-long reductions of the small configuration)
+    if constexpr (LA == LB) {
+      if (p.K >= 4096 && w4_fits<LA, LB>(p)) return launch_w4<LA, LB>(p, stream);
+    }
+    return launch_dl<256, 256, 2, 4, LA, LB, BK, NSTAGES>(p, stream);
+  }
   if (tile == 2) return launch_dl<192, 256, 2, 4, LA, LB, BK, NSTAGES>(p, stream);
   return launch_dl<128, 128, 2, 2, LA, LB, BK, NSTAGES>(p, stream);
 }
