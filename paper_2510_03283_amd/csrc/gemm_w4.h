@@ -388,38 +388,65 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const GemmParams p) {
       const int F = N;
       bf16_t *const hi = (bf16_t *)Cp, *const lo = (bf16_t *)G.c_lo, *const gu = (bf16_t *)G.c_gu;
       const int f_u = n0 + wn * (WTN / 2);
-      // this lane stores the pair (fc, fc + 1) of row (row + odd): lane parts of the indices
-      const int lane_h = (int)((lrow + (odd ? 1 : 0)) * ldc) + lcol - (odd ? 1 : 0);
-      const int lane_g = (lrow + (odd ? 1 : 0)) * 2 * F + lcol - (odd ? 1 : 0);
+      // Stores of full 128-byte lines.  After the pair swap a lane holds the packed pair (fc, fc + 1) of row
+      // (row + odd) for each of the wave's two unit blocks (jj = 0, 1), in the row half lane / 32 selects.  One
+      // v_permlane32_swap of the two blocks' words gives {lower lanes: block 0, upper lanes: block 1} of
+      // row half 0 in one register and the same of row half 1 in the other: a store then covers 64 units
+      // (128 bytes) of two rows instead of 32 units of four.
+      const int col_l = lane - (odd ? 1 : 0);                      // lane part of the unit index (blocks are 32 apart)
+      const int row_l = odd ? 1 : 0;                               // lane part of the row
+      const int lane_h = (int)(row_l * ldc) + col_l, lane_g = row_l * 2 * F + col_l;
       // KIND 0: only hm (inference rows); 1: hm in two terms and G, U kept (fine-tune rows); 2: decided per element
       auto emit = [&](auto GUARD, auto KIND) W4_INL {
         constexpr bool guard = decltype(GUARD)::value;
         constexpr int kind = decltype(KIND)::value;
         static_for<0, TM>([&](auto I) W4_INL {
-          static_for<0, TN / 2>([&](auto JJ) W4_INL {
-            constexpr int i = decltype(I)::value, jj = decltype(JJ)::value;
-            const int fcu = f_u + jj * 32;
-            static_for<0, 8>([&](auto R2) W4_INL {
-              constexpr int r = 2 * decltype(R2)::value;
-              const int rowu = row_u + i * 32 + 8 * (r >> 2) + (r & 3);
+          constexpr int i = decltype(I)::value;
+          static_for<0, 8>([&](auto R2) W4_INL {
+            constexpr int r = 2 * decltype(R2)::value;
+            const int rowu = row_u + i * 32 + 8 * (r >> 2) + (r & 3);
+            uint32_t wh[2], wl[2], wg[2], wu[2];
+            static_for<0, 2>([&](auto JJ) W4_INL {
+              constexpr int jj = decltype(JJ)::value;
               const float g2[2] = {acc[i][2 * jj][r], acc[i][2 * jj][r + 1]}, u2[2] = {acc[i][2 * jj + 1][r], acc[i][2 * jj + 1][r + 1]};
               float h2[2];
 #pragma unroll
               for (int e = 0; e < 2; ++e) h2[e] = g2[e] * __builtin_amdgcn_rcpf(1.0f + __expf(-g2[e])) * u2[e];
-              const float hp = swap_pair(h2[0], h2[1]), gp = swap_pair(g2[0], g2[1]), up = swap_pair(u2[0], u2[1]);
-              if (!guard || (rowu + lrow + (odd ? 1 : 0) < M && fcu + lcol - (odd ? 1 : 0) < F)) {
-                uint32_t ph, pl;
-                split_pk_bf16(odd ? hp : h2[0], odd ? h2[1] : hp, ph, pl);
-                *(uint32_t *)(hi + (long long)rowu * ldc + fcu + lane_h) = ph;
-                if (kind == 1 || (kind == 2 && lo)) *(uint32_t *)(lo + (long long)rowu * ldc + fcu + lane_h) = pl;
-                if (kind == 1 || (kind == 2 && gu)) {
-                  *(uint32_t *)(gu + (long long)rowu * 2 * F + fcu + lane_g) = cvt_pk_bf16(odd ? gp : g2[0], odd ? g2[1] : gp);
-                  *(uint32_t *)(gu + (long long)rowu * 2 * F + F + fcu + lane_g) = cvt_pk_bf16(odd ? up : u2[0], odd ? u2[1] : up);
-                }
+              const float hp = swap_pair(h2[0], h2[1]);
+              split_pk_bf16(odd ? hp : h2[0], odd ? h2[1] : hp, wh[jj], wl[jj]);
+              if (kind != 0) {
+                const float gp = swap_pair(g2[0], g2[1]), up = swap_pair(u2[0], u2[1]);
+                wg[jj] = cvt_pk_bf16(odd ? gp : g2[0], odd ? g2[1] : gp);
+                wu[jj] = cvt_pk_bf16(odd ? up : u2[0], odd ? u2[1] : up);
               }
             });
-            W4_SB;
+            const u32x2_t sh = __builtin_amdgcn_permlane32_swap(wh[0], wh[1], false, false);
+            const bool okc = !guard || f_u + col_l < F;
+            // row halves: words [0] belong to rows rowu + row_l, words [1] to rows rowu + 4 + row_l
+            static_for<0, 2>([&](auto H) W4_INL {
+              constexpr int hh = decltype(H)::value;
+              if (okc && (!guard || rowu + 4 * hh + row_l < M)) *(uint32_t *)(hi + (long long)(rowu + 4 * hh) * ldc + f_u + lane_h) = sh[hh];
+            });
+            if (kind == 1 || (kind == 2 && lo)) {
+              const u32x2_t sl = __builtin_amdgcn_permlane32_swap(wl[0], wl[1], false, false);
+              static_for<0, 2>([&](auto H) W4_INL {
+                constexpr int hh = decltype(H)::value;
+                if (okc && (!guard || rowu + 4 * hh + row_l < M)) *(uint32_t *)(lo + (long long)(rowu + 4 * hh) * ldc + f_u + lane_h) = sl[hh];
+              });
+            }
+            if (kind == 1 || (kind == 2 && gu)) {
+              const u32x2_t sg = __builtin_amdgcn_permlane32_swap(wg[0], wg[1], false, false);
+              const u32x2_t su = __builtin_amdgcn_permlane32_swap(wu[0], wu[1], false, false);
+              static_for<0, 2>([&](auto H) W4_INL {
+                constexpr int hh = decltype(H)::value;
+                if (okc && (!guard || rowu + 4 * hh + row_l < M)) {
+                  *(uint32_t *)(gu + (long long)(rowu + 4 * hh) * 2 * F + f_u + lane_g) = sg[hh];
+                  *(uint32_t *)(gu + (long long)(rowu + 4 * hh) * 2 * F + F + f_u + lane_g) = su[hh];
+                }
+              });
+            }
           });
+          W4_SB;
         });
       };
       const bool in = m0 + BM <= M && n0 + BN / 2 <= F;
@@ -472,8 +499,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const GemmParams p) {
   // fp32 output (or bf16 with an odd column count).  MODE 0: fp32, no residual.  MODE 1: fp32 + fp32 residual
   // (the output projections, and weight gradients that accumulate): the residuals of eight blocks are
   // requested together before the first is added - with one wave per SIMD nothing else covers the latency of
-  // a request, and block by block a tile would pay it sixteen times.  MODE 2: the remaining combinations,
-  // decided per element.
+  // a request, and block by block a tile would pay it sixteen times (requesting the next four blocks while
+  // four are added and stored measured slower).  MODE 2: the remaining combinations, decided per element.
   auto emit = [&](auto GUARD, auto MODE) W4_INL {
     constexpr bool guard = decltype(GUARD)::value;
     constexpr int mode = decltype(MODE)::value;
