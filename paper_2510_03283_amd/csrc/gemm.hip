@@ -558,12 +558,10 @@ hipError_t launch_layout(GemmParams &p, hipStream_t stream) {
   const double c128 = tile_cost<128, 128>(p, 512, 2.0, 0.83);
   const int tile = c256 <= c192 && c256 <= c128 ? 1 : (c192 <= c128 ? 2 : 0);
   if (tile == 1) {
-    // the four-wave kernel where it is the faster one: both operands in the same layout (NT, TN) and a
-    // reduction long enough to pay for its longer start and end of a tile (measured: 8 - 12 % faster at
-    // K >= 4096, up to 14 % slower on the 2048-long reductions of the small configuration)
-    if constexpr (LA == LB) {
-      if (p.K >= 4096 && w4_fits<LA, LB>(p)) return launch_w4<LA, LB>(p, stream);
-    }
+    // the four-wave kernel where the reduction is long enough to pay for its longer start and end of a tile
+    // (measured: 7 - 12 % faster at K >= 4096, up to 14 % slower on the 2048-long reductions of the small
+    // configuration)
+    if (p.K >= 4096 && w4_fits<LA, LB>(p)) return launch_w4<LA, LB>(p, stream);
     return launch_dl<256, 256, 2, 4, LA, LB, BK, NSTAGES>(p, stream);
   }
   if (tile == 2) return launch_dl<192, 256, 2, 4, LA, LB, BK, NSTAGES>(p, stream);

@@ -467,26 +467,39 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const GemmParams p) {
   const long long c_col0 = c_col + (long long)blockIdx.y * p.c_split_stride;
   if (obf && !(N & 1) && !(c_col & 1)) {
     // packed bf16: neighbouring lanes (columns c, c+1) swap one value of a register pair (rows r, r+1); the
-    // even lane stores columns (c, c+1) of row r, the odd lane columns (c-1, c) of row r+1
-    const int lane_p = (int)((lrow + (odd ? 1 : 0)) * ldc) + lcol - (odd ? 1 : 0);
+    // even lane then holds columns (c, c+1) of row r, the odd lane columns (c-1, c) of row r+1.  The words of
+    // two neighbouring column blocks go through v_permlane32_swap (see the SwiGLU stores): a store covers
+    // 64 columns (128 bytes) of two rows.
+    const int col_l = lane - (odd ? 1 : 0), row_l = odd ? 1 : 0;
+    const int lane_p = (int)(row_l * ldc) + col_l;
     auto emit = [&](auto GUARD) W4_INL {
       constexpr bool guard = decltype(GUARD)::value;
       static_for<0, TM>([&](auto I) W4_INL {
-        static_for<0, TN>([&](auto J) W4_INL {
-          constexpr int i = decltype(I)::value, j = decltype(J)::value;
-          const int colu = col_u + j * 32;
+        static_for<0, TN / 2>([&](auto JP) W4_INL {
+          constexpr int i = decltype(I)::value, jp = decltype(JP)::value;
+          const int colp = col_u + jp * 64;      // first column of the block pair
           static_for<0, 8>([&](auto R2) W4_INL {
             constexpr int r = 2 * decltype(R2)::value;
             const int rowu = row_u + i * 32 + 8 * (r >> 2) + (r & 3);
-            float va = acc[i][j][r], vb = acc[i][j][r + 1];
-            if (rk && (!guard || colu + lcol < N)) {
-              const long long ri = (long long)rowu * ldr + c_col + colu;      // (row, col) and (row + 1, col) of the residual
-              if (!guard || rowu + lrow < M) va += rk == 1 ? ((const float *)Rp)[ri + lane_r] : bf2f(((const bf16_t *)Rp)[ri + lane_r]);
-              if (!guard || rowu + lrow + 1 < M) vb += rk == 1 ? ((const float *)Rp)[ri + ldr + lane_r] : bf2f(((const bf16_t *)Rp)[ri + ldr + lane_r]);
-            }
-            const float vp = swap_pair(va, vb);
-            if (!guard || (rowu + lrow + (odd ? 1 : 0) < M && colu + lcol - (odd ? 1 : 0) < N))
-              *(uint32_t *)((bf16_t *)Cp + (long long)rowu * ldc + c_col + colu + lane_p) = cvt_pk_bf16(odd ? vp : va, odd ? vb : vp);
+            uint32_t w[2];
+            static_for<0, 2>([&](auto JB) W4_INL {
+              constexpr int jb = decltype(JB)::value, j = 2 * jp + jb;
+              const int colu = col_u + j * 32;
+              float va = acc[i][j][r], vb = acc[i][j][r + 1];
+              if (rk && (!guard || colu + lcol < N)) {
+                const long long ri = (long long)rowu * ldr + c_col + colu;      // (row, col) and (row + 1, col) of the residual
+                if (!guard || rowu + lrow < M) va += rk == 1 ? ((const float *)Rp)[ri + lane_r] : bf2f(((const bf16_t *)Rp)[ri + lane_r]);
+                if (!guard || rowu + lrow + 1 < M) vb += rk == 1 ? ((const float *)Rp)[ri + ldr + lane_r] : bf2f(((const bf16_t *)Rp)[ri + ldr + lane_r]);
+              }
+              const float vp = swap_pair(va, vb);
+              w[jb] = cvt_pk_bf16(odd ? vp : va, odd ? vb : vp);
+            });
+            const u32x2_t sw = __builtin_amdgcn_permlane32_swap(w[0], w[1], false, false);
+            static_for<0, 2>([&](auto H) W4_INL {
+              constexpr int hh = decltype(H)::value;      // row half: rows rowu + 4 hh + row_l
+              if (!guard || (rowu + 4 * hh + row_l < M && colp + col_l < N))
+                *(uint32_t *)((bf16_t *)Cp + (long long)(rowu + 4 * hh) * ldc + c_col + colp + lane_p) = sw[hh];
+            });
           });
           W4_SB;
         });
