@@ -71,11 +71,15 @@ __device__ __forceinline__ W4Cur w4_tile_src(int tt, int nk, int kt0, int m0, in
 // The resources of a tile in scalar registers.
 struct W4Src { u32x4_t qa, qb, qu; uint32_t oa, ob; };
 __device__ __forceinline__ uint32_t w4_sgpr(uint32_t x) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)x); }
-__device__ __forceinline__ W4Src w4_resources(const W4Cur c, uint32_t a_bytes) {
+// dead: a request that only keeps the count of loads in flight constant (past the last tile) gets empty
+// resources: its loads return zeros without going to memory.
+__device__ __forceinline__ W4Src w4_resources(const W4Cur c, uint32_t a_bytes, bool dead = false) {
   W4Src r;
+  a_bytes = dead ? 0u : a_bytes;
+  const uint32_t b_bytes = dead ? 0u : c.b_bytes;
   r.qa = u32x4_t{w4_sgpr(c.a0), w4_sgpr(c.a1), w4_sgpr(a_bytes), 0x00020000u};
-  r.qb = u32x4_t{w4_sgpr(c.b0), w4_sgpr(c.b1), w4_sgpr(c.b_bytes), 0x00020000u};
-  r.qu = u32x4_t{w4_sgpr(c.u0), w4_sgpr(c.u1), w4_sgpr(c.b_bytes), 0x00020000u};
+  r.qb = u32x4_t{w4_sgpr(c.b0), w4_sgpr(c.b1), w4_sgpr(b_bytes), 0x00020000u};
+  r.qu = u32x4_t{w4_sgpr(c.u0), w4_sgpr(c.u1), w4_sgpr(b_bytes), 0x00020000u};
   r.oa = c.oa;
   r.ob = c.ob;
   return r;
@@ -270,7 +274,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const GemmParams p) {
       const Src s0 = tile_src(0);
       static_for<0, 2 * NL>([&](auto X) W4_INL { request(W4_IC(1), X, s0); });
       W4_SB;
-      const Src s1 = tile_src(min(1, n_it - 1));
+      const Src s1 = w4_resources(tile_cur(min(1, n_it - 1)), a_bytes, n_it < 2);
       static_for<0, 2 * NL>([&](auto X) W4_INL { request(W4_IC(0), X, s1); });
       W4_SB;
       wait_vmcnt<2 * NL>();      // tile 0 is in
@@ -279,7 +283,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const GemmParams p) {
       W4_SB;
       rq_tt = min(2, n_it - 1);
       rq = tile_cur(rq_tt);
-      const Src s2 = w4_resources(rq, a_bytes);
+      const Src s2 = w4_resources(rq, a_bytes, n_it < 3);
       static_for<0, 2 * NL>([&](auto X) W4_INL { request(W4_IC(1), X, s2); });
       W4_SB;
       __syncthreads();
@@ -295,6 +299,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const GemmParams p) {
       constexpr bool tail = decltype(TAIL)::value;
       // the next request: tile t + 3, or the last tile again.  Only a change of pass or of k segment takes
       // the full computation.
+      bool dead = false;
+      if (!tail && rq_tt >= n_it - 1) dead = true;
       if (!tail && rq_tt < n_it - 1) {
         ++rq_tt;
         const int kq = (kt0 + rq_tt) * BKT;      // (k segments exclude passes)
@@ -305,7 +311,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const GemmParams p) {
           rq.ob += stepB;
         }
       }
-      const Src src = w4_resources(rq, a_bytes);
+      const Src src = w4_resources(rq, a_bytes, dead);
       // (the tiles behind the loop request nothing: what they would request lies past the last tile, and a
       // load still in flight when control leaves this code could land in a register that holds something else
       // by then; the last of them moves nothing either)
@@ -321,7 +327,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const GemmParams p) {
         }
       };
       // k steps 0..2: one fragment of the next step behind each of the first eight MFMAs, one move behind
-      // each of the next six (16 moves over the three steps)
+      // each of the next six (16 moves over the three steps).  (One heavy instruction behind every MFMA - all
+      // ds_writes first, the requests behind them, the last eight in k step 3 - makes long reductions 1 - 2 %
+      // faster and the first k tiles of every output tile slower: 3 - 5 % slower over the whole step.)
       static_for<0, 3>([&](auto KK) W4_INL {
         constexpr int kk = decltype(KK)::value;
         static_for<0, 16>([&](auto Q) W4_INL {
