@@ -42,7 +42,8 @@ HEADLINE = "7b_ft"
 BIG = ("7b", "7b_decode", "7b_ft")          # cached contexts drawn on the GPU; oracle timed on a sub-batch
 HBM_CLASSES = ("attn_decode", "logsoftmax", "dlogits")      # streamed once from HBM; the other timed classes are contractions
 # kernel class -> the source file whose hash a counter summary must carry to be quoted
-CLASS_SOURCE = {"gemm_nt": "gemm.hip", "gemm_nn": "gemm.hip", "gemm_tn": "gemm.hip", "attn_decode": "attn_decode.hip",
+GEMM_SRC = "gemm.hip+gemm_w4.h"      # several files: the hash is taken over their concatenation
+CLASS_SOURCE = {"gemm_nt": GEMM_SRC, "gemm_nn": GEMM_SRC, "gemm_tn": GEMM_SRC, "attn_decode": "attn_decode.hip",
                 "attn_fwd_prefill": "attn_fwd.hip", "attn_fwd_ft": "attn_fwd.hip", "attn_bwd": "attn_bwd.hip",
                 "logsoftmax": "dpo_head.hip", "dlogits": "dpo_head.hip"}
 
@@ -61,7 +62,7 @@ def traffic_from_profiles(workload, kernel):
     mh = re.search(r"kernel_source_sha256:\s*([0-9a-f]{64})", text)
     if not mt or not mh:
         return None, f"{path}: summary carries no traffic_bytes_per_launch / kernel_source_sha256 line"
-    now = hashlib.sha256(open(os.path.join(ROOT, "paper_2510_03283_amd", "csrc", src), "rb").read()).hexdigest()
+    now = hashlib.sha256(b"".join(open(os.path.join(ROOT, "paper_2510_03283_amd", "csrc", f), "rb").read() for f in src.split("+"))).hexdigest()
     if now != mh.group(1):
         return None, f"{path}: measured on another version of {src} (sha256 {mh.group(1)[:12]}.., now {now[:12]}..)"
     return float(mt.group(1)), f"{path} (csrc/{src} sha256 {now[:12]}..)"
