@@ -85,6 +85,16 @@ __device__ __forceinline__ W4Src w4_resources(const W4Cur c, uint32_t a_bytes, b
   return r;
 }
 
+// An accumulator element for the epilogue, read where it lives.  The accumulators stay in AGPRs from the loop to
+// the end of the kernel; handed over as plain values, the register allocator copies whole 16-register blocks into
+// VGPRs at the end of the loop for all epilogue variants at once, spills what does not fit and reloads a block
+// per element between the stores (every reload a wait that drains the stores in flight).
+__device__ __forceinline__ float w4_acc_rd(float a) {
+  float v;
+  asm("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
+  return v;
+}
+
 template <int LA, int LB>
 __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const GemmParams p) {
   constexpr int BM = 256, BN = 256, BKT = 64, NTHR = 256, WGN = 2, WTM = 128, WTN = 128, TM = 4, TN = 4;
@@ -372,20 +382,35 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const GemmParams p) {
   }
 
   // Epilogue.  Accumulator register r of block (i, j) holds row 8 (r / 4) + 4 (lane / 32) + r % 4 and column
-  // lane % 32 of the 32x32 block.  An element's index is split into a part that is uniform over the wave (tile,
-  // wave, block, register: scalar arithmetic, one uniform row pointer per register) and a small lane part
-  // (one vector register for all stores).  Interior tiles store without per-element checks: every store
-  // loop exists twice (GUARD).
+  // lane % 32 of the 32x32 block.  Every access is a buffer instruction on a view of the wave's part of the
+  // matrix (from its first row and column on, as many bytes as its existing rows take): the address is
+  // "view + uniform row offset + lane offset".  The row offset is one scalar that walks down the rows (from one
+  // register to the next the row index grows by 1, 1, 1, 5; by 2, 6 where registers are handled in pairs), the
+  // lane offset one register per column block, and that is all the address arithmetic there is.  Edges need no
+  // code: an access to a row past the last is out of the view's range, which the hardware drops (a load
+  // returns zero), a lane whose column does not exist carries an offset beyond any view, and an output that was
+  // not asked for is an empty view.
   // (no lambda below may name p, G or S: captured by reference the kernel arguments are copied to private memory)
+  // (the reads of the accumulators are asm, which the compiler's hazard handling does not look into: the wait
+  // states between the last MFMA and the first read of its result are given here)
+  asm volatile("s_nop 15\n\ts_nop 15");
+  W4_SB;
   const int rk = p.resid_kind, obf = p.out_bf16;
   void *const Cp = G.c;
   const void *const Rp = G.resid;
   const int c_col = S.c_col;
   const long long ldc = p.ldc, ldr = p.ldr;
   const bool odd = lane & 1;
-  const int row_u = m0 + wm * WTM, lrow = 4 * (lane >> 5);          // uniform and lane part of the row of (i = 0, r = 0)
-  const int lcol = lane & 31;
-  const int lane_c = (int)(lrow * ldc) + lcol, lane_r = (int)(lrow * ldr) + lcol;      // lane part of an element index in C / residual
+  const int row_u = m0 + wm * WTM;                                  // the wave's first row
+  const int rows_v = max(0, min(WTM, M - row_u));                   // how many of its rows exist
+  const int lrow = 4 * (lane >> 5), lcol = lane & 31;
+  constexpr uint32_t OUT = 0x80000000u;                             // lane offset of a column that does not exist
+  auto view = [](const void *base, long long bytes) W4_INL {
+    return __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, (int)bytes, 0x00020000);
+  };
+  auto store32 = [](uint32_t w, __amdgpu_buffer_rsrc_t q, uint32_t voff, uint32_t soff) W4_INL {
+    __builtin_amdgcn_raw_buffer_store_b32(w, q, (int)voff, (int)soff, 0);
+  };
   auto swap_pair = [&](float mine_r, float mine_r1) W4_INL -> float {     // the partner's value for the row this lane stores
     const float send = odd ? mine_r : mine_r1;
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(send), 0xB1, 0xF, 0xF, true));
@@ -403,182 +428,165 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const GemmParams p) {
       // (128 bytes) of two rows instead of 32 units of four.
       const int col_l = lane - (odd ? 1 : 0);                      // lane part of the unit index (blocks are 32 apart)
       const int row_l = odd ? 1 : 0;                               // lane part of the row
-      const int lane_h = (int)(row_l * ldc) + col_l, lane_g = row_l * 2 * F + col_l;
-      // KIND 0: only hm (inference rows); 1: hm in two terms and G, U kept (fine-tune rows); 2: decided per element
-      auto emit = [&](auto GUARD, auto KIND) W4_INL {
-        constexpr bool guard = decltype(GUARD)::value;
+      const bool okc = f_u + col_l < F;
+      // lane offsets for row half 0 and (four rows on) row half 1; U lies F units behind G
+      uint32_t vh[2], vg[2], vu[2];
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+        vh[hh] = okc ? (uint32_t)((int)((row_l + 4 * hh) * ldc) + col_l) * 2u : OUT;
+        vg[hh] = okc ? (uint32_t)((row_l + 4 * hh) * 2 * F + col_l) * 2u : OUT;
+        vu[hh] = okc ? vg[hh] + (uint32_t)F * 2u : OUT;
+      }
+      const auto qh = view(hi + (long long)row_u * ldc + f_u, rows_v * ldc * 2);
+      const auto ql = view(lo + (long long)row_u * ldc + f_u, lo ? rows_v * ldc * 2 : 0);
+      const auto qg = view(gu + (long long)row_u * 2 * F + f_u, gu ? (long long)rows_v * F * 4 : 0);
+      // (row strides go through w4_sgpr: a stride that shares a subexpression with a lane offset is otherwise
+      // computed in vector registers, and a vector register as the scalar offset of a buffer instruction
+      // becomes a loop over its distinct values)
+      const uint32_t h2r = w4_sgpr((uint32_t)(ldc * 4)), h6r = w4_sgpr((uint32_t)(ldc * 12)), g2r = w4_sgpr((uint32_t)F * 8u), g6r = w4_sgpr((uint32_t)F * 24u);      // 2 and 6 rows
+      // KIND 0: only hm (inference rows); 1: hm in two terms and G, U kept (fine-tune rows)
+      auto emit = [&](auto KIND) W4_INL {
         constexpr int kind = decltype(KIND)::value;
+        uint32_t sh = 0, sg = 0;      // row offsets in hm (both terms) and in G|U
         static_for<0, TM>([&](auto I) W4_INL {
           constexpr int i = decltype(I)::value;
           static_for<0, 8>([&](auto R2) W4_INL {
             constexpr int r = 2 * decltype(R2)::value;
-            const int rowu = row_u + i * 32 + 8 * (r >> 2) + (r & 3);
             uint32_t wh[2], wl[2], wg[2], wu[2];
             static_for<0, 2>([&](auto JJ) W4_INL {
               constexpr int jj = decltype(JJ)::value;
-              const float g2[2] = {acc[i][2 * jj][r], acc[i][2 * jj][r + 1]}, u2[2] = {acc[i][2 * jj + 1][r], acc[i][2 * jj + 1][r + 1]};
+              const float g2[2] = {w4_acc_rd(acc[i][2 * jj][r]), w4_acc_rd(acc[i][2 * jj][r + 1])};
+              const float u2[2] = {w4_acc_rd(acc[i][2 * jj + 1][r]), w4_acc_rd(acc[i][2 * jj + 1][r + 1])};
               float h2[2];
 #pragma unroll
               for (int e = 0; e < 2; ++e) h2[e] = g2[e] * __builtin_amdgcn_rcpf(1.0f + __expf(-g2[e])) * u2[e];
               const float hp = swap_pair(h2[0], h2[1]);
               split_pk_bf16(odd ? hp : h2[0], odd ? h2[1] : hp, wh[jj], wl[jj]);
-              if (kind != 0) {
+              if constexpr (kind != 0) {
                 const float gp = swap_pair(g2[0], g2[1]), up = swap_pair(u2[0], u2[1]);
                 wg[jj] = cvt_pk_bf16(odd ? gp : g2[0], odd ? g2[1] : gp);
                 wu[jj] = cvt_pk_bf16(odd ? up : u2[0], odd ? u2[1] : up);
               }
             });
-            const u32x2_t sh = __builtin_amdgcn_permlane32_swap(wh[0], wh[1], false, false);
-            const bool okc = !guard || f_u + col_l < F;
-            // row halves: words [0] belong to rows rowu + row_l, words [1] to rows rowu + 4 + row_l
-            static_for<0, 2>([&](auto H) W4_INL {
-              constexpr int hh = decltype(H)::value;
-              if (okc && (!guard || rowu + 4 * hh + row_l < M)) *(uint32_t *)(hi + (long long)(rowu + 4 * hh) * ldc + f_u + lane_h) = sh[hh];
-            });
-            if (kind == 1 || (kind == 2 && lo)) {
-              const u32x2_t sl = __builtin_amdgcn_permlane32_swap(wl[0], wl[1], false, false);
+            // row halves: words [0] belong to rows (row + row_l), words [1] to the rows four further on
+            const u32x2_t s_h = __builtin_amdgcn_permlane32_swap(wh[0], wh[1], false, false);
+            static_for<0, 2>([&](auto H) W4_INL { store32(s_h[decltype(H)::value], qh, vh[decltype(H)::value], sh); });
+            if constexpr (kind != 0) {
+              const u32x2_t s_l = __builtin_amdgcn_permlane32_swap(wl[0], wl[1], false, false);
+              const u32x2_t s_g = __builtin_amdgcn_permlane32_swap(wg[0], wg[1], false, false);
+              const u32x2_t s_u = __builtin_amdgcn_permlane32_swap(wu[0], wu[1], false, false);
               static_for<0, 2>([&](auto H) W4_INL {
                 constexpr int hh = decltype(H)::value;
-                if (okc && (!guard || rowu + 4 * hh + row_l < M)) *(uint32_t *)(lo + (long long)(rowu + 4 * hh) * ldc + f_u + lane_h) = sl[hh];
+                store32(s_l[hh], ql, vh[hh], sh);
+                store32(s_g[hh], qg, vg[hh], sg);
+                store32(s_u[hh], qg, vu[hh], sg);
               });
             }
-            if (kind == 1 || (kind == 2 && gu)) {
-              const u32x2_t sg = __builtin_amdgcn_permlane32_swap(wg[0], wg[1], false, false);
-              const u32x2_t su = __builtin_amdgcn_permlane32_swap(wu[0], wu[1], false, false);
-              static_for<0, 2>([&](auto H) W4_INL {
-                constexpr int hh = decltype(H)::value;
-                if (okc && (!guard || rowu + 4 * hh + row_l < M)) {
-                  *(uint32_t *)(gu + (long long)(rowu + 4 * hh) * 2 * F + f_u + lane_g) = sg[hh];
-                  *(uint32_t *)(gu + (long long)(rowu + 4 * hh) * 2 * F + F + f_u + lane_g) = su[hh];
-                }
-              });
-            }
+            sh += (r & 2) ? h6r : h2r;
+            sg += (r & 2) ? g6r : g2r;
           });
           W4_SB;
         });
       };
-      const bool in = m0 + BM <= M && n0 + BN / 2 <= F;
-      if (!lo && !gu) {
-        if (in) emit(std::false_type{}, W4_IC(0));
-        else emit(std::true_type{}, W4_IC(0));
-      } else if (lo && gu) {
-        if (in) emit(std::false_type{}, W4_IC(1));
-        else emit(std::true_type{}, W4_IC(1));
-      } else {
-        emit(std::true_type{}, W4_IC(2));
-      }
+      if (!lo && !gu) emit(W4_IC(0));
+      else emit(W4_IC(1));
     }
     return;
   }
-  const bool interior = m0 + BM <= M && n0 + BN <= N;
-  const int col_u = n0 + wn * WTN;                                  // uniform part of the column of j = 0
+  const int col_u = n0 + wn * WTN;                                  // the wave's first column
   const long long c_col0 = c_col + (long long)blockIdx.y * p.c_split_stride;
-  if (obf && !(N & 1) && !(c_col & 1)) {
-    // packed bf16: neighbouring lanes (columns c, c+1) swap one value of a register pair (rows r, r+1); the
-    // even lane then holds columns (c, c+1) of row r, the odd lane columns (c-1, c) of row r+1.  The words of
-    // two neighbouring column blocks go through v_permlane32_swap (see the SwiGLU stores): a store covers
-    // 64 columns (128 bytes) of two rows.
+  if (obf) {
+    // packed bf16 (even column count and offset, no residual): neighbouring lanes (columns c, c+1) swap one
+    // value of a register pair (rows r, r+1); the even lane then holds columns (c, c+1) of row r, the odd lane
+    // columns (c-1, c) of row r+1.  The words of two neighbouring column blocks go through v_permlane32_swap
+    // (see the SwiGLU stores): a store covers 64 columns (128 bytes) of two rows.
     const int col_l = lane - (odd ? 1 : 0), row_l = odd ? 1 : 0;
-    const int lane_p = (int)(row_l * ldc) + col_l;
-    auto emit = [&](auto GUARD) W4_INL {
-      constexpr bool guard = decltype(GUARD)::value;
-      static_for<0, TM>([&](auto I) W4_INL {
+    uint32_t vp[2][TN / 2];      // lane offsets by row half and block pair
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+      for (int jp = 0; jp < TN / 2; ++jp)
+        vp[hh][jp] = col_u + jp * 64 + col_l < N ? (uint32_t)((int)((row_l + 4 * hh) * ldc) + col_l + jp * 64) * 2u : OUT;
+    const auto qc = view((bf16_t *)Cp + (long long)row_u * ldc + c_col + col_u, rows_v * ldc * 2);
+    const uint32_t p2r = w4_sgpr((uint32_t)(ldc * 4)), p6r = w4_sgpr((uint32_t)(ldc * 12));      // 2 and 6 rows
+    uint32_t sc = 0;
+    static_for<0, TM>([&](auto I) W4_INL {
+      static_for<0, 8>([&](auto R2) W4_INL {
+        constexpr int i = decltype(I)::value, r = 2 * decltype(R2)::value;
         static_for<0, TN / 2>([&](auto JP) W4_INL {
-          constexpr int i = decltype(I)::value, jp = decltype(JP)::value;
-          const int colp = col_u + jp * 64;      // first column of the block pair
-          static_for<0, 8>([&](auto R2) W4_INL {
-            constexpr int r = 2 * decltype(R2)::value;
-            const int rowu = row_u + i * 32 + 8 * (r >> 2) + (r & 3);
-            uint32_t w[2];
-            static_for<0, 2>([&](auto JB) W4_INL {
-              constexpr int jb = decltype(JB)::value, j = 2 * jp + jb;
-              const int colu = col_u + j * 32;
-              float va = acc[i][j][r], vb = acc[i][j][r + 1];
-              if (rk && (!guard || colu + lcol < N)) {
-                const long long ri = (long long)rowu * ldr + c_col + colu;      // (row, col) and (row + 1, col) of the residual
-                if (!guard || rowu + lrow < M) va += rk == 1 ? ((const float *)Rp)[ri + lane_r] : bf2f(((const bf16_t *)Rp)[ri + lane_r]);
-                if (!guard || rowu + lrow + 1 < M) vb += rk == 1 ? ((const float *)Rp)[ri + ldr + lane_r] : bf2f(((const bf16_t *)Rp)[ri + ldr + lane_r]);
-              }
-              const float vp = swap_pair(va, vb);
-              w[jb] = cvt_pk_bf16(odd ? vp : va, odd ? vb : vp);
-            });
-            const u32x2_t sw = __builtin_amdgcn_permlane32_swap(w[0], w[1], false, false);
-            static_for<0, 2>([&](auto H) W4_INL {
-              constexpr int hh = decltype(H)::value;      // row half: rows rowu + 4 hh + row_l
-              if (!guard || (rowu + 4 * hh + row_l < M && colp + col_l < N))
-                *(uint32_t *)((bf16_t *)Cp + (long long)(rowu + 4 * hh) * ldc + c_col + colp + lane_p) = sw[hh];
-            });
+          constexpr int jp = decltype(JP)::value;
+          uint32_t w[2];
+          static_for<0, 2>([&](auto JB) W4_INL {
+            constexpr int jb = decltype(JB)::value, j = 2 * jp + jb;
+            const float va = w4_acc_rd(acc[i][j][r]), vb = w4_acc_rd(acc[i][j][r + 1]);
+            const float vx = swap_pair(va, vb);
+            w[jb] = cvt_pk_bf16(odd ? vx : va, odd ? vb : vx);
           });
-          W4_SB;
+          const u32x2_t sw = __builtin_amdgcn_permlane32_swap(w[0], w[1], false, false);
+          static_for<0, 2>([&](auto H) W4_INL { store32(sw[decltype(H)::value], qc, vp[decltype(H)::value][jp], sc); });
         });
+        sc += (r & 2) ? p6r : p2r;
       });
-    };
-    if (interior) emit(std::false_type{});
-    else emit(std::true_type{});
+      W4_SB;
+    });
     return;
   }
-  // fp32 output (or bf16 with an odd column count).  MODE 0: fp32, no residual.  MODE 1: fp32 + fp32 residual
-  // (the output projections, and weight gradients that accumulate): the residuals of eight blocks are
-  // requested together before the first is added - with one wave per SIMD nothing else covers the latency of
-  // a request, and block by block a tile would pay it sixteen times (requesting the next four blocks while
-  // four are added and stored measured slower).  MODE 2: the remaining combinations, decided per element.
-  auto emit = [&](auto GUARD, auto MODE) W4_INL {
-    constexpr bool guard = decltype(GUARD)::value;
-    constexpr int mode = decltype(MODE)::value;
+  // fp32 output; RES 0: no residual, 1: + fp32 residual (projections onto an fp32 stream, weight gradients that
+  // accumulate), 2: + bf16 residual.  The residuals of eight blocks are requested together before the first is
+  // added: with one wave per SIMD nothing else covers the latency of a request.
+  auto emit = [&](auto RES) W4_INL {
+    constexpr int res = decltype(RES)::value, rsz = res == 2 ? 2 : 4;
+    uint32_t vc[TN], vr[TN];      // lane offsets by column block, in C and in the residual
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const bool ok = col_u + j * 32 + lcol < N;
+      vc[j] = ok ? (uint32_t)((int)(lrow * ldc) + lcol + j * 32) * 4u : OUT;
+      vr[j] = ok ? (uint32_t)((int)(lrow * ldr) + lcol + j * 32) * (uint32_t)rsz : OUT;
+    }
+    const auto qc = view((char *)Cp + ((long long)row_u * ldc + c_col0 + col_u) * 4, rows_v * ldc * 4);
+    const auto qr = view((const char *)Rp + ((long long)row_u * ldr + c_col0 + col_u) * rsz, res ? rows_v * ldr * rsz : 0);
+    const uint32_t c1 = w4_sgpr((uint32_t)(ldc * 4)), c5 = w4_sgpr((uint32_t)(ldc * 20)), c64 = w4_sgpr((uint32_t)(ldc * 256));
+    const uint32_t r1 = w4_sgpr((uint32_t)(ldr * rsz)), r5 = w4_sgpr((uint32_t)(ldr * (5 * rsz))), r64 = w4_sgpr((uint32_t)(ldr * (64 * rsz)));
+    uint32_t sc = 0, sr = 0;      // row offsets of the current 64-row half
     static_for<0, TM / 2>([&](auto IH) W4_INL {
       constexpr int ih = decltype(IH)::value;
-      float res[2 * TN][16];
-      if constexpr (mode == 1) {
-        static_for<0, 2 * TN>([&](auto B) W4_INL {
-          constexpr int i = 2 * ih + decltype(B)::value / TN, j = decltype(B)::value % TN;
-          const int colu = col_u + j * 32;
-          static_for<0, 16>([&](auto R) W4_INL {
-            constexpr int r = decltype(R)::value;
-            const int rowu = row_u + i * 32 + 8 * (r >> 2) + (r & 3);
-            res[decltype(B)::value][r] = (!guard || (colu + lcol < N && rowu + lrow < M)) ? ((const float *)Rp)[(long long)rowu * ldr + c_col0 + colu + lane_r] : 0.f;
+      float rv[2][16][TN];
+      if constexpr (res != 0) {
+        static_for<0, TN>([&](auto J) W4_INL {
+          constexpr int j = decltype(J)::value;
+          uint32_t q = sr;
+          static_for<0, 32>([&](auto IR) W4_INL {
+            constexpr int ii = decltype(IR)::value / 16, r = decltype(IR)::value % 16;
+            if constexpr (res == 1) rv[ii][r][j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(qr, (int)vr[j], (int)q, 0));
+            else rv[ii][r][j] = bf2f(__builtin_amdgcn_raw_buffer_load_b16(qr, (int)vr[j], (int)q, 0));
+            q += (r & 3) == 3 ? r5 : r1;
           });
         });
+        sr += r64;
         W4_SB;
       }
-      static_for<0, 2 * TN>([&](auto B) W4_INL {
-        constexpr int i = 2 * ih + decltype(B)::value / TN, j = decltype(B)::value % TN;
-        const int colu = col_u + j * 32;
-        if (!guard || colu + lcol < N) {
-          static_for<0, 16>([&](auto R) W4_INL {
-            constexpr int r = decltype(R)::value;
-            const int rowu = row_u + i * 32 + 8 * (r >> 2) + (r & 3);
-            if (!guard || rowu + lrow < M) {
-              float v = acc[i][j][r];
-              if constexpr (mode == 0) {
-                ((float *)Cp)[(long long)rowu * ldc + c_col0 + colu + lane_c] = v;
-              } else if constexpr (mode == 1) {
-                ((float *)Cp)[(long long)rowu * ldc + c_col0 + colu + lane_c] = v + res[decltype(B)::value][r];
-              } else {
-                if (rk == 1) v += ((const float *)Rp)[(long long)rowu * ldr + c_col0 + colu + lane_r];
-                else if (rk == 2) v += bf2f(((const bf16_t *)Rp)[(long long)rowu * ldr + c_col0 + colu + lane_r]);
-                if (obf) ((bf16_t *)Cp)[(long long)rowu * ldc + c_col0 + colu + lane_c] = f2bf(v);
-                else ((float *)Cp)[(long long)rowu * ldc + c_col0 + colu + lane_c] = v;
-              }
-            }
-          });
-        }
+      static_for<0, TN>([&](auto J) W4_INL {
+        constexpr int j = decltype(J)::value;
+        uint32_t q = sc;
+        static_for<0, 32>([&](auto IR) W4_INL {
+          constexpr int ii = decltype(IR)::value / 16, r = decltype(IR)::value % 16, i = 2 * ih + ii;
+          float v = w4_acc_rd(acc[i][j][r]);
+          if constexpr (res != 0) v += rv[ii][r][j];
+          store32(__builtin_bit_cast(uint32_t, v), qc, vc[j], q);
+          q += (r & 3) == 3 ? c5 : c1;
+        });
         W4_SB;
       });
+      sc += c64;
     });
   };
-  if (!obf && rk == 0) {
-    if (interior) emit(std::false_type{}, W4_IC(0));
-    else emit(std::true_type{}, W4_IC(0));
-  } else if (!obf && rk == 1) {
-    if (interior) emit(std::false_type{}, W4_IC(1));
-    else emit(std::true_type{}, W4_IC(1));
-  } else {
-    if (interior) emit(std::false_type{}, W4_IC(2));
-    else emit(std::true_type{}, W4_IC(2));
-  }
+  if (rk == 0) emit(W4_IC(0));
+  else if (rk == 1) emit(W4_IC(1));
+  else emit(W4_IC(2));
 }
 
-// Operand views must fit the 32-bit byte offsets of a buffer load.
+// Operand views must fit the 32-bit byte offsets of a buffer load, and 128 rows of an output or residual the
+// 31 bits of an offset inside a wave's view.  bf16 output is stored in column pairs and takes no residual here.
 template <int LA, int LB>
 bool w4_fits(const GemmParams &p) {
   const long long lim = (1ll << 32) - 65536;
@@ -589,6 +597,10 @@ bool w4_fits(const GemmParams &p) {
   for (int s = 0; s < p.n_ns; ++s) {
     const long long rows = LB == 0 ? p.ns[s].N : p.K;
     if (rows * p.ldb * 2 >= lim) return false;
+    if (p.out_bf16 && !p.swiglu && ((p.ns[s].N & 1) || (p.ns[s].c_col & 1))) return false;
+    if (p.swiglu && (p.ns[s].N & 1)) return false;
   }
+  if (p.out_bf16 && !p.swiglu && p.resid_kind != 0) return false;
+  if (p.ldc >= (1ll << 21) || p.ldr >= (1ll << 21)) return false;
   return true;
 }
