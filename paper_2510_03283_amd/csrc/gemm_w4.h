@@ -275,6 +275,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const GemmParams p) {
     }
     return;
   }
+  const int n_run = max(n_it, 3);      // tile times: at least one turn of the loop and one tile behind it
   int rq_tt;      // the tile requested last, and where it comes from
   W4Cur rq;
   {
@@ -361,24 +362,24 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const GemmParams p) {
       // may copy or spill what is live there.  So the loop's last iteration ends with a wait for all loads (the
       // pipeline runs empty once per output tile), and the code behind the loop issues none.
       if constexpr (!tail && ph == 1) {
-        if (t + 3 >= n_it) {
+        if (t + 3 >= n_run) {
           wait_vmcnt<0>();
           W4_SB;
         }
       }
     };
-    // the loop proper has no exit but its back edge; the last one or two tiles run behind it
+    // The loop proper has no exit but its back edge; the last one or two tiles run behind it.  It always runs at
+    // least once: a reduction of one or two tiles is padded with empty tiles (zeros, requested from empty
+    // resources).  With a way around the loop the accumulators reach the code behind it in two register
+    // assignments, and the loop's exit pays for the difference with a permutation of all of them.
     int t = 0;
-    if (n_it <= 2) {
-      wait_vmcnt<0>();
-      W4_SB;
-    }
-    for (; t + 2 < n_it; t += 2) {
+    do {
       phase(W4_IC(0), std::false_type{}, t);
       phase(W4_IC(1), std::false_type{}, t + 1);
-    }
+      t += 2;
+    } while (t + 2 < n_run);
     phase(W4_IC(0), std::true_type{}, t);
-    if (t + 1 < n_it) phase(W4_IC(1), std::true_type{}, t + 1);
+    if (t + 1 < n_run) phase(W4_IC(1), std::true_type{}, t + 1);
   }
 
   // Epilogue.  Accumulator register r of block (i, j) holds row 8 (r / 4) + 4 (lane / 32) + r % 4 and column
