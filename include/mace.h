@@ -370,6 +370,32 @@ typedef struct {
 } mace_gemm_plan_t;
 int mace_launch_plan(mace_handle_t h, mace_gemm_plan_t *out, int32_t max_entries, int32_t *n_out);
 
+/* The dense contraction kernel on its own (for kernel-level tests and benchmarks; every product of the
+ * iteration of Section 2.1 / Fig. 4 goes through the same launcher with the same operand forms).
+ *   C[m, n] = sum_k A[m, k] B[n, k]  (+ sum_k A_lo[m, k] B[n, k])  (+ R[m, n])
+ * A, A_lo, B: device bf16.  layout_a = 0: A is [M, K] row-major, 1: [K, M] row-major; layout_b = 0: B is [N, K]
+ * row-major, 1: [K, N] row-major (supported pairs: (0,0), (0,1), (1,1)); lda, ldb, ldc, ldr in elements.  a_lo
+ * (nullable) is the second bf16 term of A: given, the product takes two passes.  C: device, fp32 (out_bf16 = 0)
+ * or bf16 (1), [M, N] with row stride ldc.  R (nullable): device fp32 (resid_kind = 1) or bf16 (2), row stride ldr.
+ * swiglu = 1 (layouts (0,0) only): b holds the gate rows and b_up the up rows of N hidden units, and instead of
+ * the products G and U the call writes hm = silu(G) * U as bf16 into c ([M, N], ldc), its second bf16 term
+ * into c_lo (nullable) and G | U as bf16 [M, 2N] into c_gu (nullable).
+ * kernel = 0: the launcher picks tile and kernel from the sizes as it does inside the iteration; 1: the 256x256
+ * four-wave kernel (MACE_BAD_SHAPE where the problem does not fit it).
+ * Requirements: K a multiple of 64 for a k-contiguous operand; M (N) a multiple of 8 for an m- (n-) contiguous
+ * one; leading dimensions multiples of 8; pointers 16-byte aligned.  Nothing is allocated; the call is
+ * asynchronous on `stream`.  Errors: MACE_INVALID_ARG (null pointers), MACE_BAD_SHAPE (the requirements). */
+typedef struct {
+  int32_t layout_a, layout_b;
+  int32_t M, N, K;
+  int64_t lda, ldb, ldc, ldr;
+  const void *a, *a_lo, *b, *b_up;
+  void *c, *c_lo, *c_gu;
+  const void *resid;
+  int32_t out_bf16, resid_kind, swiglu, kernel;
+} mace_gemm_desc_t;
+int mace_gemm_bf16(mace_handle_t h, const mace_gemm_desc_t *d, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

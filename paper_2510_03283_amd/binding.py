@@ -20,7 +20,7 @@ EXPORTS = [
     "mace_kv_slot_mapping", "mace_kv_cache_append", "mace_kv_cache_gather", "mace_hybrid_layer_fwd",
     "mace_hybrid_layer_bwd", "mace_hybrid_layer_fwd_lora", "mace_hybrid_layer_bwd_lora", "mace_dpo_logprob_loss", "mace_dpo_logprob_loss_shared",
     "mace_next_token_logits", "mace_adamw_step", "mace_head_norm_stats", "mace_kv_head_budget", "mace_profile_enable", "mace_profile_collect",
-    "mace_set_option", "mace_launch_plan", "mace_next_token_logits_static",
+    "mace_set_option", "mace_launch_plan", "mace_next_token_logits_static", "mace_gemm_bf16",
 ]
 MACE_OPT_HEAD_TWO_PASS, MACE_OPT_SINGLE_STREAM, MACE_OPT_DECODE_CHUNK = 1, 2, 3
 
@@ -70,6 +70,14 @@ class BatchT(C.Structure):
 class GemmPlanT(C.Structure):
     _fields_ = [("name", C.c_char * 32), ("layout", C.c_int32), ("tile_m", C.c_int32), ("tile_n", C.c_int32), ("k_splits", C.c_int32),
                 ("on_side_stream", C.c_int32), ("m", C.c_int64), ("n", C.c_int64), ("k", C.c_int64)]
+
+
+class GemmDescT(C.Structure):
+    _fields_ = [("layout_a", C.c_int32), ("layout_b", C.c_int32), ("M", C.c_int32), ("N", C.c_int32), ("K", C.c_int32),
+                ("lda", C.c_int64), ("ldb", C.c_int64), ("ldc", C.c_int64), ("ldr", C.c_int64),
+                ("a", C.c_void_p), ("a_lo", C.c_void_p), ("b", C.c_void_p), ("b_up", C.c_void_p),
+                ("c", C.c_void_p), ("c_lo", C.c_void_p), ("c_gu", C.c_void_p), ("resid", C.c_void_p),
+                ("out_bf16", C.c_int32), ("resid_kind", C.c_int32), ("swiglu", C.c_int32), ("kernel", C.c_int32)]
 
 
 class ProfileEntryT(C.Structure):
@@ -136,6 +144,8 @@ def load():
     lib.mace_set_option.restype = C.c_int
     lib.mace_launch_plan.argtypes = [vp, C.POINTER(GemmPlanT), i32, C.POINTER(i32)]
     lib.mace_launch_plan.restype = C.c_int
+    lib.mace_gemm_bf16.argtypes = [vp, C.POINTER(GemmDescT), vp]
+    lib.mace_gemm_bf16.restype = C.c_int
     _lib = lib
     return lib
 
@@ -187,6 +197,23 @@ def mace_launch_plan(h) -> list:
     return [dict(name=arr[i].name.decode(), layout=int(arr[i].layout), tile=(int(arr[i].tile_m), int(arr[i].tile_n)),
                  k_splits=int(arr[i].k_splits), on_side_stream=int(arr[i].on_side_stream), m=int(arr[i].m), n=int(arr[i].n),
                  k=int(arr[i].k)) for i in range(min(n.value, 256))]
+
+
+def mace_gemm_bf16(h, layout_a: int, layout_b: int, M: int, N: int, K: int, a, b, c, a_lo=None, resid=None, b_up=None, c_lo=None,
+                   c_gu=None, lda=None, ldb=None, ldc=None, ldr=None, swiglu=False, kernel=0, stream=None):
+    """The dense contraction kernel on its own (argument marshalling only; see include/mace.h)."""
+    d = GemmDescT()
+    d.layout_a, d.layout_b, d.M, d.N, d.K = layout_a, layout_b, M, N, K
+    d.lda = lda if lda is not None else (K if layout_a == 0 else M)
+    d.ldb = ldb if ldb is not None else (K if layout_b == 0 else N)
+    d.ldc = ldc if ldc is not None else N
+    d.ldr = ldr if ldr is not None else d.ldc
+    d.a, d.a_lo, d.b, d.b_up = _dev(a), _dev(a_lo), _dev(b), _dev(b_up)
+    d.c, d.c_lo, d.c_gu, d.resid = _dev(c), _dev(c_lo), _dev(c_gu), _dev(resid)
+    d.out_bf16 = 1 if c.dtype == torch.bfloat16 else 0
+    d.resid_kind = 0 if resid is None else (2 if resid.dtype == torch.bfloat16 else 1)
+    d.swiglu, d.kernel = int(bool(swiglu)), int(kernel)
+    _check(load().mace_gemm_bf16(h, C.byref(d), _stream(stream)), "mace_gemm_bf16")
 
 
 def mace_fwd_saved_bytes(h, n_ft_tokens: int) -> int:

@@ -568,6 +568,27 @@ int mace_launch_plan(mace_handle_t h, mace_gemm_plan_t *out, int32_t max_entries
   return MACE_OK;
 }
 
+int mace_gemm_bf16(mace_handle_t h, const mace_gemm_desc_t *d, void *stream) {
+  if (!h || !d || !d->a || !d->b || !d->c) return fail(MACE_INVALID_ARG, "mace_gemm_bf16: null argument");
+  if (d->M <= 0 || d->N <= 0 || d->K <= 0) return fail(MACE_BAD_SHAPE, "mace_gemm_bf16: M, N and K must be positive");
+  if (d->swiglu && !d->b_up) return fail(MACE_INVALID_ARG, "mace_gemm_bf16: SwiGLU mode needs b_up");
+  GemmParams p = gp_init(d->K, d->lda, d->ldb, d->ldc);
+  p.ldr = d->ldr;
+  p.out_bf16 = d->swiglu ? 1 : d->out_bf16;
+  p.resid_kind = d->resid ? d->resid_kind : 0;
+  p.force_w4 = d->kernel == 1;
+  gp_group(p, (const bf16_t *)d->a, (const bf16_t *)d->a_lo, d->c, d->resid, d->M, d->a_lo ? 2 : 1);
+  p.mg[0].c_lo = d->swiglu ? d->c_lo : nullptr;
+  p.mg[0].c_gu = d->swiglu ? d->c_gu : nullptr;
+  gp_seg(p, (const bf16_t *)d->b, nullptr, d->N, 0);
+  if (d->swiglu) {
+    p.swiglu = 1;
+    gp_seg(p, (const bf16_t *)d->b_up, nullptr, d->N, 0);
+  }
+  h->plan.clear();
+  return run_gemm(h, d->layout_a, d->layout_b, p, (hipStream_t)stream, "mace_gemm_bf16");
+}
+
 void mace_destroy(mace_handle_t h) {
   if (!h) return;
   if (h->inv_freq) (void)hipFree(h->inv_freq);

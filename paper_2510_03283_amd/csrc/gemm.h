@@ -53,6 +53,7 @@ struct GemmParams {
   int mt_start[4];  // filled by gemm_launch
   int nt_start[4];
   int tile_m, tile_n;   // filled by gemm_launch: the block tile its cost model chose
+  int force_w4;     // 1: the 256x256 four-wave kernel whatever the cost model says (rejected if the problem does not fit it)
 };
 
 // Number of k slices worth using for a single-group, single-segment problem (1 = none): small

@@ -552,11 +552,15 @@ double tile_cost(const GemmParams &p, int slots, double slot_share, double eff) 
 }
 
 template <int LA, int LB>
-hipError_t launch_layout(GemmParams &p, hipStream_t stream) {
+hipError_t launch_layout(GemmParams &p, hipStream_t stream, const char **why) {
   const double c256 = tile_cost<256, 256>(p, 256, 1.0, 1.0);
   const double c192 = tile_cost<192, 256>(p, 256, 1.0, 0.92);
   const double c128 = tile_cost<128, 128>(p, 512, 2.0, 0.83);
   const int tile = c256 <= c192 && c256 <= c128 ? 1 : (c192 <= c128 ? 2 : 0);
+  if (p.force_w4) {
+    if (!w4_fits<LA, LB>(p)) { *why = "gemm: the problem does not fit the four-wave kernel"; return hipErrorInvalidValue; }
+    return launch_w4<LA, LB>(p, stream);
+  }
   if (tile == 1) {
     // the four-wave kernel where the reduction is long enough to pay for its longer start and end of a tile
     // (measured: 7 - 12 % faster at K >= 4096, up to 14 % slower on the 2048-long reductions of the small
@@ -611,9 +615,9 @@ hipError_t gemm_launch(int LA, int LB, GemmParams &p, hipStream_t stream, const 
   // multi-pass row groups first (stable): their tiles take longest and should start first
   for (int i = 1; i < p.n_mg; ++i)
     for (int j = i; j > 0 && p.mg[j].npass > p.mg[j - 1].npass; --j) std::swap(p.mg[j], p.mg[j - 1]);
-  if (LA == 0 && LB == 0) return launch_layout<0, 0>(p, stream);
-  if (LA == 0 && LB == 1) return launch_layout<0, 1>(p, stream);
-  if (LA == 1 && LB == 1) return launch_layout<1, 1>(p, stream);
+  if (LA == 0 && LB == 0) return launch_layout<0, 0>(p, stream, why);
+  if (LA == 0 && LB == 1) return launch_layout<0, 1>(p, stream, why);
+  if (LA == 1 && LB == 1) return launch_layout<1, 1>(p, stream, why);
   *why = "gemm: unsupported layout";
   return hipErrorInvalidValue;
 }
