@@ -519,11 +519,14 @@ hipError_t launch_w4(GemmParams &p, hipStream_t stream) {
 
 bool aligned16(const void *q) { return ((uintptr_t)q & 15) == 0; }
 
-// Tile choice.  256x256 tiles (8 waves, one block per CU) do 0.75 LDS fragment reads per MFMA and
-// half the L2 traffic of 128x128 tiles (4 waves, two blocks per CU), but quantise worse on small
-// problems; 192x256 (8 waves) sits between.  Each candidate is priced as
-//   length of its schedule over the (CU x resident block) slots  x  tile area  /  measured relative efficiency,
-// a tile of a row group with p passes taking p time units on its slot, and the cheapest is launched.
+// Tile choice.  256x256 tiles (four waves with 128x128 wave tiles, one block per CU) do 0.5 LDS fragment
+// reads per MFMA and half the L2 traffic of 128x128 tiles (4 waves, two blocks per CU), but quantise worse on
+// small problems; 192x256 (8 waves) sits between.  Each candidate is priced as
+//   length of its schedule over the (CU x resident block) slots  x  tile area  /  relative efficiency,
+// a tile of a row group with p passes taking p time units on its slot, and the cheapest is launched.  The
+// efficiencies (0.69 for 192x256, 0.62 for 128x128, relative to the four-wave kernel) are fitted to whole steps
+// of the benchmark configurations: step time is flat for factors between 0.68 and 0.8 of the kernels' long-run
+// ratios (0.92, 0.83) and 1 - 6 % worse on either side.
 template <int BM, int BN>
 double tile_cost(const GemmParams &p, int slots, double slot_share, double eff) {
   const int ks = p.k_splits > 1 ? p.k_splits : 1;
@@ -554,18 +557,17 @@ double tile_cost(const GemmParams &p, int slots, double slot_share, double eff) 
 template <int LA, int LB>
 hipError_t launch_layout(GemmParams &p, hipStream_t stream, const char **why) {
   const double c256 = tile_cost<256, 256>(p, 256, 1.0, 1.0);
-  const double c192 = tile_cost<192, 256>(p, 256, 1.0, 0.92);
-  const double c128 = tile_cost<128, 128>(p, 512, 2.0, 0.83);
+  const double c192 = tile_cost<192, 256>(p, 256, 1.0, 0.69);
+  const double c128 = tile_cost<128, 128>(p, 512, 2.0, 0.62);
   const int tile = c256 <= c192 && c256 <= c128 ? 1 : (c192 <= c128 ? 2 : 0);
   if (p.force_w4) {
     if (!w4_fits<LA, LB>(p)) { *why = "gemm: the problem does not fit the four-wave kernel"; return hipErrorInvalidValue; }
     return launch_w4<LA, LB>(p, stream);
   }
   if (tile == 1) {
-    // the four-wave kernel where the reduction is long enough to pay for its longer start and end of a tile
-    // (measured: 7 - 12 % faster at K >= 4096, up to 14 % slower on the 2048-long reductions of the small
-    // configuration)
-    if (p.K >= 4096 && w4_fits<LA, LB>(p)) return launch_w4<LA, LB>(p, stream);
+    // the four-wave kernel, at every reduction length (measured against the eight-wave kernel of the same tile:
+    // 5 % faster at K = 1024 .. 2048, 7 - 12 % at K >= 4096); the eight-wave kernel takes what does not fit it
+    if (w4_fits<LA, LB>(p)) return launch_w4<LA, LB>(p, stream);
     return launch_dl<256, 256, 2, 4, LA, LB, BK, NSTAGES>(p, stream);
   }
   if (tile == 2) return launch_dl<192, 256, 2, 4, LA, LB, BK, NSTAGES>(p, stream);
