@@ -380,6 +380,9 @@ int mace_launch_plan(mace_handle_t h, mace_gemm_plan_t *out, int32_t max_entries
  * swiglu = 1 (layouts (0,0) only): b holds the gate rows and b_up the up rows of N hidden units, and instead of
  * the products G and U the call writes hm = silu(G) * U as bf16 into c ([M, N], ldc), its second bf16 term
  * into c_lo (nullable) and G | U as bf16 [M, 2N] into c_gu (nullable).
+ * swiglu = 2 (layouts (0,1), kernel = 1 only): the backward form.  The product is dHm [M, N]; c_gu holds G | U of the
+ * forward (bf16 [M, 2N], read only) and instead of dHm the call writes dG | dU as bf16 [M, 2N] into c (ldc = 2N):
+ * dG = dHm U s (1 + G (1 - s)), dU = dHm G s, s = sigmoid(G).
  * kernel = 0: the launcher picks tile and kernel from the sizes as it does inside the iteration; 1: the 256x256
  * four-wave kernel (MACE_BAD_SHAPE where the problem does not fit it).
  * Requirements: K a multiple of 64 for a k-contiguous operand; M (N) a multiple of 8 for an m- (n-) contiguous

@@ -212,7 +212,7 @@ def mace_gemm_bf16(h, layout_a: int, layout_b: int, M: int, N: int, K: int, a, b
     d.c, d.c_lo, d.c_gu, d.resid = _dev(c), _dev(c_lo), _dev(c_gu), _dev(resid)
     d.out_bf16 = 1 if c.dtype == torch.bfloat16 else 0
     d.resid_kind = 0 if resid is None else (2 if resid.dtype == torch.bfloat16 else 1)
-    d.swiglu, d.kernel = int(bool(swiglu)), int(kernel)
+    d.swiglu, d.kernel = int(swiglu), int(kernel)
     _check(load().mace_gemm_bf16(h, C.byref(d), _stream(stream)), "mace_gemm_bf16")
 
 

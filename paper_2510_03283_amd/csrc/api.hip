@@ -571,17 +571,19 @@ int mace_launch_plan(mace_handle_t h, mace_gemm_plan_t *out, int32_t max_entries
 int mace_gemm_bf16(mace_handle_t h, const mace_gemm_desc_t *d, void *stream) {
   if (!h || !d || !d->a || !d->b || !d->c) return fail(MACE_INVALID_ARG, "mace_gemm_bf16: null argument");
   if (d->M <= 0 || d->N <= 0 || d->K <= 0) return fail(MACE_BAD_SHAPE, "mace_gemm_bf16: M, N and K must be positive");
-  if (d->swiglu && !d->b_up) return fail(MACE_INVALID_ARG, "mace_gemm_bf16: SwiGLU mode needs b_up");
+  if (d->swiglu == 1 && !d->b_up) return fail(MACE_INVALID_ARG, "mace_gemm_bf16: SwiGLU mode needs b_up");
+  if (d->swiglu == 2 && (!d->c_gu || d->kernel != 1)) return fail(MACE_INVALID_ARG, "mace_gemm_bf16: SwiGLU backward mode needs c_gu and kernel = 1");
   GemmParams p = gp_init(d->K, d->lda, d->ldb, d->ldc);
   p.ldr = d->ldr;
   p.out_bf16 = d->swiglu ? 1 : d->out_bf16;
+  p.swiglu_bwd = d->swiglu == 2;
   p.resid_kind = d->resid ? d->resid_kind : 0;
   p.force_w4 = d->kernel == 1;
   gp_group(p, (const bf16_t *)d->a, (const bf16_t *)d->a_lo, d->c, d->resid, d->M, d->a_lo ? 2 : 1);
   p.mg[0].c_lo = d->swiglu ? d->c_lo : nullptr;
   p.mg[0].c_gu = d->swiglu ? d->c_gu : nullptr;
   gp_seg(p, (const bf16_t *)d->b, nullptr, d->N, 0);
-  if (d->swiglu) {
+  if (d->swiglu == 1) {
     p.swiglu = 1;
     gp_seg(p, (const bf16_t *)d->b_up, nullptr, d->N, 0);
   }
@@ -1063,14 +1065,24 @@ static int layer_bwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
   HIP_TRY(launch_split_f32(dy_ft, (size_t)Tf * D.d, B.dy_bf, nullptr, st), "cast dy");
   // MLP: dHm = dY Wd ; SwiGLU backward ; dWd = dY^T Hm with the Hm the forward kept
   {
-    GemmParams p = gp_init(D.d, D.d, D.F, D.F);
-    p.out_bf16 = 1;
-    gp_group(p, B.dy_bf, nullptr, B.dhm, nullptr, Tf, 1);
-    gp_seg(p, W.hi[W_D], nullptr, D.F, 0);
-    TRY(run_gemm(h, 0, 1, p, st, "dhm gemm"));
+    // where the product runs on the four-wave kernel its epilogue does the SwiGLU backward (dHm stays in registers)
+    GemmParams pf = gp_init(D.d, D.d, D.F, 2ll * D.F);
+    pf.out_bf16 = 1; pf.swiglu_bwd = 1;
+    gp_group(pf, B.dy_bf, nullptr, B.dgu, nullptr, Tf, 1);
+    pf.mg[0].c_gu = (void *)S.gu;
+    gp_seg(pf, W.hi[W_D], nullptr, D.F, 0);
+    if (gemm_uses_four_wave(0, 1, pf)) {
+      TRY(run_gemm(h, 0, 1, pf, st, "dhm gemm + swiglu bwd"));
+    } else {
+      GemmParams p = gp_init(D.d, D.d, D.F, D.F);
+      p.out_bf16 = 1;
+      gp_group(p, B.dy_bf, nullptr, B.dhm, nullptr, Tf, 1);
+      gp_seg(p, W.hi[W_D], nullptr, D.F, 0);
+      TRY(run_gemm(h, 0, 1, p, st, "dhm gemm"));
+      prof_mark(h, st, T_SWIGLU);
+      HIP_TRY(launch_swiglu_bwd(B.dhm, S.gu, Tf, D.F, B.dgu, st), "swiglu bwd");
+    }
   }
-  prof_mark(h, st, T_SWIGLU);
-  HIP_TRY(launch_swiglu_bwd(B.dhm, S.gu, Tf, D.F, B.dgu, st), "swiglu bwd");
   if (grads->w_down) {
     GemmParams p = gp_init(Tf, D.d, D.F, D.F);
     p.resid_kind = acc;

@@ -53,6 +53,10 @@ struct GemmParams {
   int mt_start[4];  // filled by gemm_launch
   int nt_start[4];
   int tile_m, tile_n;   // filled by gemm_launch: the block tile its cost model chose
+  // SwiGLU backward mode (NN form, four-wave kernel only - ask gemm_uses_four_wave first): the product is dHm [M, N = F];
+  // instead of it the epilogue writes dG | dU as bf16 [M, 2F] into c (ldc = 2F) from G | U of the forward, bf16 [M, 2F]
+  // in c_gu (read only): dG = dHm U s (1 + G (1 - s)), dU = dHm G s, s = sigmoid(G).
+  int swiglu_bwd;
   int force_w4;     // 1: the 256x256 four-wave kernel whatever the cost model says (rejected if the problem does not fit it)
 };
 
@@ -60,6 +64,10 @@ struct GemmParams {
 // outputs with a long reduction leave most CUs idle otherwise.  Priced with the launcher's tile
 // cost model plus the traffic of writing and summing the partial results.
 int gemm_suggest_k_splits(int M, int N, int K);
+
+// Whether gemm_launch would run this problem on the four-wave kernel (its cost model picks the 256x256 tile, or
+// force_w4 is set, and the problem fits the kernel).  Forms that only that kernel has are launched after asking.
+bool gemm_uses_four_wave(int LA, int LB, const GemmParams &p);
 
 // Returns hipSuccess or the launch error; a non-null *why is set on a rejected shape.
 hipError_t gemm_launch(int LA, int LB, GemmParams &p, hipStream_t stream, const char **why);

@@ -554,16 +554,26 @@ double tile_cost(const GemmParams &p, int slots, double slot_share, double eff) 
   return (double)end * BM * BN * slot_share / eff;
 }
 
-template <int LA, int LB>
-hipError_t launch_layout(GemmParams &p, hipStream_t stream, const char **why) {
+// 1: 256x256, 2: 192x256, 0: 128x128
+int choose_tile(const GemmParams &p) {
   const double c256 = tile_cost<256, 256>(p, 256, 1.0, 1.0);
   const double c192 = tile_cost<192, 256>(p, 256, 1.0, 0.69);
   const double c128 = tile_cost<128, 128>(p, 512, 2.0, 0.62);
-  const int tile = c256 <= c192 && c256 <= c128 ? 1 : (c192 <= c128 ? 2 : 0);
-  if (p.force_w4) {
-    if (!w4_fits<LA, LB>(p)) { *why = "gemm: the problem does not fit the four-wave kernel"; return hipErrorInvalidValue; }
+  return c256 <= c192 && c256 <= c128 ? 1 : (c192 <= c128 ? 2 : 0);
+}
+
+template <int LA, int LB>
+bool uses_w4(const GemmParams &p) {
+  return (p.force_w4 || choose_tile(p) == 1) && w4_fits<LA, LB>(p);
+}
+
+template <int LA, int LB>
+hipError_t launch_layout(GemmParams &p, hipStream_t stream, const char **why) {
+  if (p.force_w4 || p.swiglu_bwd) {
+    if (!uses_w4<LA, LB>(p)) { *why = "gemm: the problem does not run on the four-wave kernel"; return hipErrorInvalidValue; }
     return launch_w4<LA, LB>(p, stream);
   }
+  const int tile = choose_tile(p);
   if (tile == 1) {
     // the four-wave kernel, at every reduction length (measured against the eight-wave kernel of the same tile:
     // 5 % faster at K = 1024 .. 2048, 7 - 12 % at K >= 4096); the eight-wave kernel takes what does not fit it
@@ -607,6 +617,15 @@ hipError_t gemm_launch(int LA, int LB, GemmParams &p, hipStream_t stream, const 
       return hipErrorInvalidValue;
     }
   }
+  if (p.swiglu_bwd) {
+    if (LA != 0 || LB != 1 || p.n_ns != 1 || p.ns[0].c_col != 0 || p.ns[0].N % 2 || !p.out_bf16 || p.resid_kind || p.k_splits > 1 || p.swiglu ||
+        p.ldc != 2ll * p.ns[0].N) {
+      *why = "gemm: SwiGLU backward mode needs the NN form, one column segment, bf16 output [M, 2N] and no residual";
+      return hipErrorInvalidValue;
+    }
+    for (int g = 0; g < p.n_mg; ++g)
+      if (!p.mg[g].c_gu) { *why = "gemm: SwiGLU backward mode needs G | U of the forward"; return hipErrorInvalidValue; }
+  }
   if (p.n_kseg > 1) {
     if (p.n_kseg > 3 || p.n_ns != 1 || p.kseg_start[0] != 0 || p.kseg_start[p.n_kseg] != p.K) { *why = "gemm: bad k segments"; return hipErrorInvalidValue; }
     for (int g = 0; g < p.n_mg; ++g)
@@ -622,6 +641,13 @@ hipError_t gemm_launch(int LA, int LB, GemmParams &p, hipStream_t stream, const 
   if (LA == 1 && LB == 1) return launch_layout<1, 1>(p, stream, why);
   *why = "gemm: unsupported layout";
   return hipErrorInvalidValue;
+}
+
+bool gemm_uses_four_wave(int LA, int LB, const GemmParams &p) {
+  if (LA == 0 && LB == 0) return uses_w4<0, 0>(p);
+  if (LA == 0 && LB == 1) return uses_w4<0, 1>(p);
+  if (LA == 1 && LB == 1) return uses_w4<1, 1>(p);
+  return false;
 }
 
 int gemm_suggest_k_splits(int M, int N, int K) {

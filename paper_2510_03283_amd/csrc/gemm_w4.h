@@ -496,6 +496,85 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const GemmParams p) {
   }
   const int col_u = n0 + wn * WTN;                                  // the wave's first column
   const long long c_col0 = c_col + (long long)blockIdx.y * p.c_split_stride;
+  if (p.swiglu_bwd) {
+    if constexpr (LA == 0 && LB == 1) {
+      // SwiGLU backward in the epilogue of dHm = dY Wd: the tile of dHm never leaves the registers.  With G and U of
+      // the forward (bf16 [M, 2F], G | U) it becomes dG = dHm U s (1 + G (1 - s)) and dU = dHm G s, s = sigmoid(G),
+      // written as bf16 [M, 2F] (dG | dU) - the same layout, so G, U, dG and dU of an element pair share one lane
+      // offset (U and dU lie F columns further on).  The pair and half swaps of the packed bf16 stores are done on
+      // the fp32 values, so that a lane computes on the two neighbouring columns it loads and stores as one word.
+      const int F = N;
+      const int col_l = lane - (odd ? 1 : 0), row_l = odd ? 1 : 0;
+      uint32_t vg[2][TN / 2], vu[2][TN / 2];      // lane offsets by row half and block pair, G / dG and U / dU
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+        for (int jp = 0; jp < TN / 2; ++jp) {
+          const bool ok = col_u + jp * 64 + col_l < F;
+          vg[hh][jp] = ok ? (uint32_t)((row_l + 4 * hh) * 2 * F + col_l + jp * 64) * 2u : OUT;
+          vu[hh][jp] = ok ? vg[hh][jp] + (uint32_t)F * 2u : OUT;
+        }
+      const auto qo = view((bf16_t *)Cp + (long long)row_u * 2 * F + col_u, (long long)rows_v * F * 4);
+      const auto qi = view((const bf16_t *)G.c_gu + (long long)row_u * 2 * F + col_u, (long long)rows_v * F * 4);
+      const uint32_t s2r = w4_sgpr((uint32_t)F * 8u), s6r = w4_sgpr((uint32_t)F * 24u);      // 2 and 6 rows
+      uint32_t sc = 0;
+      static_for<0, TM>([&](auto I) W4_INL {
+        constexpr int i = decltype(I)::value;
+        // G and U of the 32 rows of block row i are requested together (nothing else covers the latency)
+        uint32_t gw[8][TN / 2][2], uw[8][TN / 2][2];
+        {
+          uint32_t q = sc;
+          static_for<0, 8>([&](auto R2) W4_INL {
+            constexpr int r2 = decltype(R2)::value;
+            static_for<0, TN / 2>([&](auto JP) W4_INL {
+              static_for<0, 2>([&](auto H) W4_INL {
+                constexpr int jp = decltype(JP)::value, hh = decltype(H)::value;
+                gw[r2][jp][hh] = __builtin_amdgcn_raw_buffer_load_b32(qi, (int)vg[hh][jp], (int)q, 0);
+                uw[r2][jp][hh] = __builtin_amdgcn_raw_buffer_load_b32(qi, (int)vu[hh][jp], (int)q, 0);
+              });
+            });
+            q += (r2 & 1) ? s6r : s2r;
+          });
+        }
+        W4_SB;
+        static_for<0, 8>([&](auto R2) W4_INL {
+          constexpr int r2 = decltype(R2)::value, r = 2 * r2;
+          static_for<0, TN / 2>([&](auto JP) W4_INL {
+            constexpr int jp = decltype(JP)::value;
+            float x0[2], x1[2];      // the lane's column pair of dHm, by block of the pair
+            static_for<0, 2>([&](auto JB) W4_INL {
+              constexpr int jb = decltype(JB)::value, j = 2 * jp + jb;
+              const float va = w4_acc_rd(acc[i][j][r]), vb = w4_acc_rd(acc[i][j][r + 1]);
+              const float vx = swap_pair(va, vb);
+              x0[jb] = odd ? vx : va;
+              x1[jb] = odd ? vb : vx;
+            });
+            const u32x2_t t0 = __builtin_amdgcn_permlane32_swap(__float_as_uint(x0[0]), __float_as_uint(x0[1]), false, false);
+            const u32x2_t t1 = __builtin_amdgcn_permlane32_swap(__float_as_uint(x1[0]), __float_as_uint(x1[1]), false, false);
+            static_for<0, 2>([&](auto H) W4_INL {
+              constexpr int hh = decltype(H)::value;
+              const float dh[2] = {__uint_as_float(t0[hh]), __uint_as_float(t1[hh])};
+              const uint32_t g2 = gw[r2][jp][hh], u2 = uw[r2][jp][hh];
+              float dg[2], du[2];
+#pragma unroll
+              for (int e = 0; e < 2; ++e) {
+                const float g = e ? __uint_as_float(g2 & 0xffff0000u) : __uint_as_float(g2 << 16);
+                const float u = e ? __uint_as_float(u2 & 0xffff0000u) : __uint_as_float(u2 << 16);
+                const float sg = __builtin_amdgcn_rcpf(1.0f + __expf(-g));
+                du[e] = dh[e] * g * sg;
+                dg[e] = dh[e] * u * sg * (1.0f + g * (1.0f - sg));
+              }
+              store32(cvt_pk_bf16(dg[0], dg[1]), qo, vg[hh][jp], sc);
+              store32(cvt_pk_bf16(du[0], du[1]), qo, vu[hh][jp], sc);
+            });
+          });
+          sc += (r2 & 1) ? s6r : s2r;
+        });
+        W4_SB;
+      });
+    }
+    return;
+  }
   if (obf) {
     // packed bf16 (even column count and offset, no residual): neighbouring lanes (columns c, c+1) swap one
     // value of a register pair (rows r, r+1); the even lane then holds columns (c, c+1) of row r, the odd lane
@@ -602,6 +681,7 @@ bool w4_fits(const GemmParams &p) {
     if (p.swiglu && (p.ns[s].N & 1)) return false;
   }
   if (p.out_bf16 && !p.swiglu && p.resid_kind != 0) return false;
+  if (p.swiglu_bwd && !(LA == 0 && LB == 1)) return false;
   if (p.ldc >= (1ll << 21) || p.ldr >= (1ll << 21)) return false;
   return true;
 }

@@ -112,6 +112,27 @@ def test_swiglu_form(torch_mod, handle, kernel, keep):
         check_out(gu, np.concatenate([G, U], axis=1), M, 2 * F, 4e-3, f"G | U, kernel {kernel}")
 
 
+def test_swiglu_backward_form(torch_mod, handle):
+    """dG | dU from dHm = dY Wd and the forward's G | U, formed in the epilogue of the product (four-wave kernel, NN form)."""
+    torch = torch_mod
+    from paper_2510_03283_amd import binding
+    M, F, K = 700, 840, 4096
+    rng = np.random.default_rng(211)
+    dy = bf16_of(torch, rng.uniform(-1, 1, (M, K)))
+    wd = bf16_of(torch, rng.uniform(-1, 1, (K, F)) / 16)          # [K, N]: the n-contiguous operand of the NN form
+    gu = bf16_of(torch, rng.uniform(-4, 4, (M + 5, 2 * F)))
+    dhm = f64(dy) @ f64(wd)
+    G, U = f64(gu)[:M, :F], f64(gu)[:M, F:]
+    s = 1.0 / (1.0 + np.exp(-G))
+    ref = np.concatenate([dhm * U * s * (1.0 + G * (1.0 - s)), dhm * G * s], axis=1)
+    dgu = out_buffer(torch, M + 5, 2 * F, torch.bfloat16)
+    binding.mace_gemm_bf16(handle, 0, 1, M, F, K, dy, wd, dgu, c_gu=gu, ldc=2 * F, swiglu=2, kernel=1)
+    torch.cuda.synchronize()
+    check_out(dgu, ref, M, 2 * F, 4e-3, "dG | dU")
+    with pytest.raises(binding.MaceError):      # only the four-wave kernel has this form
+        binding.mace_gemm_bf16(handle, 0, 1, M, F, K, dy, wd, dgu, c_gu=gu, ldc=2 * F, swiglu=2, kernel=0)
+
+
 def test_rejects_what_the_four_wave_kernel_cannot_do(torch_mod, handle):
     torch = torch_mod
     from paper_2510_03283_amd import binding
