@@ -906,6 +906,10 @@ static int layer_fwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
     HIP_TRY(launch_scale_split(L.t_qkv + (size_t)I.Ti * 3 * LR, (size_t)I.Tf * 3 * LR, lora->scale, S.tq, L.tq_lo, s2), "lora t_qkv split ft");
     if (s2 != st) prof_mark(h, s2, -1);
   }
+  // Where the product runs on the four-wave kernel (and no adapter correction has to be added to it first), the
+  // rotary embedding and the operand split of the fine-tune rows happen in its epilogue: those rows of qkv never
+  // exist in fp32, and their angle table takes the place of the fp32 buffer.
+  bool rope_fused = false;
   {
     GemmParams p = gp_init(D.d, D.d, D.d, D.nqkv);
     gp_group(p, S.a, F.a_lo, F.qkv_f, nullptr, I.Tf, np_ft);
@@ -913,7 +917,21 @@ static int layer_fwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
     gp_seg(p, W.hi[W_Q], W.lo[W_Q], D.qd, 0);
     gp_seg(p, W.hi[W_K], W.lo[W_K], D.kd, D.qd);
     gp_seg(p, W.hi[W_V], W.lo[W_V], D.kd, D.qd + D.kd);
-    TRY(run_gemm(h, 0, 0, p, st, "qkv gemm"));
+    if (!lora && D.hd == 128 && I.Tf > 0) {
+      GemmParams pr = p;
+      pr.mg[0].rope = 1;
+      pr.rope_cs = F.qkv_f;
+      pr.ns[0].rope_hi = S.q; pr.ns[0].rope_lo = F.q_lo; pr.ns[0].rope_rot = 1;
+      pr.ns[1].rope_hi = S.k; pr.ns[1].rope_lo = F.k_lo; pr.ns[1].rope_rot = 1;
+      pr.ns[2].rope_hi = S.v; pr.ns[2].rope_lo = F.v_lo; pr.ns[2].rope_rot = 0;
+      if (gemm_uses_four_wave(0, 0, pr)) {
+        prof_mark(h, st, T_ROPE);
+        HIP_TRY(launch_rope_table(batch->positions + I.Ti, h->inv_freq, I.Tf, D.hd, (float2 *)F.qkv_f, st), "rope table");
+        TRY(run_gemm(h, 0, 0, pr, st, "qkv gemm + rope"));
+        rope_fused = true;
+      }
+    }
+    if (!rope_fused) TRY(run_gemm(h, 0, 0, p, st, "qkv gemm"));
   }
   if (lora) {
     HIP_TRY(side_join(h, st), "join side stream");
@@ -930,9 +948,11 @@ static int layer_fwd_impl(mace_handle_t h, const mace_layer_w_t *w, const mace_l
     HIP_TRY(launch_rope_split(F.qkv_i, batch->positions, h->inv_freq, I.Ti, D.Hq, D.Hkv, D.hd, F.q_i, F.k_i, F.v_i, nullptr, nullptr, nullptr,
                               batch->slot_mapping, cache->k, cache->v, D.bf, cache->num_blocks * cache->block_size, cache->block_size, st), "rope");
   }
-  prof_mark(h, st, T_ROPE);
-  HIP_TRY(launch_rope_split(F.qkv_f, batch->positions + I.Ti, h->inv_freq, I.Tf, D.Hq, D.Hkv, D.hd, S.q, S.k, S.v, F.q_lo, F.k_lo, F.v_lo,
-                            nullptr, nullptr, nullptr, D.bf, 0, 1, st), "rope ft");
+  if (!rope_fused) {
+    prof_mark(h, st, T_ROPE);
+    HIP_TRY(launch_rope_split(F.qkv_f, batch->positions + I.Ti, h->inv_freq, I.Tf, D.Hq, D.Hkv, D.hd, S.q, S.k, S.v, F.q_lo, F.k_lo, F.v_lo,
+                              nullptr, nullptr, nullptr, D.bf, 0, 1, st), "rope ft");
+  }
   // 4. attention: prefill (causal), decode (paged), fine-tune (causal, split operands, LSE kept)
   prof_mark(h, st, T_ATTN_PREFILL, 4.0 * D.hd * D.Hq * I.pairs_prefill);
   if (I.prefix && batch->n_prefill > 0)

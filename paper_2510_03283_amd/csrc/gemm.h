@@ -23,11 +23,19 @@ struct GemmMGroup {
   // term; c_gu (nullable) G and U as bf16 [M, 2F] (G in columns [0,F), U in [F,2F)).
   void *c_lo;
   void *c_gu;
+  // Rotary mode (NT form, four-wave kernel only - ask gemm_uses_four_wave first; head dimension 128): 1 = the rows
+  // of this group are not written to c; every column segment writes its part as two bf16 terms [M, N] (row stride
+  // N) into its rope_hi / rope_lo, rotated by the group's angle table where the segment says so.
+  int rope;
 };
 struct GemmNSeg {
   const bf16_t *b[2];   // [0] = hi (or only) operand, [1] = lo term (pass 3)
   int N;                // columns in the segment
   int c_col;            // first output column of the segment
+  // rotary mode (row groups with rope = 1): outputs of this segment and whether its heads are rotated (Q, K) or
+  // only split into two terms (V)
+  void *rope_hi, *rope_lo;
+  int rope_rot;
 };
 struct GemmParams {
   GemmMGroup mg[3];
@@ -57,6 +65,7 @@ struct GemmParams {
   // instead of it the epilogue writes dG | dU as bf16 [M, 2F] into c (ldc = 2F) from G | U of the forward, bf16 [M, 2F]
   // in c_gu (read only): dG = dHm U s (1 + G (1 - s)), dU = dHm G s, s = sigmoid(G).
   int swiglu_bwd;
+  const float *rope_cs;   // rotary mode: (cos, sin) of row r of the rope group and pair index i at rope_cs[2 (64 r + i)]
   int force_w4;     // 1: the 256x256 four-wave kernel whatever the cost model says (rejected if the problem does not fit it)
 };
 

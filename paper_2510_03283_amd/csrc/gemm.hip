@@ -562,6 +562,12 @@ int choose_tile(const GemmParams &p) {
   return c256 <= c192 && c256 <= c128 ? 1 : (c192 <= c128 ? 2 : 0);
 }
 
+bool has_rope(const GemmParams &p) {
+  for (int g = 0; g < p.n_mg; ++g)
+    if (p.mg[g].rope) return true;
+  return false;
+}
+
 template <int LA, int LB>
 bool uses_w4(const GemmParams &p) {
   return (p.force_w4 || choose_tile(p) == 1) && w4_fits<LA, LB>(p);
@@ -569,7 +575,7 @@ bool uses_w4(const GemmParams &p) {
 
 template <int LA, int LB>
 hipError_t launch_layout(GemmParams &p, hipStream_t stream, const char **why) {
-  if (p.force_w4 || p.swiglu_bwd) {
+  if (p.force_w4 || p.swiglu_bwd || has_rope(p)) {      // forms that only the four-wave kernel has
     if (!uses_w4<LA, LB>(p)) { *why = "gemm: the problem does not run on the four-wave kernel"; return hipErrorInvalidValue; }
     return launch_w4<LA, LB>(p, stream);
   }
@@ -616,6 +622,11 @@ hipError_t gemm_launch(int LA, int LB, GemmParams &p, hipStream_t stream, const 
       *why = "gemm: SwiGLU mode needs the NT form, two equal column segments and a plain bf16 output";
       return hipErrorInvalidValue;
     }
+  }
+  if (has_rope(p)) {
+    bool ok = LA == 0 && LB == 0 && !p.swiglu && !p.swiglu_bwd && !p.out_bf16 && !p.resid_kind && p.k_splits <= 1 && p.n_kseg <= 1 && p.rope_cs;
+    for (int s = 0; s < p.n_ns; ++s) ok = ok && p.ns[s].N % 128 == 0 && p.ns[s].rope_hi;
+    if (!ok) { *why = "gemm: rotary mode needs the NT form, plain fp32 output for the other rows, segments of whole 128-wide heads and an angle table"; return hipErrorInvalidValue; }
   }
   if (p.swiglu_bwd) {
     if (LA != 0 || LB != 1 || p.n_ns != 1 || p.ns[0].c_col != 0 || p.ns[0].N % 2 || !p.out_bf16 || p.resid_kind || p.k_splits > 1 || p.swiglu ||

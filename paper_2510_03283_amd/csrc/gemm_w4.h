@@ -495,6 +495,82 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const GemmParams p) {
     return;
   }
   const int col_u = n0 + wn * WTN;                                  // the wave's first column
+  if (G.rope) {
+    if constexpr (LA == 0 && LB == 0) {
+      // Rotary embedding and operand split in the epilogue of the QKV product: the wave's 128 columns are one head
+      // (head dimension 128), so element i of the head sits in column blocks 0, 1 and its partner i + 64 in the
+      // same register of blocks 2, 3.  (cos, sin) of (row, i) come from the group's table; the rotated (Q, K) or
+      // plain (V) values leave as two bf16 terms through the pair and half swaps of the packed bf16 stores.
+      const int rot = S.rope_rot;
+      bf16_t *const ohi = (bf16_t *)S.rope_hi, *const olo = (bf16_t *)S.rope_lo;
+      const int col_l = lane - (odd ? 1 : 0), row_l = odd ? 1 : 0;
+      uint32_t vo[2][2];      // lane offsets of the stores by row half and block pair (output rows are N wide)
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+        for (int jp = 0; jp < 2; ++jp)
+          vo[hh][jp] = col_u + jp * 64 + col_l < N ? (uint32_t)((row_l + 4 * hh) * N + col_l + jp * 64) * 2u : OUT;
+      const uint32_t vt[2] = {(uint32_t)(lrow * 64 + lcol) * 8u, (uint32_t)(lrow * 64 + 32 + lcol) * 8u};      // table, blocks 0 and 1
+      const auto qh = view(ohi + (long long)row_u * N + col_u, (long long)rows_v * N * 2);
+      const auto ql = view(olo + (long long)row_u * N + col_u, olo ? (long long)rows_v * N * 2 : 0);
+      const auto qt = view(p.rope_cs + (long long)row_u * 128, (long long)rows_v * 512);
+      const uint32_t o2r = w4_sgpr((uint32_t)N * 4u), o6r = w4_sgpr((uint32_t)N * 12u);      // 2 and 6 output rows
+      uint32_t so = 0, st = 0;      // row offsets of the outputs and of the table
+      static_for<0, TM>([&](auto I) W4_INL {
+        constexpr int i = decltype(I)::value;
+        u32x2_t cs[16][2];      // the table entries of the block row's 16 registers, requested together
+        {
+          uint32_t q = st;
+          static_for<0, 16>([&](auto R) W4_INL {
+            constexpr int r = decltype(R)::value;
+            static_for<0, 2>([&](auto J) W4_INL { cs[r][decltype(J)::value] = __builtin_amdgcn_raw_buffer_load_b64(qt, (int)vt[decltype(J)::value], (int)q, 0); });
+            q += (r & 3) == 3 ? 2560u : 512u;
+          });
+          st += 32u * 512u;
+        }
+        W4_SB;
+        static_for<0, 8>([&](auto R2) W4_INL {
+          constexpr int r2 = decltype(R2)::value, r = 2 * r2;
+          float v[TN][2];
+          static_for<0, TN>([&](auto J) W4_INL {
+            constexpr int j = decltype(J)::value;
+            v[j][0] = w4_acc_rd(acc[i][j][r]);
+            v[j][1] = w4_acc_rd(acc[i][j][r + 1]);
+          });
+          if (rot) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+              for (int e = 0; e < 2; ++e) {
+                const float c = __uint_as_float(cs[r + e][j][0]), sn = __uint_as_float(cs[r + e][j][1]);
+                const float a = v[j][e], b = v[j + 2][e];
+                v[j][e] = a * c - b * sn;
+                v[j + 2][e] = b * c + a * sn;
+              }
+          }
+          uint32_t wh[TN], wl[TN];
+#pragma unroll
+          for (int j = 0; j < TN; ++j) {
+            const float vx = swap_pair(v[j][0], v[j][1]);
+            split_pk_bf16(odd ? vx : v[j][0], odd ? v[j][1] : vx, wh[j], wl[j]);
+          }
+          static_for<0, 2>([&](auto JP) W4_INL {
+            constexpr int jp = decltype(JP)::value;
+            const u32x2_t s_h = __builtin_amdgcn_permlane32_swap(wh[2 * jp], wh[2 * jp + 1], false, false);
+            const u32x2_t s_l = __builtin_amdgcn_permlane32_swap(wl[2 * jp], wl[2 * jp + 1], false, false);
+            static_for<0, 2>([&](auto H) W4_INL {
+              constexpr int hh = decltype(H)::value;
+              store32(s_h[hh], qh, vo[hh][jp], so);
+              store32(s_l[hh], ql, vo[hh][jp], so);
+            });
+          });
+          so += (r2 & 1) ? o6r : o2r;
+        });
+        W4_SB;
+      });
+    }
+    return;
+  }
   const long long c_col0 = c_col + (long long)blockIdx.y * p.c_split_stride;
   if (p.swiglu_bwd) {
     if constexpr (LA == 0 && LB == 1) {
@@ -682,6 +758,8 @@ bool w4_fits(const GemmParams &p) {
   }
   if (p.out_bf16 && !p.swiglu && p.resid_kind != 0) return false;
   if (p.swiglu_bwd && !(LA == 0 && LB == 1)) return false;
+  for (int g = 0; g < p.n_mg; ++g)
+    if (p.mg[g].rope && !(LA == 0 && LB == 0)) return false;
   if (p.ldc >= (1ll << 21) || p.ldr >= (1ll << 21)) return false;
   return true;
 }
