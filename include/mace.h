@@ -383,6 +383,11 @@ int mace_launch_plan(mace_handle_t h, mace_gemm_plan_t *out, int32_t max_entries
  * swiglu = 2 (layouts (0,1), kernel = 1 only): the backward form.  The product is dHm [M, N]; c_gu holds G | U of the
  * forward (bf16 [M, 2N], read only) and instead of dHm the call writes dG | dU as bf16 [M, 2N] into c (ldc = 2N):
  * dG = dHm U s (1 + G (1 - s)), dU = dHm G s, s = sigmoid(G).
+ * rope_cs != NULL (layouts (0,0), kernel = 1 only, N a multiple of 128): the rotary form of the QKV product.  The
+ * columns are heads of 128; rope_cs is a device fp32 table [M, 64, 2] of (cos, sin) per row and pair index.  Instead
+ * of C the call writes the product as two bf16 terms, c (first) and c_lo (second, nullable), both [M, N] with row
+ * stride N, after rotating every head (rope_rotate = 1: column i < 64 of a head becomes a cos - b sin and column i + 64
+ * becomes b cos + a sin, a and b being the two columns' products) or unrotated (rope_rotate = 0).
  * kernel = 0: the launcher picks tile and kernel from the sizes as it does inside the iteration; 1: the 256x256
  * four-wave kernel (MACE_BAD_SHAPE where the problem does not fit it).
  * Requirements: K a multiple of 64 for a k-contiguous operand; M (N) a multiple of 8 for an m- (n-) contiguous
@@ -396,6 +401,8 @@ typedef struct {
   void *c, *c_lo, *c_gu;
   const void *resid;
   int32_t out_bf16, resid_kind, swiglu, kernel;
+  const float *rope_cs;
+  int32_t rope_rotate;
 } mace_gemm_desc_t;
 int mace_gemm_bf16(mace_handle_t h, const mace_gemm_desc_t *d, void *stream);
 

@@ -77,7 +77,8 @@ class GemmDescT(C.Structure):
                 ("lda", C.c_int64), ("ldb", C.c_int64), ("ldc", C.c_int64), ("ldr", C.c_int64),
                 ("a", C.c_void_p), ("a_lo", C.c_void_p), ("b", C.c_void_p), ("b_up", C.c_void_p),
                 ("c", C.c_void_p), ("c_lo", C.c_void_p), ("c_gu", C.c_void_p), ("resid", C.c_void_p),
-                ("out_bf16", C.c_int32), ("resid_kind", C.c_int32), ("swiglu", C.c_int32), ("kernel", C.c_int32)]
+                ("out_bf16", C.c_int32), ("resid_kind", C.c_int32), ("swiglu", C.c_int32), ("kernel", C.c_int32),
+                ("rope_cs", C.c_void_p), ("rope_rotate", C.c_int32)]
 
 
 class ProfileEntryT(C.Structure):
@@ -200,7 +201,7 @@ def mace_launch_plan(h) -> list:
 
 
 def mace_gemm_bf16(h, layout_a: int, layout_b: int, M: int, N: int, K: int, a, b, c, a_lo=None, resid=None, b_up=None, c_lo=None,
-                   c_gu=None, lda=None, ldb=None, ldc=None, ldr=None, swiglu=False, kernel=0, stream=None):
+                   c_gu=None, lda=None, ldb=None, ldc=None, ldr=None, swiglu=False, kernel=0, rope_cs=None, rope_rotate=True, stream=None):
     """The dense contraction kernel on its own (argument marshalling only; see include/mace.h)."""
     d = GemmDescT()
     d.layout_a, d.layout_b, d.M, d.N, d.K = layout_a, layout_b, M, N, K
@@ -213,6 +214,7 @@ def mace_gemm_bf16(h, layout_a: int, layout_b: int, M: int, N: int, K: int, a, b
     d.out_bf16 = 1 if c.dtype == torch.bfloat16 else 0
     d.resid_kind = 0 if resid is None else (2 if resid.dtype == torch.bfloat16 else 1)
     d.swiglu, d.kernel = int(swiglu), int(kernel)
+    d.rope_cs, d.rope_rotate = _dev(rope_cs), int(bool(rope_rotate))
     _check(load().mace_gemm_bf16(h, C.byref(d), _stream(stream)), "mace_gemm_bf16")
 
 

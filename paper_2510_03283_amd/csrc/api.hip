@@ -587,6 +587,13 @@ int mace_gemm_bf16(mace_handle_t h, const mace_gemm_desc_t *d, void *stream) {
     p.swiglu = 1;
     gp_seg(p, (const bf16_t *)d->b_up, nullptr, d->N, 0);
   }
+  if (d->rope_cs) {
+    if (d->swiglu || d->kernel != 1 || d->resid) return fail(MACE_INVALID_ARG, "mace_gemm_bf16: the rotary form takes kernel = 1 and neither SwiGLU mode nor a residual");
+    p.out_bf16 = 0;
+    p.mg[0].rope = 1;
+    p.rope_cs = d->rope_cs;
+    p.ns[0].rope_hi = d->c; p.ns[0].rope_lo = d->c_lo; p.ns[0].rope_rot = d->rope_rotate ? 1 : 0;
+  }
   h->plan.clear();
   return run_gemm(h, d->layout_a, d->layout_b, p, (hipStream_t)stream, "mace_gemm_bf16");
 }

@@ -133,6 +133,34 @@ def test_swiglu_backward_form(torch_mod, handle):
         binding.mace_gemm_bf16(handle, 0, 1, M, F, K, dy, wd, dgu, c_gu=gu, ldc=2 * F, swiglu=2, kernel=0)
 
 
+@pytest.mark.parametrize("rotate", [True, False])
+def test_rotary_form(torch_mod, handle, rotate):
+    """The QKV product with the rotary embedding and the two-term split in its epilogue: heads of 128 columns, column
+    i < 64 of a head paired with column i + 64, angles from a per-row table; 2.5 heads wide tiles and 700 rows leave
+    partial tiles in both directions."""
+    torch = torch_mod
+    from paper_2510_03283_amd import binding
+    M, N, K = 700, 640, 4096
+    rng = np.random.default_rng(401 + rotate)
+    a, b, A, B = operands(torch, rng, 0, 0, M, N, K)
+    ang = rng.uniform(-3.0, 3.0, (M + 5, 64))
+    cs = torch.from_numpy(np.stack([np.cos(ang), np.sin(ang)], axis=-1).astype(np.float32)).cuda().contiguous()
+    P = (A @ B.T).reshape(M, N // 128, 2, 64)
+    if rotate:
+        c64, s64 = f64(cs)[:M, None, :, 0], f64(cs)[:M, None, :, 1]
+        ref = np.stack([P[:, :, 0] * c64 - P[:, :, 1] * s64, P[:, :, 1] * c64 + P[:, :, 0] * s64], axis=2).reshape(M, N)
+    else:
+        ref = P.reshape(M, N)
+    hi = out_buffer(torch, M + 5, N, torch.bfloat16)
+    lo = out_buffer(torch, M + 5, N, torch.bfloat16)
+    binding.mace_gemm_bf16(handle, 0, 0, M, N, K, a, b, hi, c_lo=lo, ldc=N, kernel=1, rope_cs=cs, rope_rotate=rotate)
+    torch.cuda.synchronize()
+    check_out(hi, ref, M, N, 4e-3, f"first term, rotate {rotate}")
+    assert np.all(f64(lo)[M:] == SENT)
+    two = f64(hi)[:M] + f64(lo)[:M]
+    assert np.abs(two - ref).max() / np.abs(ref).max() <= 5e-5, "two terms"
+
+
 def test_rejects_what_the_four_wave_kernel_cannot_do(torch_mod, handle):
     torch = torch_mod
     from paper_2510_03283_amd import binding
