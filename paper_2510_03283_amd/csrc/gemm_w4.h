@@ -337,17 +337,22 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const GemmParams p) {
           request(W4_IC(ph), X, src);
         }
       };
-      // k steps 0..2: one fragment of the next step behind each of the first eight MFMAs, one move behind
-      // each of the next six (16 moves over the three steps).  (One heavy instruction behind every MFMA - all
-      // ds_writes first, the requests behind them, the last eight in k step 3 - makes long reductions 1 - 2 %
-      // faster and the first k tiles of every output tile slower: 3 - 5 % slower over the whole step.)
+      // k steps 0..2: behind fourteen of the sixteen MFMAs either one fragment read of the next step or one move,
+      // the two kinds interleaved (r m r r m r - r m r m r m r m -; 16 moves over the three steps).  Measured
+      // against other orders on one box: all eight reads first and the six moves behind them (the first version)
+      // is 1 - 4 % slower on every shape, moves first 1 - 4 % slower still.  (One heavy instruction behind every
+      // MFMA - all ds_writes first, the requests behind them, the last eight in k step 3 - makes long reductions
+      // 1 - 2 % faster than the first version and the first k tiles of every output tile slower.)
       static_for<0, 3>([&](auto KK) W4_INL {
         constexpr int kk = decltype(KK)::value;
         static_for<0, 16>([&](auto Q) W4_INL {
           constexpr int q = decltype(Q)::value;
           mfma1(KK, Q);
-          if constexpr (q < 8) { read1(W4_IC(ph), W4_IC(kk + 1), W4_IC((kk + 1) & 1), Q); W4_SB; }
-          else if constexpr (q < 14 && kk * 6 + (q - 8) < 2 * NL) { W4_SB; move(W4_IC(kk * 6 + (q - 8))); W4_SB; }
+          // what follows MFMA q of a k step: fragment RD[q] of the next step, or move MV[q] of this step's six
+          constexpr int RD[16] = {0, -1, 1, 2, -1, 3, -1, 4, -1, 5, -1, 6, -1, 7, -1, -1};
+          constexpr int MV[16] = {-1, 0, -1, -1, 1, -1, -1, -1, 2, -1, 3, -1, 4, -1, 5, -1};
+          if constexpr (RD[q] >= 0) { read1(W4_IC(ph), W4_IC(kk + 1), W4_IC((kk + 1) & 1), W4_IC(RD[q])); W4_SB; }
+          if constexpr (MV[q] >= 0 && kk * 6 + MV[q] < 2 * NL) { W4_SB; move(W4_IC(kk * 6 + MV[q])); W4_SB; }
         });
       });
       mfma1(W4_IC(3), W4_IC(0)); W4_SB;
