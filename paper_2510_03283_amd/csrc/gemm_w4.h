@@ -339,10 +339,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const GemmParams p) {
       };
       // k steps 0..2: behind fourteen of the sixteen MFMAs either one fragment read of the next step or one move,
       // the two kinds interleaved (r m r r m r - r m r m r m r m -; 16 moves over the three steps).  Measured
-      // against other orders on one box: all eight reads first and the six moves behind them (the first version)
-      // is 1 - 4 % slower on every shape, moves first 1 - 4 % slower still.  (One heavy instruction behind every
-      // MFMA - all ds_writes first, the requests behind them, the last eight in k step 3 - makes long reductions
-      // 1 - 2 % faster than the first version and the first k tiles of every output tile slower.)
+      // against other orders on one box: all eight reads first and the six moves behind them is 1 - 4 % slower on
+      // every shape, moves first 1 - 4 % slower still.  (One heavy instruction behind every MFMA - all ds_writes
+      // first, the requests behind them, the last eight in k step 3 - is 1 - 2 % faster than reads-then-moves on
+      // long reductions and makes the first k tiles of every output tile slower.)
       static_for<0, 3>([&](auto KK) W4_INL {
         constexpr int kk = decltype(KK)::value;
         static_for<0, 16>([&](auto Q) W4_INL {
