@@ -161,6 +161,34 @@ def test_rotary_form(torch_mod, handle, rotate):
     assert np.abs(two - ref).max() / np.abs(ref).max() <= 5e-5, "two terms"
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shapes_on_the_four_wave_kernel(torch_mod, handle, seed):
+    """Seeded sweep of small ragged problems pinned to the four-wave kernel: one to 600 rows, 2 to 700 columns (not
+    multiples of the 32-wide accumulator blocks), one to twelve k tiles, the three layouts, both output types, either
+    residual type, padded leading dimensions."""
+    torch = torch_mod
+    from paper_2510_03283_amd import binding
+    rng = np.random.default_rng(7000 + seed)
+    la, lb = [(0, 0), (0, 1), (1, 1)][int(rng.integers(0, 3))]
+    M = int(rng.integers(1, 76)) * 8 if la == 1 else int(rng.integers(1, 601))
+    N = int(rng.integers(1, 88)) * 8 if lb == 1 else 2 * int(rng.integers(1, 351))
+    K = 64 * int(rng.integers(1, 13))
+    a, b, A, B = operands(torch, rng, la, lb, M, N, K)
+    ref = A @ B.T
+    bf16_out = bool(rng.integers(0, 2))
+    ldc = N + 2 * int(rng.integers(0, 9))
+    r = None
+    if not bf16_out and rng.integers(0, 2):
+        r = torch.from_numpy(rng.uniform(-20, 20, (M + 2, ldc + 6)).astype(np.float32)).cuda()
+        if rng.integers(0, 2):
+            r = r.to(torch.bfloat16)
+        ref = ref + f64(r)[:M, :N]
+    c = out_buffer(torch, M + 3, ldc, torch.bfloat16 if bf16_out else torch.float32)
+    binding.mace_gemm_bf16(handle, la, lb, M, N, K, a, b, c, resid=r, ldc=ldc, ldr=None if r is None else ldc + 6, kernel=1)
+    torch.cuda.synchronize()
+    check_out(c, ref, M, N, 4e-3 if bf16_out else 1e-5, f"seed {seed}: layouts {la}{lb}, {M}x{N}x{K}, bf16 out {bf16_out}, residual {None if r is None else r.dtype}")
+
+
 def test_rejects_what_the_four_wave_kernel_cannot_do(torch_mod, handle):
     torch = torch_mod
     from paper_2510_03283_amd import binding
